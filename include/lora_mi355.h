@@ -1,0 +1,192 @@
+/*
+ * liblora_mi355 - one serving step of a shared LLM backbone with many unmerged LoRA
+ * adapters, for AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * Problem statement followed (paper Sec. 1 and Sec. 2.2): adapters are kept unmerged over one
+ * shared backbone; a LoRA adapter is two low-rank matrices per targeted layer whose activations
+ * are added to the backbone layer's output, its size being its rank; requests of different
+ * adapters run inside the same batch; a request can run only while its adapter is in GPU memory;
+ * the GPU holds a fixed region of at most A_max adapters, each slot sized for the largest
+ * adapter (S_max), and adapters are swapped in from CPU memory.  Sec. 2.1: one step mixes
+ * prefill tokens with one-token decode requests (continuous batching).
+ *
+ * Per token t with adapter i = id[t], every targeted projection p computes
+ *
+ *     y[t,:] = x[t,:] W_p^T + s_i (x[t,:] A_{i,p}^T) B_{i,p}^T        (id[t] = -1: backbone only)
+ *
+ * with W_p [d_out,d_in], A_{i,p} [r_i,d_in], B_{i,p} [d_out,r_i], all row-major bf16, s_i fp32;
+ * products are accumulated in fp32 and y is rounded once to bf16 (nearest even).
+ *
+ * Conventions for every call
+ *   - returns a lora_status, never throws, never aborts the process;
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers are
+ *     ordinary process memory, "pinned host" is page-locked memory from hipHostMalloc;
+ *   - argument errors are detected on the host and reported before anything is enqueued;
+ *   - GPU work is enqueued on the stream handed in (a hipStream_t passed as void*; NULL = the
+ *     default stream); no hot call (lora_slots_load, lora_bucket, lora_layer_forward)
+ *     synchronises with the device or allocates memory;
+ *   - there is no CPU fallback: without a usable GPU the calls that enqueue work fail with
+ *     LORA_ERR_HIP.
+ */
+#ifndef LORA_MI355_H
+#define LORA_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lora_ctx lora_ctx; /* opaque */
+
+typedef enum {
+    LORA_OK = 0,
+    LORA_ERR_INVALID_ARG = 1,      /* null pointer, negative size, unknown mode, stale segment map */
+    LORA_ERR_SHAPE = 2,            /* unsupported projection shape or rank (see lora_create) */
+    LORA_ERR_OOM = 3,              /* the memory handed in is smaller than lora_slab_bytes() */
+    LORA_ERR_SLOT_RANGE = 4,       /* explicit slot index outside [0, n_slots) */
+    LORA_ERR_RANK_EXCEEDS_SMAX = 5,/* adapter rank larger than max_rank (S_max) */
+    LORA_ERR_SLOTS_EXHAUSTED = 6,  /* every slot is held by an adapter of the current batch */
+    LORA_ERR_NOT_RESIDENT = 7,     /* reported by lora_poll_device_flags: a token named a non-resident adapter */
+    LORA_ERR_HIP = 8,              /* a HIP runtime call failed (no device, bad stream, ...) */
+    LORA_ERR_ID_RANGE = 9          /* adapter id outside [0, max_adapter_id] */
+} lora_status;
+
+/* Segment-map modes (lora_bucket). */
+enum {
+    LORA_BUCKET_SORTED = 0, /* group tokens by slot with a stable sort: decode / mixed steps */
+    LORA_BUCKET_RUNS = 1    /* keep token order, segments = runs of equal slot: prefill, tokens contiguous per request */
+};
+
+/* Kernel-path override for lora_layer_forward (lora_config.path). */
+enum {
+    LORA_PATH_AUTO = 0,  /* chosen from T and the projection shape */
+    LORA_PATH_FUSED = 1, /* one GEMM pass over full K, LoRA expand inside its epilogue */
+    LORA_PATH_SPLITK = 2 /* K split over workgroups, fp32 partials, reduce + expand kernel */
+};
+
+/* Bits of the device flag word (lora_poll_device_flags). */
+enum { LORA_FLAG_NOT_RESIDENT = 1u };
+
+/* lora_config.flags */
+enum {
+    LORA_CREATE_HOST_ONLY = 1u /* slot-table bookkeeping only: no device memory, nothing enqueued
+                                  (lets a scheduler or simulator replay the adapter cache) */
+};
+
+typedef struct {
+    int32_t d_in;  /* multiple of 64 */
+    int32_t d_out; /* multiple of 8 */
+} lora_proj_shape;
+
+typedef struct {
+    int32_t n_slots;        /* A_max: adapters resident at once, 1 .. 4095 */
+    int32_t max_rank;       /* S_max: slot size in rank units, multiple of 8, 8 .. 64 */
+    int32_t n_proj;         /* targeted projections per layer, 1 .. 16 */
+    const lora_proj_shape *proj; /* host, n_proj entries, copied by lora_create */
+    int32_t max_tokens;     /* largest T of any step */
+    int32_t max_adapter_id; /* adapter ids are 0 .. max_adapter_id */
+    void *slab;             /* device memory owned by the caller, 256-byte aligned, lora_slab_bytes() long;
+                               holds the slot region and all scratch; must outlive the context */
+    size_t slab_bytes;
+    int32_t path;           /* LORA_PATH_* */
+    int32_t split_k;        /* 0 = automatic; otherwise the K split of the SPLITK path (1..16) */
+    uint32_t flags;         /* LORA_CREATE_* */
+} lora_config;
+
+/* One adapter to make resident.  A[p] / B[p]: pinned host, row-major bf16, A[p] is
+ * [rank, d_in_p], B[p] is [d_out_p, rank]; they must stay valid and unchanged until the copy
+ * stream has passed the call.  rank must be 0 or a multiple of 8 (<= max_rank); rank 0 needs no
+ * A/B.  slot: in, >= 0 = explicit slot, -1 = the library picks (an empty slot, else the least
+ * recently used one); out = slot used.  copied: out, 1 if weights were copied, 0 if the adapter
+ * was already resident (touch only). */
+typedef struct {
+    int32_t adapter_id;
+    int32_t rank;
+    float scale;            /* s_i = alpha / rank */
+    int32_t slot;
+    int32_t copied;
+    const void *const *A;
+    const void *const *B;
+} lora_adapter_desc;
+
+/* Result of lora_bucket.  The arrays are device memory owned by the context and stay valid
+ * until the next lora_bucket on it.  perm[T]: token index at each grouped position;
+ * seg_start[n_seg+1], seg_slot[n_seg]: segment g covers grouped positions
+ * [seg_start[g], seg_start[g+1]) and uses slot seg_slot[g] (-1 = backbone only);
+ * n_seg: one int32.  Entries past n_seg are unspecified. */
+typedef struct {
+    const int32_t *perm;
+    const int32_t *seg_start;
+    const int32_t *seg_slot;
+    const int32_t *n_seg;
+    int32_t T;
+    int32_t mode;
+    uint64_t epoch; /* identifies the lora_bucket call that produced this map */
+} lora_segments;
+
+/* Device bytes the context needs for `cfg` (slot region + scratch); 0 if cfg is invalid.
+ * Slot region = n_slots * max_rank * sum_p (d_in_p + d_out_p) * 2 bytes: every slot has the
+ * uniform S_max footprint, but kernels only ever read an adapter's own rank rows. */
+size_t lora_slab_bytes(const lora_config *cfg);
+
+/* Creates a context on the current device.  cfg->slab must hold lora_slab_bytes(cfg) bytes
+ * (LORA_ERR_OOM otherwise).  All slots start empty.  Errors: INVALID_ARG, SHAPE, OOM, HIP. */
+lora_status lora_create(const lora_config *cfg, lora_ctx **out);
+
+/* Waits for the context's own events, releases host resources.  The slab stays the caller's. */
+lora_status lora_destroy(lora_ctx *ctx);
+
+/* Makes n adapters resident (paper Sec. 2.2 / Sec. 5.2.2: adapters are loaded from CPU memory
+ * into the GPU's adapter region; load time grows with adapter size, unloading is free).
+ * in_use / n_in_use (host): adapter ids of the batch about to run; they are marked used now and
+ * are never chosen as victims.  The whole call is planned on the host first: on any error
+ * nothing is enqueued and the table is unchanged.  On success the copies (one per matrix),
+ * the slot metadata update and the id->slot map update are enqueued on copy_stream; later
+ * lora_bucket / lora_layer_forward calls on other streams wait for them through events, and
+ * the copies themselves wait for forward work already enqueued (a slot is never overwritten
+ * while an earlier step may still read it).
+ * Errors: INVALID_ARG, ID_RANGE, SLOT_RANGE, RANK_EXCEEDS_SMAX, SHAPE (rank not a multiple of
+ * 8), SLOTS_EXHAUSTED, HIP. */
+lora_status lora_slots_load(lora_ctx *ctx, int32_t n, lora_adapter_desc *descs,
+                            const int32_t *in_use, int32_t n_in_use, void *copy_stream);
+
+/* Builds the token->adapter segment map for one step (shared by all projections and layers
+ * of the step).  d_token_adapter: device, int32[T], adapter id per token or -1.  Integer work
+ * only; the result is unique: SORTED = stable ascending sort of token indices by slot (slot -1
+ * first) + run-length encoding; RUNS = identity order + run-length encoding.  A token whose
+ * adapter id is out of range or not resident sets LORA_FLAG_NOT_RESIDENT in the device flag
+ * word and is treated as -1.  T = 0 is valid (n_seg = 0).
+ * Errors: INVALID_ARG (T < 0, T > max_tokens, bad mode, null pointers), HIP. */
+lora_status lora_bucket(lora_ctx *ctx, const int32_t *d_token_adapter, int32_t T, int32_t mode,
+                        lora_segments *out, void *stream);
+
+/* One projection of the step: d_out[t,:] = bf16(x[t,:] W^T + s (x[t,:] A^T) B^T) for every token,
+ * in original token order.  d_x: device bf16 [T, d_in_p]; d_W: device bf16 [d_out_p, d_in_p];
+ * d_out: device bf16 [T, d_out_p]; all row-major, 16-byte aligned, not aliased.  seg must be
+ * the map of the latest lora_bucket on this context, and the call must be ordered after that
+ * lora_bucket (same stream, or an event).  T = 0 is a no-op.
+ * Errors: INVALID_ARG (proj out of range, stale seg, null or misaligned pointers), HIP. */
+lora_status lora_layer_forward(lora_ctx *ctx, int32_t proj, const void *d_x, const void *d_W,
+                               const lora_segments *seg, void *d_out, void *stream);
+
+/* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
+ * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set, else LORA_OK; *flags (may be NULL)
+ * receives the raw word. */
+lora_status lora_poll_device_flags(lora_ctx *ctx, uint32_t *flags, void *stream);
+
+/* Slot-table queries (host state, no device access). */
+int32_t lora_slot_of(const lora_ctx *ctx, int32_t adapter_id);      /* slot or -1 */
+int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter id or -1 */
+
+/* Kernel launches made by the most recent lora_layer_forward on this context: fills up to `cap`
+ * entries of names[] (static strings) and returns the count.  For benchmarks and profiling. */
+int32_t lora_last_launches(const lora_ctx *ctx, const char **names, int32_t cap);
+
+const char *lora_status_string(lora_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_MI355_H */
