@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of one multi-adapter LoRA layer-step on one MI355X.
+
+A step = lora_bucket + lora_layer_forward for each of the seven projections of one decoder layer
+(q, k, v, o, gate, up, down), on synthetic inputs already resident in HBM.  The default workload is
+the 8B-shape decode step: 256 one-token requests, 32 resident adapters of ranks {8,16,32}, adapter
+ids Zipf(1.0).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def kernel_algorithmic_bytes(w, kernel: str) -> float:
+    """Bytes one layer-step's launches of `kernel` must move (all seven projections): each array
+    counted once, in the kernel that has to touch it; split-K partials and re-reads are not counted."""
+    used = w.distinct_adapters()
+    rank_sum = sum(w.adapters[a].rank for a in used)
+    T = w.T
+    tot = 0.0
+    for (d_in, d_out) in w.proj:
+        if kernel.startswith("gemm_splitk"):
+            tot += 2.0 * d_in * d_out + 2.0 * T * d_in
+        elif kernel.startswith("gemm_fused"):
+            tot += 2.0 * d_in * d_out + 2.0 * T * d_in + 2.0 * T * d_out + 2.0 * rank_sum * d_out
+        elif kernel == "reduce_expand":
+            tot += 2.0 * T * d_out + 2.0 * rank_sum * d_out
+        elif kernel == "shrink":
+            tot += 2.0 * rank_sum * d_in
+    return tot
+
+
+def kernel_flops(w, kernel: str) -> float:
+    T = w.T
+    if kernel.startswith("gemm"):
+        return float(sum(2.0 * T * d_in * d_out for (d_in, d_out) in w.proj))
+    return 0.0
+
+
+def cpu_baseline(w, budget_s: float = 15.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: the first n tokens of
+    the step through all seven projections."""
+    import numpy as np
+    import oracle
+    n = 1
+    t_used = 0.0
+    done = 0
+    while done < w.T and t_used < budget_s:
+        take = min(n, w.T - done)
+        sl = slice(done, done + take)
+        t0 = time.perf_counter()
+        oracle.bucket(w.token_ids[sl], np.arange(w.max_adapter_id + 1, dtype=np.int32), w.mode)
+        for p in range(len(w.proj)):
+            oracle.project(w.x[p][sl], w.W[p], w.token_ids[sl], oracle.adapters_of(w, p))
+        t_used += time.perf_counter() - t0
+        done += take
+        n *= 2
+    return {"value": done / t_used, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {done} of {w.T} tokens of the step, all 7 projections, fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 2 (8B decode, the headline), 3, 4 or 5")
+    ap.add_argument("--copies", type=int, default=4, help="distinct weight/slot copies rotated through")
+    ap.add_argument("--shrink", type=int, default=1, help="divide the model dimensions (debugging only)")
+    ap.add_argument("--path", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; the path shards by adapter with no exchange, "
+              "so --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_24044_amd import binding as B
+    from paper_2602_24044_amd import workloads as wl
+    from paper_2602_24044_amd.runtime import Session
+
+    kw = {"shrink": args.shrink} if args.shrink != 1 else {}
+    w = wl.by_index(args.config, **kw)
+    names = {2: "8B-shape decode, 256 requests x 1 token, 32 adapters ranks {8,16,32}, Zipf(1.0) ids",
+             3: "8B-shape prefill, 32 requests lognormal lengths, 64 adapters rank 16",
+             4: "8B-shape many-adapter decode, 512 tokens uniform over 384 adapters ranks {8,16,32,64}",
+             5: "70B-shape mixed step, 2048-token prefill chunk + 384 decode tokens, 128 slots"}
+
+    copies = max(1, args.copies)
+    sessions = []
+    for _ in range(copies):
+        s = Session(w, path=args.path)
+        s.load(w.resident)
+        if w.missing:
+            s.load(w.missing, in_use=w.distinct_adapters())
+        sessions.append(s)
+    torch.cuda.synchronize()
+
+    def run(n):
+        for i in range(n):
+            sessions[i % copies].step()
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = w.T * args.steps / dt
+
+    # second pass of the same steps with every kernel bracketed by HIP events on its stream
+    for s in sessions:
+        B.lora_profile_reset(s.ctx)
+        B.lora_profile_enable(s.ctx, True)
+    done = 0
+    while done < args.steps:
+        n = min(args.steps - done, 64 * copies)
+        run(n)
+        torch.cuda.synchronize()
+        done += n
+        for s in sessions:
+            B.lora_profile_collect(s.ctx)      # drains the event pool into the context's running totals
+    prof = {}
+    for s in sessions:
+        for k, (ms, cnt) in B.lora_profile_collect(s.ctx).items():
+            a, b = prof.get(k, (0.0, 0))
+            prof[k] = (a + ms, b + cnt)
+        B.lora_profile_enable(s.ctx, False)
+    kernels = {k: {"avg_us": ms / cnt * 1e3, "launches_per_step": cnt / args.steps,
+                   "us_per_step": ms / args.steps * 1e3} for k, (ms, cnt) in prof.items() if cnt}
+    dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    dom_t = kernels[dominant]["us_per_step"] * 1e-6
+    dom_bytes = kernel_algorithmic_bytes(w, dominant)
+    dom_flops = kernel_flops(w, dominant)
+    achieved_gbs = dom_bytes / dom_t / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                "launch_avg_us": kernels[dominant]["avg_us"],
+                "mfma_tflops": dom_flops / dom_t / 1e12, "mfma_frac": dom_flops / dom_t / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    if args.config in (3, 5):
+        tf = dom_flops / dom_t / 1e12
+        roofline.update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / MFMA_BF16_PEAK_TFLOPS, "hbm_gbs": achieved_gbs})
+
+    step_bytes = wl.algorithmic_bytes(w)
+    out = {
+        "metric": "LoRA-layer tokens/s at 8B-shape decode B=256; % MFMA peak & HBM GB/s",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": names.get(args.config, w.name), "name": w.name, "tokens": w.T,
+                   "projections": len(w.proj), "distinct_adapters": len(w.distinct_adapters()),
+                   "weight_copies_rotated": copies, "path": args.path},
+        "layer_step": {"algorithmic_bytes": step_bytes, "hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "flops": wl.algorithmic_flops(w),
+                       "tflops": wl.algorithmic_flops(w) / (ms_per_step * 1e-3) / 1e12},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    for s in sessions:
+        s.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

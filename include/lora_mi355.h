@@ -184,6 +184,15 @@ int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter i
  * entries of names[] (static strings) and returns the count.  For benchmarks and profiling. */
 int32_t lora_last_launches(const lora_ctx *ctx, const char **names, int32_t cap);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the context launches is
+ * bracketed by a pair of HIP timing events on its own stream.  lora_profile_collect waits for the
+ * recorded events, adds them to running totals per kernel name and returns the number of distinct
+ * names; up to `cap` entries of names[] (valid until lora_profile_reset or lora_destroy),
+ * total_ms[] and counts[] are filled.  At most 8192 launches are recorded between two collects. */
+lora_status lora_profile_enable(lora_ctx *ctx, int32_t on);
+int32_t lora_profile_collect(lora_ctx *ctx, const char **names, double *total_ms, int64_t *counts, int32_t cap);
+lora_status lora_profile_reset(lora_ctx *ctx);
+
 const char *lora_status_string(lora_status s);
 
 #ifdef __cplusplus

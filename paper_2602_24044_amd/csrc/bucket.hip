@@ -1,0 +1,195 @@
+// Token -> adapter segment map (integer only) and the small slot-metadata kernels.
+//
+// A serving step batches requests of different adapters together (paper Sec. 2.2) and mixes
+// prefill chunks with one-token decode requests (Sec. 2.1).  The map groups the tokens of a step
+// by the slot their adapter occupies so that each adapter's A and B are streamed once per step.
+// SORTED: stable counting sort of token indices by slot; RUNS: token order kept, runs of equal
+// slot.  One 1024-thread workgroup: LDS histogram, LDS prefix scan, wavefront ballots for the
+// stable rank of a token among equal keys.
+#include "lora_internal.hpp"
+
+namespace lora {
+namespace {
+
+constexpr int kBT = 1024;
+constexpr int kNW = kBT / kWave;
+constexpr int kMaxKeys = kMaxSlots + 1;
+
+__device__ inline int wave_incl_scan(int v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive prefix of one int per thread over the workgroup; *total = sum over all threads.
+__device__ inline int block_excl_scan(int v, int* s_wave, int* total)
+{
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int inc = wave_incl_scan(v, lane);
+    if (lane == kWave - 1) s_wave[w] = inc;
+    __syncthreads();
+    if (w == 0) {
+        int t = lane < kNW ? s_wave[lane] : 0;
+        int ti = wave_incl_scan(t, lane);
+        if (lane < kNW) s_wave[lane] = ti - t;
+        if (lane == kNW - 1) s_wave[kNW] = ti;
+    }
+    __syncthreads();
+    const int res = s_wave[w] + inc - v;
+    *total = s_wave[kNW];
+    __syncthreads();
+    return res;
+}
+
+// Run-length encoding of row_slot[0..T); with align > 0 a run also ends at every multiple of align.
+__device__ void rle(const int32_t* row_slot, int T, int align, int32_t* out_start, int32_t* out_slot,
+                    int32_t* out_n, int* s_wave)
+{
+    int running = 0;
+    for (int c = 0; c < T; c += kBT) {
+        const int m = c + (int)threadIdx.x;
+        int head = 0, s = 0;
+        if (m < T) {
+            s = row_slot[m];
+            head = (m == 0) || (align > 0 && (m % align) == 0) || (row_slot[m - 1] != s);
+        }
+        int total;
+        const int ex = block_excl_scan(head, s_wave, &total);
+        if (head) {
+            out_start[running + ex] = m;
+            out_slot[running + ex] = s;
+        }
+        running += total;
+    }
+    if (threadIdx.x == 0) {
+        out_start[running] = T;
+        *out_n = running;
+    }
+}
+
+__global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
+{
+    __shared__ int s_run[kMaxKeys];      // histogram, then running output offset per key
+    __shared__ int s_wave[kNW + 1];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int T = a.T;
+    const int nkeys = a.n_slots + 1;     // key = slot + 1, key 0 = backbone only
+    const bool sorted = (a.mode == 0);
+
+    for (int k = tid; k < nkeys; k += kBT) s_run[k] = 0;
+    __syncthreads();
+
+    // keys, histogram, residency check
+    bool bad = false;
+    for (int t = tid; t < T; t += kBT) {
+        const int id = a.ids[t];
+        int key = 0;
+        if (id >= 0) {
+            int s = -1;
+            if (id < a.n_ids) s = a.id2slot[id];
+            if (s >= 0 && s < a.n_slots) key = s + 1; else bad = true;
+        }
+        if (sorted) {
+            a.tok_key[t] = key;
+            atomicAdd(&s_run[key], 1);
+        } else {
+            a.perm[t] = t;
+            a.row_slot[t] = key - 1;
+        }
+    }
+    if (bad) atomicOr(a.flags, 1u);
+    __syncthreads();
+
+    if (sorted) {
+        // exclusive scan of the histogram: s_run[key] becomes the first grouped position of key
+        int carry = 0;
+        for (int k0 = 0; k0 < nkeys; k0 += kBT) {
+            const int k = k0 + tid;
+            const int c = (k < nkeys) ? s_run[k] : 0;
+            int total;
+            const int ex = block_excl_scan(c, s_wave, &total);
+            if (k < nkeys) s_run[k] = carry + ex;
+            carry += total;
+        }
+        __syncthreads();
+
+        // stable scatter: tokens are taken 1024 at a time in index order, wave after wave
+        const int nbits = 32 - __clz(a.n_slots);
+        for (int c = 0; c < T; c += kBT) {
+            const int t = c + tid;
+            const bool valid = t < T;
+            const int key = valid ? a.tok_key[t] : 0;
+            unsigned long long peers = __ballot(valid);
+            for (int b = 0; b < nbits; ++b) {
+                const bool bit = (key >> b) & 1;
+                const unsigned long long mb = __ballot(valid && bit);
+                peers &= bit ? mb : ~mb;
+            }
+            const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+            const int cw = __popcll(peers);
+            const int rem = T - c;
+            const int nw = rem >= kBT ? kNW : (rem + kWave - 1) / kWave;
+            for (int w = 0; w < nw; ++w) {
+                if (wave == w && valid) {
+                    const int pos = s_run[key] + rank;
+                    a.perm[pos] = t;
+                    a.row_slot[pos] = key - 1;
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (wave == w && valid && rank == cw - 1) s_run[key] += cw;
+                __syncthreads();
+            }
+        }
+    }
+    __syncthreads();
+
+    rle(a.row_slot, T, 0, a.seg_start, a.seg_slot, a.n_seg, s_wave);
+    rle(a.row_slot, T, kPieceRows, a.piece_start, a.piece_slot, a.n_pieces, s_wave);
+}
+
+__global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    for (int i = 0; i < u.n; ++i) {
+        if (u.evicted[i] >= 0) id2slot[u.evicted[i]] = -1;
+        slot_rank[u.slot[i]] = u.rank[i];
+        slot_scale[u.slot[i]] = u.scale[i];
+        if (u.adapter[i] >= 0) id2slot[u.adapter[i]] = u.slot[i];
+    }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int32_t value, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = value;
+}
+
+}  // namespace
+
+hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(kBT), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot,
+                              hipStream_t stream)
+{
+    hipLaunchKernelGGL(meta_update_kernel, dim3(1), dim3(kWave), 0, stream, u, slot_rank, slot_scale, id2slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, value, n);
+    return hipGetLastError();
+}
+
+}  // namespace lora

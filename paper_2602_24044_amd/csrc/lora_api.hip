@@ -1,0 +1,688 @@
+// Host side of liblora_mi355: context, slot table with least-recently-used replacement, and the
+// launch sequences behind lora_slots_load / lora_bucket / lora_layer_forward.
+#include "../../include/lora_mi355.h"
+#include "lora_internal.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace lora;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    size_t slot_stride_elems = 0;          // bf16 elements per slot
+    size_t a_off[kMaxProj] = {0};          // element offsets inside a slot
+    size_t b_off[kMaxProj] = {0};
+    size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
+    size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
+           off_piece_slot = 0, off_tok_key = 0, off_vpart = 0, off_part = 0;
+    size_t vpart_elems = 0, part_elems = 0;
+    size_t total = 0;
+};
+
+int auto_split_cap(int N)
+{
+    const int tiles_n = (N + 127) / 128;
+    int s = (256 + tiles_n - 1) / tiles_n;
+    return std::max(1, std::min(16, s));
+}
+
+bool valid_config(const lora_config* c)
+{
+    if (!c || !c->proj) return false;
+    if (c->n_slots < 1 || c->n_slots > kMaxSlots) return false;
+    if (c->max_rank < 8 || c->max_rank > kMaxRank || c->max_rank % 8) return false;
+    if (c->n_proj < 1 || c->n_proj > kMaxProj) return false;
+    if (c->max_tokens < 1 || c->max_adapter_id < 0) return false;
+    if (c->path < LORA_PATH_AUTO || c->path > LORA_PATH_SPLITK) return false;
+    if (c->split_k < 0 || c->split_k > 16) return false;
+    for (int p = 0; p < c->n_proj; ++p) {
+        if (c->proj[p].d_in < 64 || c->proj[p].d_in % 64) return false;
+        if (c->proj[p].d_out < 8 || c->proj[p].d_out % 8) return false;
+    }
+    return true;
+}
+
+Layout make_layout(const lora_config* c)
+{
+    Layout L;
+    size_t e = 0;
+    int k_max = 0;
+    for (int p = 0; p < c->n_proj; ++p) {
+        L.a_off[p] = e;
+        e += (size_t)c->max_rank * c->proj[p].d_in;
+        L.b_off[p] = e;
+        e += (size_t)c->max_rank * c->proj[p].d_out;
+        k_max = std::max(k_max, c->proj[p].d_in);
+    }
+    L.slot_stride_elems = align_up(e * 2, kAlign) / 2;
+    const size_t Tm = (size_t)c->max_tokens;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, kAlign); return at; };
+    L.off_slots = take(L.slot_stride_elems * 2 * (size_t)c->n_slots);
+    L.off_slot_rank = take(4 * (size_t)c->n_slots);
+    L.off_slot_scale = take(4 * (size_t)c->n_slots);
+    L.off_id2slot = take(4 * ((size_t)c->max_adapter_id + 1));
+    L.off_header = take(256);
+    L.off_perm = take(4 * Tm);
+    L.off_row_slot = take(4 * Tm);
+    L.off_seg_start = take(4 * (Tm + 1));
+    L.off_seg_slot = take(4 * Tm);
+    const size_t max_pieces = Tm + Tm / kPieceRows + 2;
+    L.off_piece_start = take(4 * (max_pieces + 1));
+    L.off_piece_slot = take(4 * max_pieces);
+    L.off_tok_key = take(4 * Tm);
+    const size_t Ts = std::min<size_t>(Tm, kSplitMaxTokens);
+    const size_t kc_max = std::min<size_t>(kMaxShrinkChunks, ((size_t)k_max + kShrinkKC - 1) / kShrinkKC);
+    L.vpart_elems = std::max(Tm * (size_t)c->max_rank, Ts * (size_t)c->max_rank * kc_max);
+    L.off_vpart = take(4 * L.vpart_elems);
+    size_t part_cols = 0;
+    for (int p = 0; p < c->n_proj; ++p) {
+        const int s = c->split_k > 0 ? c->split_k : auto_split_cap(c->proj[p].d_out);
+        part_cols = std::max(part_cols, (size_t)c->proj[p].d_out * (size_t)s);
+    }
+    L.part_elems = align_up(Ts, 256) * part_cols;
+    L.off_part = take(4 * L.part_elems);
+    L.total = o;
+    return L;
+}
+
+struct ProfileSlot {
+    hipEvent_t beg, end;
+    const char* name;
+};
+
+}  // namespace
+
+struct lora_ctx {
+    lora_config cfg;
+    std::vector<lora_proj_shape> proj;
+    Layout L;
+    bool host_only = false;
+    char* base = nullptr;
+
+    // host slot table
+    std::vector<int32_t> slot_adapter, slot_rank_h;
+    std::vector<float> slot_scale_h;
+    std::vector<uint64_t> slot_last_used;
+    std::vector<int32_t> id2slot_h;
+    uint64_t tick = 0;
+    int n_resident = 0;
+
+    // stream ordering
+    hipEvent_t ev_meta = nullptr, ev_fwd = nullptr;
+    hipEvent_t ev_proj[kMaxProj] = {nullptr};
+    bool meta_pending = false;
+    bool proj_pending[kMaxProj] = {false};
+    hipStream_t copy_stream = nullptr;      // stream of the latest load
+    hipStream_t last_fwd_stream = nullptr;
+    bool have_fwd = false;
+
+    // current segment map
+    uint64_t epoch = 0;
+    int32_t seg_T = -1, seg_mode = 0;
+
+    // launch log / profiling
+    std::vector<const char*> last_launches;
+    bool profiling = false;
+    std::vector<ProfileSlot> prof_pool;
+    size_t prof_used = 0;
+    std::vector<std::string> prof_names;
+    std::vector<double> prof_ms;
+    std::vector<int64_t> prof_count;
+
+    template <typename Tp> Tp* dev(size_t off) const { return reinterpret_cast<Tp*>(base + off); }
+    int32_t* d_slot_rank() const { return dev<int32_t>(L.off_slot_rank); }
+    float* d_slot_scale() const { return dev<float>(L.off_slot_scale); }
+    int32_t* d_id2slot() const { return dev<int32_t>(L.off_id2slot); }
+    uint32_t* d_flags() const { return dev<uint32_t>(L.off_header); }
+    int32_t* d_n_seg() const { return dev<int32_t>(L.off_header) + 1; }
+    int32_t* d_n_pieces() const { return dev<int32_t>(L.off_header) + 2; }
+
+    DeviceView view(int32_t T) const
+    {
+        DeviceView v;
+        v.slots = dev<uint16_t>(L.off_slots);
+        v.slot_stride = L.slot_stride_elems;
+        v.slot_rank = d_slot_rank();
+        v.slot_scale = d_slot_scale();
+        v.perm = dev<int32_t>(L.off_perm);
+        v.row_slot = dev<int32_t>(L.off_row_slot);
+        v.piece_start = dev<int32_t>(L.off_piece_start);
+        v.piece_slot = dev<int32_t>(L.off_piece_slot);
+        v.n_pieces = d_n_pieces();
+        v.T = T;
+        v.max_rank = cfg.max_rank;
+        return v;
+    }
+};
+
+namespace {
+
+// Brackets one kernel launch with timing events while profiling is on.
+struct LaunchScope {
+    lora_ctx* c;
+    hipStream_t s;
+    ProfileSlot* slot = nullptr;
+    LaunchScope(lora_ctx* ctx, hipStream_t stream, const char* name) : c(ctx), s(stream)
+    {
+        c->last_launches.push_back(name);
+        if (c->profiling && c->prof_used < c->prof_pool.size()) {
+            slot = &c->prof_pool[c->prof_used++];
+            slot->name = name;
+            (void)hipEventRecord(slot->beg, s);
+        }
+    }
+    void rename(const char* name)
+    {
+        c->last_launches.back() = name;
+        if (slot) slot->name = name;
+    }
+    ~LaunchScope()
+    {
+        if (slot) (void)hipEventRecord(slot->end, s);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* lora_status_string(lora_status s)
+{
+    switch (s) {
+        case LORA_OK: return "ok";
+        case LORA_ERR_INVALID_ARG: return "invalid argument";
+        case LORA_ERR_SHAPE: return "unsupported shape or rank";
+        case LORA_ERR_OOM: return "slab too small";
+        case LORA_ERR_SLOT_RANGE: return "slot index out of range";
+        case LORA_ERR_RANK_EXCEEDS_SMAX: return "adapter rank exceeds max_rank";
+        case LORA_ERR_SLOTS_EXHAUSTED: return "no evictable slot";
+        case LORA_ERR_NOT_RESIDENT: return "token names a non-resident adapter";
+        case LORA_ERR_HIP: return "HIP runtime error";
+        case LORA_ERR_ID_RANGE: return "adapter id out of range";
+    }
+    return "unknown status";
+}
+
+size_t lora_slab_bytes(const lora_config* cfg)
+{
+    if (!valid_config(cfg)) return 0;
+    if (cfg->flags & LORA_CREATE_HOST_ONLY) return 0;
+    return make_layout(cfg).total;
+}
+
+lora_status lora_create(const lora_config* cfg, lora_ctx** out)
+{
+    if (!out) return LORA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg || !cfg->proj) return LORA_ERR_INVALID_ARG;
+    if (!valid_config(cfg)) {
+        if (cfg->n_proj >= 1 && cfg->n_proj <= kMaxProj && cfg->n_slots >= 1 && cfg->max_tokens >= 1 &&
+            cfg->max_adapter_id >= 0)
+            return LORA_ERR_SHAPE;
+        return LORA_ERR_INVALID_ARG;
+    }
+    lora_ctx* c = new (std::nothrow) lora_ctx();
+    if (!c) return LORA_ERR_OOM;
+    c->cfg = *cfg;
+    c->proj.assign(cfg->proj, cfg->proj + cfg->n_proj);
+    c->cfg.proj = c->proj.data();
+    c->L = make_layout(&c->cfg);
+    c->host_only = (cfg->flags & LORA_CREATE_HOST_ONLY) != 0;
+    c->slot_adapter.assign(cfg->n_slots, -1);
+    c->slot_rank_h.assign(cfg->n_slots, 0);
+    c->slot_scale_h.assign(cfg->n_slots, 0.f);
+    c->slot_last_used.assign(cfg->n_slots, 0);
+    c->id2slot_h.assign((size_t)cfg->max_adapter_id + 1, -1);
+
+    if (!c->host_only) {
+        if (!cfg->slab || (reinterpret_cast<uintptr_t>(cfg->slab) % kAlign) != 0) {
+            delete c;
+            return LORA_ERR_INVALID_ARG;
+        }
+        if (cfg->slab_bytes < c->L.total) {
+            delete c;
+            return LORA_ERR_OOM;
+        }
+        c->base = static_cast<char*>(cfg->slab);
+        bool ok = hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming) == hipSuccess;
+        for (int p = 0; ok && p < cfg->n_proj; ++p)
+            ok = hipEventCreateWithFlags(&c->ev_proj[p], hipEventDisableTiming) == hipSuccess;
+        ok = ok && launch_fill_i32(c->d_slot_rank(), 0, cfg->n_slots, nullptr) == hipSuccess;
+        ok = ok && launch_fill_i32(reinterpret_cast<int32_t*>(c->d_slot_scale()), 0, cfg->n_slots, nullptr) == hipSuccess;
+        ok = ok && launch_fill_i32(c->d_id2slot(), -1, (size_t)cfg->max_adapter_id + 1, nullptr) == hipSuccess;
+        ok = ok && launch_fill_i32(c->dev<int32_t>(c->L.off_header), 0, 64, nullptr) == hipSuccess;
+        ok = ok && launch_fill_i32(c->dev<int32_t>(c->L.off_piece_start), 0, 1, nullptr) == hipSuccess;
+        ok = ok && hipDeviceSynchronize() == hipSuccess;
+        if (!ok) {
+            (void)hipGetLastError();
+            lora_destroy(c);
+            return LORA_ERR_HIP;
+        }
+    }
+    *out = c;
+    return LORA_OK;
+}
+
+lora_status lora_destroy(lora_ctx* c)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    if (!c->host_only) {
+        (void)hipDeviceSynchronize();
+        if (c->ev_meta) (void)hipEventDestroy(c->ev_meta);
+        if (c->ev_fwd) (void)hipEventDestroy(c->ev_fwd);
+        for (int p = 0; p < kMaxProj; ++p)
+            if (c->ev_proj[p]) (void)hipEventDestroy(c->ev_proj[p]);
+        for (auto& s : c->prof_pool) {
+            (void)hipEventDestroy(s.beg);
+            (void)hipEventDestroy(s.end);
+        }
+    }
+    delete c;
+    return LORA_OK;
+}
+
+int32_t lora_slot_of(const lora_ctx* c, int32_t adapter_id)
+{
+    if (!c || adapter_id < 0 || adapter_id > c->cfg.max_adapter_id) return -1;
+    return c->id2slot_h[adapter_id];
+}
+
+int32_t lora_slot_adapter(const lora_ctx* c, int32_t slot)
+{
+    if (!c || slot < 0 || slot >= c->cfg.n_slots) return -1;
+    return c->slot_adapter[slot];
+}
+
+lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, const int32_t* in_use,
+                            int32_t n_in_use, void* copy_stream_v)
+{
+    if (!c || n < 0 || n_in_use < 0 || (n > 0 && !descs) || (n_in_use > 0 && !in_use)) return LORA_ERR_INVALID_ARG;
+    const int n_slots = c->cfg.n_slots, n_proj = c->cfg.n_proj;
+    const int32_t max_id = c->cfg.max_adapter_id;
+
+    // ---- validate ----
+    for (int i = 0; i < n_in_use; ++i)
+        if (in_use[i] < 0 || in_use[i] > max_id) return LORA_ERR_ID_RANGE;
+    for (int i = 0; i < n; ++i) {
+        const lora_adapter_desc& d = descs[i];
+        if (d.adapter_id < 0 || d.adapter_id > max_id) return LORA_ERR_ID_RANGE;
+        if (d.rank < 0) return LORA_ERR_INVALID_ARG;
+        if (d.rank > c->cfg.max_rank) return LORA_ERR_RANK_EXCEEDS_SMAX;
+        if (d.rank % 8) return LORA_ERR_SHAPE;
+        if (d.slot < -1 || d.slot >= n_slots) return LORA_ERR_SLOT_RANGE;
+        if (d.rank > 0 && !c->host_only) {
+            if (!d.A || !d.B) return LORA_ERR_INVALID_ARG;
+            for (int p = 0; p < n_proj; ++p)
+                if (!d.A[p] || !d.B[p]) return LORA_ERR_INVALID_ARG;
+        }
+    }
+
+    // ---- plan on a copy of the table ----
+    std::vector<int32_t> adapter = c->slot_adapter, rank = c->slot_rank_h, id2slot = c->id2slot_h;
+    std::vector<float> scale = c->slot_scale_h;
+    std::vector<uint64_t> last_used = c->slot_last_used;
+    const uint64_t tick = c->tick + 1;
+    std::vector<char> is_protected((size_t)max_id + 1, 0), placed_now(n_slots, 0);
+    for (int i = 0; i < n_in_use; ++i) {
+        is_protected[in_use[i]] = 1;
+        const int s = id2slot[in_use[i]];
+        if (s >= 0) last_used[s] = tick;
+    }
+    struct Step { int slot, adapter, evicted, rank; float scale; bool copied; };
+    std::vector<Step> steps;
+    steps.reserve(n);
+    std::vector<int> out_slot(n), out_copied(n);
+    for (int i = 0; i < n; ++i) {
+        const lora_adapter_desc& d = descs[i];
+        const int cur = id2slot[d.adapter_id];
+        if (cur >= 0 && (d.slot < 0 || d.slot == cur)) {
+            last_used[cur] = tick;
+            placed_now[cur] = 1;
+            out_slot[i] = cur;
+            out_copied[i] = 0;
+            continue;
+        }
+        int s = d.slot;
+        if (s < 0) {
+            for (int k = 0; k < n_slots && s < 0; ++k)
+                if (adapter[k] < 0) s = k;
+            if (s < 0) {
+                uint64_t best = 0;
+                for (int k = 0; k < n_slots; ++k) {
+                    if (placed_now[k] || is_protected[adapter[k]]) continue;
+                    if (s < 0 || last_used[k] < best) {
+                        s = k;
+                        best = last_used[k];
+                    }
+                }
+                if (s < 0) return LORA_ERR_SLOTS_EXHAUSTED;
+            }
+        }
+        if (cur >= 0) {  // the adapter moves to an explicit other slot: its old slot becomes empty
+            steps.push_back({cur, -1, d.adapter_id, 0, 0.f, false});
+            adapter[cur] = -1;
+            rank[cur] = 0;
+            scale[cur] = 0.f;
+            id2slot[d.adapter_id] = -1;
+        }
+        const int evicted = adapter[s];
+        if (evicted >= 0) id2slot[evicted] = -1;
+        adapter[s] = d.adapter_id;
+        rank[s] = d.rank;
+        scale[s] = d.scale;
+        id2slot[d.adapter_id] = s;
+        last_used[s] = tick;
+        placed_now[s] = 1;
+        steps.push_back({s, d.adapter_id, evicted, d.rank, d.scale, true});
+        out_slot[i] = s;
+        out_copied[i] = 1;
+    }
+
+    // ---- commit ----
+    c->slot_adapter.swap(adapter);
+    c->slot_rank_h.swap(rank);
+    c->slot_scale_h.swap(scale);
+    c->slot_last_used.swap(last_used);
+    c->id2slot_h.swap(id2slot);
+    c->tick = tick;
+    c->n_resident = 0;
+    for (int k = 0; k < n_slots; ++k) c->n_resident += c->slot_adapter[k] >= 0;
+    for (int i = 0; i < n; ++i) {
+        descs[i].slot = out_slot[i];
+        descs[i].copied = out_copied[i];
+    }
+    if (c->host_only || steps.empty()) return LORA_OK;
+
+    // ---- enqueue ----
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream_v);
+    if (c->have_fwd && c->last_fwd_stream != cs) {
+        // earlier steps may still read the slots about to be overwritten
+        if (hipEventRecord(c->ev_fwd, c->last_fwd_stream) != hipSuccess) return LORA_ERR_HIP;
+        if (hipStreamWaitEvent(cs, c->ev_fwd, 0) != hipSuccess) return LORA_ERR_HIP;
+    }
+    for (size_t b = 0; b < steps.size(); b += kMetaBatch) {
+        MetaUpdates u;
+        std::memset(&u, 0, sizeof u);
+        u.n = (int)std::min<size_t>(kMetaBatch, steps.size() - b);
+        for (int i = 0; i < u.n; ++i) {
+            const Step& st = steps[b + i];
+            u.slot[i] = st.slot;
+            u.adapter[i] = st.adapter;
+            u.evicted[i] = st.evicted;
+            u.rank[i] = st.rank;
+            u.scale[i] = st.scale;
+        }
+        if (launch_meta_update(u, c->d_slot_rank(), c->d_slot_scale(), c->d_id2slot(), cs) != hipSuccess)
+            return LORA_ERR_HIP;
+    }
+    if (hipEventRecord(c->ev_meta, cs) != hipSuccess) return LORA_ERR_HIP;
+    c->meta_pending = true;
+    char* slots = c->base + c->L.off_slots;
+    for (int p = 0; p < n_proj; ++p) {
+        const size_t d_in = c->proj[p].d_in, d_out = c->proj[p].d_out;
+        for (int i = 0; i < n; ++i) {
+            if (!out_copied[i] || descs[i].rank <= 0) continue;
+            const size_t r = descs[i].rank;
+            char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
+            if (hipMemcpyAsync(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2, hipMemcpyHostToDevice, cs) != hipSuccess)
+                return LORA_ERR_HIP;
+            if (hipMemcpyAsync(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2, hipMemcpyHostToDevice, cs) != hipSuccess)
+                return LORA_ERR_HIP;
+        }
+        if (hipEventRecord(c->ev_proj[p], cs) != hipSuccess) return LORA_ERR_HIP;
+        c->proj_pending[p] = true;
+    }
+    c->copy_stream = cs;
+    return LORA_OK;
+}
+
+lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, int32_t mode, lora_segments* out,
+                        void* stream_v)
+{
+    if (!c || !out || T < 0 || T > c->cfg.max_tokens) return LORA_ERR_INVALID_ARG;
+    if (mode != LORA_BUCKET_SORTED && mode != LORA_BUCKET_RUNS) return LORA_ERR_INVALID_ARG;
+    if (T > 0 && !d_token_adapter) return LORA_ERR_INVALID_ARG;
+    if (c->host_only) return LORA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream_v);
+    if (c->meta_pending && s != c->copy_stream) {
+        if (hipStreamWaitEvent(s, c->ev_meta, 0) != hipSuccess) return LORA_ERR_HIP;
+    }
+    BucketArgs a;
+    a.ids = d_token_adapter;
+    a.T = T;
+    a.mode = mode;
+    a.id2slot = c->d_id2slot();
+    a.n_ids = c->cfg.max_adapter_id + 1;
+    a.n_slots = c->cfg.n_slots;
+    a.perm = c->dev<int32_t>(c->L.off_perm);
+    a.row_slot = c->dev<int32_t>(c->L.off_row_slot);
+    a.seg_start = c->dev<int32_t>(c->L.off_seg_start);
+    a.seg_slot = c->dev<int32_t>(c->L.off_seg_slot);
+    a.n_seg = c->d_n_seg();
+    a.piece_start = c->dev<int32_t>(c->L.off_piece_start);
+    a.piece_slot = c->dev<int32_t>(c->L.off_piece_slot);
+    a.n_pieces = c->d_n_pieces();
+    a.tok_key = c->dev<int32_t>(c->L.off_tok_key);
+    a.flags = c->d_flags();
+    c->last_launches.clear();
+    {
+        LaunchScope ls(c, s, "bucket");
+        if (launch_bucket(a, s) != hipSuccess) return LORA_ERR_HIP;
+    }
+    c->epoch += 1;
+    c->seg_T = T;
+    c->seg_mode = mode;
+    c->last_fwd_stream = s;
+    c->have_fwd = true;
+    out->perm = a.perm;
+    out->seg_start = a.seg_start;
+    out->seg_slot = a.seg_slot;
+    out->n_seg = a.n_seg;
+    out->T = T;
+    out->mode = mode;
+    out->epoch = c->epoch;
+    return LORA_OK;
+}
+
+lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const void* d_W, const lora_segments* seg,
+                               void* d_out, void* stream_v)
+{
+    if (!c || !seg) return LORA_ERR_INVALID_ARG;
+    if (p < 0 || p >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
+    if (seg->epoch != c->epoch || seg->T != c->seg_T || c->epoch == 0) return LORA_ERR_INVALID_ARG;
+    if (c->host_only) return LORA_ERR_HIP;
+    const int32_t T = seg->T;
+    c->last_launches.clear();
+    if (T == 0) return LORA_OK;
+    if (!d_x || !d_W || !d_out) return LORA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_x) | reinterpret_cast<uintptr_t>(d_W) | reinterpret_cast<uintptr_t>(d_out)) & 15)
+        return LORA_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream_v);
+    if (c->proj_pending[p] && s != c->copy_stream) {
+        if (hipStreamWaitEvent(s, c->ev_proj[p], 0) != hipSuccess) return LORA_ERR_HIP;
+    }
+    const int K = c->proj[p].d_in, N = c->proj[p].d_out;
+
+    // ---- plan ----
+    bool split = false;
+    if (T <= kSplitMaxTokens) {
+        if (c->cfg.path == LORA_PATH_SPLITK) split = true;
+        else if (c->cfg.path == LORA_PATH_AUTO) {
+            const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
+            split = tiles256 < 128;
+        }
+    }
+    const int Mpad = (T + 255) / 256 * 256;
+    int S = 1;
+    if (split) {
+        const int tiles = ((T + 255) / 256) * ((N + 127) / 128);
+        S = c->cfg.split_k > 0 ? c->cfg.split_k : std::max(1, std::min(16, (256 + tiles / 2) / tiles));
+        S = std::min(S, std::max(1, (K / kBK) / 2));
+        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)N);
+        S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
+        if ((size_t)S * Mpad * N > c->L.part_elems) return LORA_ERR_OOM;
+    }
+    int n_kc = 1, kc_len = K;
+    if (T <= kSplitMaxTokens) {
+        n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
+        kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
+        n_kc = (K + kc_len - 1) / kc_len;
+    }
+    if ((size_t)n_kc * T * c->cfg.max_rank > c->L.vpart_elems) return LORA_ERR_OOM;
+
+    const DeviceView dv = c->view(T);
+    float* vpart = c->dev<float>(c->L.off_vpart);
+    float* part = c->dev<float>(c->L.off_part);
+
+    // ---- shrink ----
+    if (c->n_resident > 0) {
+        ShrinkArgs sa;
+        sa.dv = dv;
+        sa.x = static_cast<const uint16_t*>(d_x);
+        sa.K = K;
+        sa.a_off = c->L.a_off[p];
+        sa.n_kc = n_kc;
+        sa.kc_len = kc_len;
+        sa.vpart = vpart;
+        const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
+        const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
+        const int grid = (int)std::max<long>(1, std::min<long>((items + 3) / 4, 2048));
+        LaunchScope ls(c, s, "shrink");
+        if (launch_shrink(sa, grid, s) != hipSuccess) return LORA_ERR_HIP;
+    }
+
+    // ---- base GEMM (+ expand) ----
+    GemmArgs ga;
+    ga.dv = dv;
+    ga.x = static_cast<const uint16_t*>(d_x);
+    ga.W = static_cast<const uint16_t*>(d_W);
+    ga.N = N;
+    ga.K = K;
+    ga.tiles_m = ga.tiles_n = 0;
+    ga.split_k = S;
+    ga.b_off = c->L.b_off[p];
+    ga.vpart = vpart;
+    ga.n_kc = n_kc;
+    ga.out = static_cast<uint16_t*>(d_out);
+    ga.part = part;
+    ga.Mpad = Mpad;
+    if (!split) {
+        LaunchScope ls(c, s, "gemm_fused");
+        const char* name = nullptr;
+        if (launch_gemm_fused(ga, s, &name) != hipSuccess) return LORA_ERR_HIP;
+        ls.rename(name);
+    } else {
+        {
+            LaunchScope ls(c, s, "gemm_splitk");
+            const char* name = nullptr;
+            if (launch_gemm_splitk(ga, s, &name) != hipSuccess) return LORA_ERR_HIP;
+            ls.rename(name);
+        }
+        ReduceArgs ra;
+        ra.dv = dv;
+        ra.N = N;
+        ra.split_k = S;
+        ra.Mpad = Mpad;
+        ra.part = part;
+        ra.vpart = vpart;
+        ra.n_kc = n_kc;
+        ra.b_off = c->L.b_off[p];
+        ra.out = static_cast<uint16_t*>(d_out);
+        ra.n_chunks = (N + 1023) / 1024;
+        const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
+        const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * ra.n_chunks;
+        const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
+        LaunchScope ls(c, s, "reduce_expand");
+        if (launch_reduce_expand(ra, grid, s) != hipSuccess) return LORA_ERR_HIP;
+    }
+    c->last_fwd_stream = s;
+    c->have_fwd = true;
+    return LORA_OK;
+}
+
+lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    if (c->host_only) return LORA_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream_v);
+    uint32_t word = 0;
+    if (hipMemcpyAsync(&word, c->d_flags(), sizeof word, hipMemcpyDeviceToHost, s) != hipSuccess) return LORA_ERR_HIP;
+    if (launch_fill_i32(reinterpret_cast<int32_t*>(c->d_flags()), 0, 1, s) != hipSuccess) return LORA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return LORA_ERR_HIP;
+    if (flags) *flags = word;
+    return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
+}
+
+int32_t lora_last_launches(const lora_ctx* c, const char** names, int32_t cap)
+{
+    if (!c) return 0;
+    const int32_t n = (int32_t)c->last_launches.size();
+    for (int32_t i = 0; i < n && i < cap && names; ++i) names[i] = c->last_launches[i];
+    return n;
+}
+
+lora_status lora_profile_enable(lora_ctx* c, int32_t on)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    if (c->host_only) return LORA_ERR_HIP;
+    if (on && c->prof_pool.empty()) {
+        c->prof_pool.resize(8192);
+        for (auto& sl : c->prof_pool) {
+            sl.name = nullptr;
+            if (hipEventCreate(&sl.beg) != hipSuccess || hipEventCreate(&sl.end) != hipSuccess) return LORA_ERR_HIP;
+        }
+    }
+    c->profiling = on != 0;
+    return LORA_OK;
+}
+
+int32_t lora_profile_collect(lora_ctx* c, const char** names, double* total_ms, int64_t* counts, int32_t cap)
+{
+    if (!c || c->host_only) return 0;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        ProfileSlot& sl = c->prof_pool[i];
+        float ms = 0.f;
+        if (hipEventSynchronize(sl.end) != hipSuccess) continue;
+        if (hipEventElapsedTime(&ms, sl.beg, sl.end) != hipSuccess) continue;
+        size_t k = 0;
+        for (; k < c->prof_names.size(); ++k)
+            if (c->prof_names[k] == sl.name) break;
+        if (k == c->prof_names.size()) {
+            c->prof_names.emplace_back(sl.name);
+            c->prof_ms.push_back(0.0);
+            c->prof_count.push_back(0);
+        }
+        c->prof_ms[k] += ms;
+        c->prof_count[k] += 1;
+    }
+    c->prof_used = 0;
+    const int32_t n = (int32_t)c->prof_names.size();
+    for (int32_t k = 0; k < n && k < cap; ++k) {
+        if (names) names[k] = c->prof_names[k].c_str();
+        if (total_ms) total_ms[k] = c->prof_ms[k];
+        if (counts) counts[k] = c->prof_count[k];
+    }
+    return n;
+}
+
+lora_status lora_profile_reset(lora_ctx* c)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    c->prof_used = 0;
+    c->prof_names.clear();
+    c->prof_ms.clear();
+    c->prof_count.clear();
+    return LORA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Internal declarations shared by the host code and the HIP kernels of liblora_mi355.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace lora {
+
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kPieceRows = 32;       // grouped rows are cut into pieces that never cross a 32-row window
+constexpr int kBK = 64;              // K extent of one LDS tile (bf16 elements)
+constexpr int kMaxSlots = 4095;
+constexpr int kMaxProj = 16;
+constexpr int kMaxRank = 64;
+constexpr int kMetaBatch = 16;       // slot-metadata updates carried by one kernel launch
+constexpr int kSplitMaxTokens = 1024;// largest T served by the split-K path
+constexpr int kShrinkKC = 512;       // K extent of one shrink work item on the split-K path
+constexpr int kMaxShrinkChunks = 64;
+
+// Device-side view of a context: everything the kernels need, passed by value.
+struct DeviceView {
+    // slot region
+    const uint16_t* slots;     // bf16 bits
+    size_t slot_stride;        // elements (bf16) between consecutive slots
+    const int32_t* slot_rank;  // [n_slots]
+    const float* slot_scale;   // [n_slots]
+    // segment map of the current step (grouped order)
+    const int32_t* perm;       // [T]
+    const int32_t* row_slot;   // [T] slot of each grouped position
+    const int32_t* piece_start;// [n_pieces + 1]
+    const int32_t* piece_slot; // [n_pieces]
+    const int32_t* n_pieces;   // [1]
+    int32_t T;
+    int32_t max_rank;
+};
+
+struct BucketArgs {
+    const int32_t* ids;
+    int32_t T;
+    int32_t mode;
+    const int32_t* id2slot;
+    int32_t n_ids;
+    int32_t n_slots;
+    int32_t* perm;
+    int32_t* row_slot;
+    int32_t* seg_start;
+    int32_t* seg_slot;
+    int32_t* n_seg;
+    int32_t* piece_start;
+    int32_t* piece_slot;
+    int32_t* n_pieces;
+    int32_t* tok_key;
+    uint32_t* flags;
+};
+
+struct MetaUpdates {
+    int32_t n;
+    int32_t slot[kMetaBatch];
+    int32_t adapter[kMetaBatch];   // adapter now in the slot (or -1)
+    int32_t evicted[kMetaBatch];   // adapter that left the slot (or -1)
+    int32_t rank[kMetaBatch];
+    float scale[kMetaBatch];
+};
+
+struct ShrinkArgs {
+    DeviceView dv;
+    const uint16_t* x;   // [T, K] bf16
+    int32_t K;
+    size_t a_off;        // element offset of this projection's A inside a slot
+    int32_t n_kc;        // K chunks
+    int32_t kc_len;      // K extent of a chunk (multiple of 64)
+    float* vpart;        // [n_kc][T][max_rank] fp32
+};
+
+struct GemmArgs {
+    DeviceView dv;
+    const uint16_t* x;   // [T, K]
+    const uint16_t* W;   // [N, K]
+    int32_t N, K;
+    int32_t tiles_m, tiles_n;
+    int32_t split_k;     // 1 on the fused path
+    size_t b_off;        // element offset of this projection's B inside a slot
+    const float* vpart;  // shrink output
+    int32_t n_kc;
+    uint16_t* out;       // fused path: [T, N] bf16
+    float* part;         // split path: [split_k][Mpad][N] fp32
+    int32_t Mpad;
+};
+
+struct ReduceArgs {
+    DeviceView dv;
+    int32_t N;
+    int32_t split_k;
+    int32_t Mpad;
+    const float* part;
+    const float* vpart;
+    int32_t n_kc;
+    size_t b_off;
+    uint16_t* out;       // [T, N] bf16
+    int32_t n_chunks;    // column chunks of 1024
+};
+
+// launchers (defined next to their kernels); every launch is asynchronous on `stream`
+hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream);
+hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot,
+                              hipStream_t stream);
+hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stream);
+hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);
+hipError_t launch_gemm_fused(const GemmArgs& a, hipStream_t stream, const char** name);
+hipError_t launch_gemm_splitk(const GemmArgs& a, hipStream_t stream, const char** name);
+hipError_t launch_reduce_expand(const ReduceArgs& a, int grid, hipStream_t stream);
+
+}  // namespace lora

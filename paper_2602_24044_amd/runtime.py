@@ -1,0 +1,141 @@
+"""Harness helper around the C ABI: owns the torch tensors (device slab, pinned host adapters, device
+inputs/outputs) that one synthetic workload needs and forwards every operation to liblora_mi355.
+No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import Workload
+
+
+def _bf16_tensor(bits: np.ndarray, device=None, pin: bool = False) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    if pin:
+        t = t.pin_memory()
+    if device is not None:
+        t = t.to(device, non_blocking=False)
+    return t.view(torch.bfloat16)
+
+
+def bf16_tensor_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class Session:
+    def __init__(self, w: Workload, path: int = B.LORA_PATH_AUTO, split_k: int = 0, device: str = "cuda:0",
+                 max_tokens: Optional[int] = None, upload_inputs: bool = True):
+        if not torch.cuda.is_available():
+            raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
+        self.w = w
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.max_tokens = int(max_tokens or max(w.T, 1))
+        cfg = B.make_config(w.proj, w.n_slots, w.max_rank, self.max_tokens, w.max_adapter_id, path=path,
+                            split_k=split_k)
+        nbytes = B.lora_slab_bytes(cfg)
+        if nbytes == 0:
+            raise B.LoraError(B.LORA_ERR_SHAPE, "lora_slab_bytes")
+        self.slab = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        cfg.slab = self.slab.data_ptr()
+        cfg.slab_bytes = nbytes
+        self.cfg = cfg
+        self.ctx = B.lora_create(cfg)
+        self.pinned: Dict[int, dict] = {}
+        self.seg: Optional[B.lora_segments] = None
+        self.W: List[torch.Tensor] = []
+        self.x: List[torch.Tensor] = []
+        self.out: List[torch.Tensor] = []
+        self.ids: Optional[torch.Tensor] = None
+        if upload_inputs:
+            self.upload_inputs()
+
+    # ---- inputs ----
+    def upload_inputs(self):
+        w = self.w
+        self.W = [_bf16_tensor(m, self.device) for m in w.W]
+        self.x = [_bf16_tensor(m, self.device) for m in w.x]
+        self.out = [torch.empty((w.T, d_out), dtype=torch.bfloat16, device=self.device) for (_, d_out) in w.proj]
+        self.ids = torch.from_numpy(w.token_ids).to(self.device)
+
+    def pin_adapter(self, aid: int) -> dict:
+        if aid not in self.pinned:
+            a = self.w.adapters[aid]
+            ent = {"adapter_id": aid, "rank": a.rank, "scale": a.scale, "slot": -1}
+            if a.rank > 0:
+                ent["A_t"] = [_bf16_tensor(m, pin=True) for m in a.A]
+                ent["B_t"] = [_bf16_tensor(m, pin=True) for m in a.B]
+                ent["A_ptrs"] = [t.data_ptr() for t in ent["A_t"]]
+                ent["B_ptrs"] = [t.data_ptr() for t in ent["B_t"]]
+            self.pinned[aid] = ent
+        return self.pinned[aid]
+
+    # ---- the three hot calls ----
+    def load(self, adapter_ids: Sequence[int], in_use: Sequence[int] = (), stream: Optional[torch.cuda.Stream] = None,
+             slots: Optional[Sequence[int]] = None, chunk: int = 64):
+        res = []
+        ids = list(adapter_ids)
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        for i in range(0, len(ids), chunk):
+            descs = []
+            for k, aid in enumerate(ids[i:i + chunk]):
+                d = dict(self.pin_adapter(aid))
+                if slots is not None:
+                    d["slot"] = int(slots[i + k])
+                descs.append(d)
+            res += B.lora_slots_load(self.ctx, descs, in_use, s)
+        return res
+
+    def bucket(self, ids: Optional[torch.Tensor] = None, mode: Optional[int] = None,
+               stream: Optional[torch.cuda.Stream] = None) -> B.lora_segments:
+        ids = self.ids if ids is None else ids
+        mode = self.w.mode if mode is None else mode
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        self.seg = B.lora_bucket(self.ctx, ids.data_ptr() if ids.numel() else 0, int(ids.numel()), mode, s)
+        return self.seg
+
+    def forward(self, p: int, x: Optional[torch.Tensor] = None, W: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        x = self.x[p] if x is None else x
+        W = self.W[p] if W is None else W
+        out = self.out[p] if out is None else out
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        B.lora_layer_forward(self.ctx, p, x.data_ptr(), W.data_ptr(), self.seg, out.data_ptr(), s)
+        return out
+
+    def step(self) -> None:
+        """One pass of the whole path: segment map + every projection."""
+        self.bucket()
+        for p in range(len(self.w.proj)):
+            self.forward(p)
+
+    # ---- read-back helpers ----
+    def _i32_at(self, ptr: int, n: int) -> np.ndarray:
+        off = ptr - self.slab.data_ptr()
+        assert 0 <= off and off + 4 * n <= self.slab.numel()
+        return self.slab[off:off + 4 * n].view(torch.int32).cpu().numpy()
+
+    def read_segments(self):
+        torch.cuda.synchronize()
+        seg = self.seg
+        n_seg = int(self._i32_at(seg.n_seg, 1)[0])
+        perm = self._i32_at(seg.perm, seg.T) if seg.T else np.zeros(0, np.int32)
+        return (perm, self._i32_at(seg.seg_start, n_seg + 1), self._i32_at(seg.seg_slot, n_seg) if n_seg else
+                np.zeros(0, np.int32), n_seg)
+
+    def id2slot(self) -> np.ndarray:
+        return np.array([B.lora_slot_of(self.ctx, i) for i in range(self.w.max_adapter_id + 1)], dtype=np.int32)
+
+    def close(self):
+        if self.ctx:
+            B.lora_destroy(self.ctx)
+            self.ctx = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,61 @@
+"""Shared helpers for the GPU parity tests (not collected by pytest)."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2602_24044_amd import binding as B
+from paper_2602_24044_amd import workloads as wl
+from paper_2602_24044_amd.runtime import Session, bf16_tensor_to_bits
+
+TOL = 5e-3   # max|y - y_ref| / max|y_ref|, bf16 in, fp32 accumulate, bf16 out
+
+
+def announce(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+
+
+def check_segments(sess, w, mode=None):
+    """Segment map of the last bucket call against the oracle, bit for bit."""
+    mode = w.mode if mode is None else mode
+    perm, seg_start, seg_slot, n_seg = sess.read_segments()
+    o_perm, o_start, o_slot, o_n, o_flags = oracle.bucket(w.token_ids, sess.id2slot(), mode)
+    assert n_seg == o_n
+    assert np.array_equal(perm, o_perm)
+    assert np.array_equal(seg_start, o_start)
+    assert np.array_equal(seg_slot, o_slot)
+    return o_flags
+
+
+def rel_err(out_bits, y_ref):
+    got = wl.bf16_bits_to_f64(out_bits)
+    denom = np.max(np.abs(y_ref))
+    return float(np.max(np.abs(got - y_ref)) / (denom if denom > 0 else 1.0))
+
+
+def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=True, tol=TOL):
+    """Loads the resident adapters, runs one step, compares every projection with the oracle."""
+    announce(f"{w.name} T={w.T} path={path} split_k={split_k} proj={w.proj}")
+    sess = Session(w, path=path, split_k=split_k)
+    try:
+        resident = w.resident if preload is None else preload
+        sess.load(resident)
+        if w.missing:
+            sess.load(w.missing, in_use=w.distinct_adapters())
+        sess.bucket()
+        if check_maps:
+            flags = check_segments(sess, w)
+            assert flags == 0
+        errs = []
+        for p in range(len(w.proj)):
+            out = sess.forward(p)
+            torch.cuda.synchronize()
+            y_ref = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p))
+            e = rel_err(bf16_tensor_to_bits(out), y_ref)
+            announce(f"  proj {p} {w.proj[p]} launches={B.lora_last_launches(sess.ctx)} rel_err={e:.3e}")
+            errs.append(e)
+        st, word = B.lora_poll_device_flags(sess.ctx)
+        assert st == B.LORA_OK and word == 0
+        assert max(errs) <= tol, errs
+        return errs
+    finally:
+        sess.close()

@@ -1,0 +1,146 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, validates
+arguments, and its host-side slot table follows the slot-table oracle."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from conftest import GOLDEN, ROOT
+from paper_2602_24044_amd import binding as B
+from test_oracle_slots import parse_trace
+
+
+def _host_ctx(n_slots=3, max_rank=32, proj=((64, 64),), max_adapter_id=63):
+    cfg = B.make_config(proj, n_slots, max_rank, 16, max_adapter_id, flags=B.LORA_CREATE_HOST_ONLY)
+    return B.lora_create(cfg)
+
+
+def test_library_exports_every_declared_symbol():
+    import ctypes
+    hdr = open(os.path.join(ROOT, "include", "lora_mi355.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lora_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert B.lora_status_string(B.LORA_OK) == "ok"
+    assert "slot" in B.lora_status_string(B.LORA_ERR_SLOTS_EXHAUSTED)
+
+
+def test_config_validation():
+    bad = [
+        dict(proj=((60, 64),)),            # d_in not a multiple of 64
+        dict(proj=((64, 12),)),            # d_out not a multiple of 8
+        dict(max_rank=12),                 # S_max not a multiple of 8
+        dict(max_rank=128),
+    ]
+    for kw in bad:
+        args = dict(proj=((64, 64),), n_slots=2, max_rank=8, max_tokens=4, max_adapter_id=3)
+        args.update(kw)
+        cfg = B.make_config(args["proj"], args["n_slots"], args["max_rank"], args["max_tokens"],
+                            args["max_adapter_id"], flags=B.LORA_CREATE_HOST_ONLY)
+        assert B.lora_slab_bytes(cfg) == 0
+        with pytest.raises(B.LoraError) as e:
+            B.lora_create(cfg)
+        assert e.value.status == B.LORA_ERR_SHAPE
+    cfg = B.make_config(((64, 64),), 0, 8, 4, 3, flags=B.LORA_CREATE_HOST_ONLY)
+    with pytest.raises(B.LoraError) as e:
+        B.lora_create(cfg)
+    assert e.value.status == B.LORA_ERR_INVALID_ARG
+
+
+def test_slab_bytes_covers_the_slot_region():
+    proj = ((4096, 4096), (4096, 1024))
+    cfg = B.make_config(proj, 32, 32, 256, 31)
+    slot_region = 32 * 32 * sum(a + b for a, b in proj) * 2   # A_max x S_max x sum(d_in + d_out) x 2 bytes
+    assert B.lora_slab_bytes(cfg) >= slot_region
+    # without device memory a real context cannot be created
+    with pytest.raises(B.LoraError) as e:
+        B.lora_create(cfg)
+    assert e.value.status == B.LORA_ERR_INVALID_ARG
+
+
+def test_hand_traced_sequence_on_the_library():
+    n_slots, calls = parse_trace(os.path.join(GOLDEN, "slot_trace.txt"))
+    ctx = _host_ctx(n_slots)
+    try:
+        for in_use, reqs, exp, state in calls:
+            descs = [dict(adapter_id=a, rank=r, scale=1.0, slot=s) for (a, r, s) in reqs]
+            if exp is None:
+                with pytest.raises(B.LoraError) as e:
+                    B.lora_slots_load(ctx, descs, in_use)
+                assert e.value.status == B.LORA_ERR_SLOTS_EXHAUSTED
+            else:
+                assert B.lora_slots_load(ctx, descs, in_use) == exp
+            assert [B.lora_slot_adapter(ctx, s) for s in range(n_slots)] == state
+    finally:
+        B.lora_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_sequences_match_the_slot_oracle(seed):
+    rng = np.random.default_rng(seed)
+    n_slots, n_ids = 6, 20
+    ctx = _host_ctx(n_slots)
+    tab = oracle.SlotTable(n_slots)
+    try:
+        for _ in range(300):
+            k = int(rng.integers(1, 4))
+            ads = rng.choice(n_ids, size=k, replace=False)
+            reqs = []
+            for a in ads:
+                slot = int(rng.integers(0, n_slots)) if rng.random() < 0.1 else -1
+                reqs.append((int(a), int(rng.choice([0, 8, 16, 32])), slot))
+            in_use = [int(v) for v in rng.choice(n_ids, size=int(rng.integers(0, 7)), replace=False)]
+            descs = [dict(adapter_id=a, rank=r, scale=1.0, slot=s) for (a, r, s) in reqs]
+            try:
+                want = tab.load(reqs, in_use)
+            except oracle.SlotsExhausted:
+                with pytest.raises(B.LoraError) as e:
+                    B.lora_slots_load(ctx, descs, in_use)
+                assert e.value.status == B.LORA_ERR_SLOTS_EXHAUSTED
+            else:
+                assert B.lora_slots_load(ctx, descs, in_use) == want
+            assert [B.lora_slot_adapter(ctx, s) for s in range(n_slots)] == tab.adapter
+            m = tab.id2slot(n_ids)
+            assert [B.lora_slot_of(ctx, i) for i in range(n_ids)] == m.tolist()
+    finally:
+        B.lora_destroy(ctx)
+
+
+def test_load_argument_errors():
+    ctx = _host_ctx(n_slots=2, max_rank=16, max_adapter_id=7)
+    try:
+        cases = [
+            (dict(adapter_id=9, rank=8, scale=1.0), B.LORA_ERR_ID_RANGE),
+            (dict(adapter_id=1, rank=32, scale=1.0), B.LORA_ERR_RANK_EXCEEDS_SMAX),
+            (dict(adapter_id=1, rank=12, scale=1.0), B.LORA_ERR_SHAPE),
+            (dict(adapter_id=1, rank=8, scale=1.0, slot=2), B.LORA_ERR_SLOT_RANGE),
+            (dict(adapter_id=1, rank=-8, scale=1.0), B.LORA_ERR_INVALID_ARG),
+        ]
+        for d, status in cases:
+            with pytest.raises(B.LoraError) as e:
+                B.lora_slots_load(ctx, [d])
+            assert e.value.status == status
+            assert [B.lora_slot_adapter(ctx, s) for s in range(2)] == [-1, -1]
+        with pytest.raises(B.LoraError) as e:
+            B.lora_slots_load(ctx, [dict(adapter_id=1, rank=8, scale=1.0)], in_use=[99])
+        assert e.value.status == B.LORA_ERR_ID_RANGE
+    finally:
+        B.lora_destroy(ctx)
+
+
+def test_host_only_context_refuses_device_work():
+    ctx = _host_ctx()
+    try:
+        with pytest.raises(B.LoraError) as e:
+            B.lora_bucket(ctx, 0, 0, B.LORA_BUCKET_SORTED)
+        assert e.value.status == B.LORA_ERR_HIP
+    finally:
+        B.lora_destroy(ctx)

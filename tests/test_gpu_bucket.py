@@ -1,0 +1,58 @@
+"""GPU parity of the integer segment-map kernel alone: bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import announce, check_segments
+from paper_2602_24044_amd import binding as B
+from paper_2602_24044_amd import workloads as wl
+from paper_2602_24044_amd.runtime import Session
+
+pytestmark = pytest.mark.gpu
+
+
+def _bucket_only_workload(T, n_slots, seed, mode, frac_none=0.1, zipf=False):
+    """Token ids only (rank-0 adapters: nothing to copy).  RUNS mode gets request-like runs."""
+    rng = np.random.default_rng(seed)
+    n_ids = n_slots + 9
+    if mode == wl.BUCKET_RUNS:
+        ids = np.zeros(0, dtype=np.int32)
+        while ids.size < T:
+            run = int(rng.integers(1, 90))
+            ids = np.concatenate([ids, np.full(run, rng.integers(-1, n_slots), dtype=np.int32)])
+        ids = ids[:T]
+    else:
+        if zipf:
+            ids = wl.zipf_ids(rng, T, list(range(n_slots)), 1.0)
+        else:
+            ids = rng.integers(0, n_slots, size=T).astype(np.int32)
+        ids[rng.random(T) < frac_none] = -1
+    return wl.custom("bucket_only", seed, [(64, 8)], ["p"], n_slots, 8, mode, ids.astype(np.int32),
+                     {i: 0 for i in range(n_ids)}, resident=[])
+
+
+@pytest.mark.parametrize("mode", [wl.BUCKET_SORTED, wl.BUCKET_RUNS])
+@pytest.mark.parametrize("T,n_slots,seed", [(1, 1, 0), (63, 3, 1), (64, 4, 2), (65, 33, 3), (256, 32, 4), (512, 384, 5),
+                                            (1023, 100, 6), (1024, 17, 7), (1025, 1000, 8), (2432, 128, 9),
+                                            (26000, 64, 10), (5000, 4095, 11)])
+def test_segment_map_bit_exact(mode, T, n_slots, seed):
+    w = _bucket_only_workload(T, n_slots, seed, mode, zipf=(seed % 2 == 0))
+    announce(f"bucket T={T} n_slots={n_slots} mode={mode} seed={seed}")
+    sess = Session(w, upload_inputs=False)
+    try:
+        # scatter the adapters over slots in a shuffled order so that slot != adapter id
+        rng = np.random.default_rng(seed + 100)
+        order = rng.permutation(n_slots)
+        sess.load([int(a) for a in order], slots=[int(s) for s in rng.permutation(n_slots)])
+        ids = torch.from_numpy(w.token_ids).to(sess.device)
+        sess.bucket(ids)
+        assert check_segments(sess, w) == 0
+        # a second call with different ids on the same context
+        ids2 = w.token_ids[::-1].copy()
+        sess.bucket(torch.from_numpy(ids2).to(sess.device))
+        w2 = w
+        w2.token_ids = ids2
+        assert check_segments(sess, w2) == 0
+    finally:
+        sess.close()

@@ -1,0 +1,243 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Segment maps bit-exact; outputs max|y - y_ref| / max|y_ref| <= 5e-3 per projection."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, announce, check_segments, rel_err, run_and_check
+from paper_2602_24044_amd import binding as B
+from paper_2602_24044_amd import workloads as wl
+from paper_2602_24044_amd.runtime import Session, bf16_tensor_to_bits
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [B.LORA_PATH_AUTO, B.LORA_PATH_FUSED, B.LORA_PATH_SPLITK]
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config1_tiny(path):
+    run_and_check(wl.config1(), path=path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("n_tokens", [256, 300])
+def test_config2_decode_reduced(path, n_tokens):
+    run_and_check(wl.config2(shrink=8, n_tokens=n_tokens), path=path)
+
+
+@pytest.mark.parametrize("path", [B.LORA_PATH_AUTO, B.LORA_PATH_FUSED])
+def test_config3_prefill_reduced(path):
+    w = wl.config3(shrink=8, n_req=12, len_div=4)
+    assert w.T > 1024
+    run_and_check(w, path=path)
+
+
+def test_config3_prefill_short_splitk():
+    w = wl.config3(shrink=8, n_req=6, len_div=8)
+    assert w.T <= 1024
+    run_and_check(w, path=B.LORA_PATH_SPLITK)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config4_many_adapters_reduced(path):
+    run_and_check(wl.config4(shrink=8), path=path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config5_mixed_with_loads_reduced(path):
+    w = wl.config5(shrink=8, prefill_len=700, n_decode=200, population=96, n_slots=48, n_missing=8)
+    run_and_check(w, path=path)
+
+
+@pytest.mark.parametrize("split_k", [1, 2, 3, 16])
+def test_split_k_values(split_k):
+    run_and_check(wl.config2(shrink=8, n_tokens=130), path=B.LORA_PATH_SPLITK, split_k=split_k)
+
+
+def _int_workload(seed, T, d_in, d_out, ranks, n_slots):
+    """Small-integer inputs: every partial sum is exact in fp32 and v is exact in bf16, so the GPU must
+    reproduce the rounded oracle bit for bit whatever its summation order."""
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    w = wl.custom("int_exact", seed, [(d_in, d_out)], ["p"], n_slots, max(max(ranks), 8), wl.BUCKET_SORTED, ids,
+                  {i: r for i, r in enumerate(ranks)}, scales={i: 2.0 ** (i % 3 - 1) for i in range(len(ranks))})
+    w.W[0] = wl.to_bf16_bits(rng.integers(-2, 3, size=(d_out, d_in)).astype(np.float32))
+    w.x[0] = wl.to_bf16_bits(rng.integers(-1, 2, size=(T, d_in)).astype(np.float32))
+    for a in w.adapters.values():
+        if a.rank > 0:
+            a.A[0] = wl.to_bf16_bits(rng.integers(-1, 2, size=(a.rank, d_in)).astype(np.float32))
+            a.B[0] = wl.to_bf16_bits(rng.integers(-2, 3, size=(d_out, a.rank)).astype(np.float32) * 0.25)
+    return w
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_small_integer_inputs_are_bit_exact(path):
+    w = _int_workload(5, T=77, d_in=128, d_out=264, ranks=[8, 16, 0, 32, 8], n_slots=5)
+    announce(f"int exact path={path}")
+    sess = Session(w, path=path)
+    try:
+        sess.load(w.resident)
+        sess.bucket()
+        out = sess.forward(0)
+        torch.cuda.synchronize()
+        y_ref = oracle.project(w.x[0], w.W[0], w.token_ids, oracle.adapters_of(w, 0))
+        assert np.max(np.abs(y_ref)) < 2.0 ** 20
+        want = wl.to_bf16_bits(y_ref.astype(np.float32))
+        got = bf16_tensor_to_bits(out)
+        # +0 and -0 are the same value
+        assert np.array_equal(wl.bf16_bits_to_f32(got), wl.bf16_bits_to_f32(want))
+    finally:
+        sess.close()
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_lora_term_alone(path):
+    # W = 0: the tolerance is then relative to the LoRA term itself
+    w = wl.config2(shrink=8, n_tokens=200)
+    for p in range(len(w.W)):
+        w.W[p] = np.zeros_like(w.W[p])
+    run_and_check(w, path=path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_zero_adapters_equal_the_gpu_base_run(path):
+    w = wl.config2(shrink=8, n_tokens=96)
+    sess = Session(w, path=path)
+    try:
+        sess.load(w.resident)
+        # base-only reference run on the GPU: every token without adapter
+        ids_none = torch.full((w.T,), -1, dtype=torch.int32, device=sess.device)
+        sess.bucket(ids_none)
+        base = [bf16_tensor_to_bits(sess.forward(p)).copy() for p in range(len(w.proj))]
+        # B = 0 for every adapter
+        wz = wl.config2(shrink=8, n_tokens=96)
+        for a in wz.adapters.values():
+            a.B = [np.zeros_like(b) for b in a.B]
+        sz = Session(wz, path=path)
+        try:
+            sz.load(wz.resident)
+            sz.bucket()
+            for p in range(len(w.proj)):
+                got = bf16_tensor_to_bits(sz.forward(p))
+                assert np.array_equal(wl.bf16_bits_to_f32(got), wl.bf16_bits_to_f32(base[p]))
+        finally:
+            sz.close()
+    finally:
+        sess.close()
+
+
+def test_rank0_and_backbone_only_tokens():
+    rng = np.random.default_rng(3)
+    ids = rng.integers(-1, 4, size=150).astype(np.int32)
+    w = wl.custom("rank0", 13, [(256, 136)], ["p"], 4, 16, wl.BUCKET_SORTED, ids, {0: 8, 1: 0, 2: 16, 3: 0})
+    for path in PATHS:
+        run_and_check(w, path=path)
+
+
+EDGE_IDS = {
+    "one_token": np.array([2], dtype=np.int32),
+    "all_same": np.full(100, 3, dtype=np.int32),
+    "all_distinct": np.arange(40, dtype=np.int32),
+    "all_backbone": np.full(70, -1, dtype=np.int32),
+    "ragged_65": (np.arange(65) % 7).astype(np.int32),
+    "alternating": (np.arange(257) % 2).astype(np.int32),
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_IDS))
+@pytest.mark.parametrize("mode", [wl.BUCKET_SORTED, wl.BUCKET_RUNS])
+def test_edge_batches(name, mode):
+    ids = EDGE_IDS[name]
+    w = wl.custom(f"edge_{name}", 17, [(128, 72)], ["p"], 40, 16, mode, ids, {i: (8 if i % 2 else 16) for i in range(40)})
+    for path in (B.LORA_PATH_FUSED, B.LORA_PATH_SPLITK):
+        run_and_check(w, path=path)
+
+
+def test_empty_batch():
+    w = wl.custom("empty", 1, [(64, 64)], ["p"], 2, 8, wl.BUCKET_SORTED, np.zeros(0, np.int32), {0: 8, 1: 8})
+    sess = Session(w, max_tokens=8)
+    try:
+        sess.load(w.resident)
+        sess.bucket()
+        perm, seg_start, seg_slot, n_seg = sess.read_segments()
+        assert n_seg == 0 and seg_start.tolist() == [0] and perm.size == 0
+        sess.forward(0)      # no-op
+        torch.cuda.synchronize()
+    finally:
+        sess.close()
+
+
+def test_non_resident_token_sets_flag_and_runs_backbone_only():
+    ids = np.array([0, 1, 2, 1, 0, 5], dtype=np.int32)
+    w = wl.custom("nonres", 19, [(128, 64)], ["p"], 2, 8, wl.BUCKET_SORTED, ids, {i: 8 for i in range(6)})
+    sess = Session(w)
+    try:
+        sess.load([0, 2])                      # adapters 1 and 5 are not resident
+        sess.bucket()
+        flags = check_segments(sess, w)
+        assert flags == oracle.FLAG_NOT_RESIDENT
+        out = sess.forward(0)
+        torch.cuda.synchronize()
+        st, word = B.lora_poll_device_flags(sess.ctx)
+        assert st == B.LORA_ERR_NOT_RESIDENT and word & B.LORA_FLAG_NOT_RESIDENT
+        st, word = B.lora_poll_device_flags(sess.ctx)
+        assert st == B.LORA_OK and word == 0   # read-and-clear
+        served = np.where(np.isin(ids, [0, 2]), ids, -1).astype(np.int32)
+        y_ref = oracle.project(w.x[0], w.W[0], served, oracle.adapters_of(w, 0))
+        assert rel_err(bf16_tensor_to_bits(out), y_ref) <= TOL
+    finally:
+        sess.close()
+
+
+def test_eviction_reloads_slot_contents():
+    # two slots, three adapters used in turn: each step must see the adapter loaded last into its slot
+    ids_all = {a: np.full(33, a, dtype=np.int32) for a in range(3)}
+    w = wl.custom("evict", 23, [(128, 80)], ["p"], 2, 16, wl.BUCKET_SORTED, ids_all[0], {0: 8, 1: 16, 2: 8})
+    sess = Session(w)
+    tab = oracle.SlotTable(2)
+    try:
+        for a in [0, 1, 2, 0, 1, 1, 2]:
+            got = sess.load([a], in_use=[a])
+            want = tab.load([(a, w.adapters[a].rank, -1)], [a])
+            assert got == want
+            ids = ids_all[a]
+            sess.bucket(torch.from_numpy(ids).to(sess.device))
+            out = sess.forward(0)
+            torch.cuda.synchronize()
+            y_ref = oracle.project(w.x[0], w.W[0], ids, oracle.adapters_of(w, 0))
+            assert rel_err(bf16_tensor_to_bits(out), y_ref) <= TOL
+    finally:
+        sess.close()
+
+
+def test_results_are_deterministic_run_to_run():
+    w = wl.config4(shrink=8, n_tokens=200, n_adapters=64)
+    for path in (B.LORA_PATH_FUSED, B.LORA_PATH_SPLITK):
+        sess = Session(w, path=path)
+        try:
+            sess.load(w.resident)
+            sess.bucket()
+            first = [bf16_tensor_to_bits(sess.forward(p)).copy() for p in range(len(w.proj))]
+            for _ in range(3):
+                sess.bucket()
+                for p in range(len(w.proj)):
+                    assert np.array_equal(bf16_tensor_to_bits(sess.forward(p)), first[p])
+        finally:
+            sess.close()
+
+
+def test_stale_segment_map_is_rejected():
+    w = wl.config1()
+    sess = Session(w)
+    try:
+        sess.load(w.resident)
+        old = sess.bucket()
+        sess.bucket()
+        with pytest.raises(B.LoraError) as e:
+            B.lora_layer_forward(sess.ctx, 0, sess.x[0].data_ptr(), sess.W[0].data_ptr(), old, sess.out[0].data_ptr())
+        assert e.value.status == B.LORA_ERR_INVALID_ARG
+        with pytest.raises(B.LoraError):
+            B.lora_layer_forward(sess.ctx, 3, sess.x[0].data_ptr(), sess.W[0].data_ptr(), sess.seg, sess.out[0].data_ptr())
+    finally:
+        sess.close()
