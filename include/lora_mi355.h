@@ -195,6 +195,10 @@ lora_status lora_profile_reset(lora_ctx *ctx);
 
 const char *lora_status_string(lora_status s);
 
+/* Text of the most recent failing HIP runtime call made by this library on the calling thread
+ * ("<call>: <hip error string>"), or "" if none failed.  Valid until the next failure. */
+const char *lora_last_hip_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,6 +18,26 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is not built; run `python -m paper_2602_24044_amd.build` (needs hipcc). "
         "There is no fallback path.")
 
+
+
+def _preload_hip_runtime() -> None:
+    """One process must hold one HIP runtime.  PyTorch ships its own libamdhip64 (same soname as the
+    system one) and resolves it by file name, so load that copy first when PyTorch is installed: this
+    library's dependency on the soname then binds to the same runtime that owns torch's memory and
+    streams, whichever of the two modules is imported first."""
+    import importlib.util
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        spec = None
+    if spec is None or not spec.submodule_search_locations:
+        return
+    cand = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
+_preload_hip_runtime()
 _lib = ctypes.CDLL(LIB_PATH)
 
 # ---- status / enums (mirror include/lora_mi355.h) ----
@@ -43,6 +63,7 @@ EXPORTS = [
     "lora_slab_bytes", "lora_create", "lora_destroy", "lora_slots_load", "lora_bucket", "lora_layer_forward",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
+    "lora_last_hip_error",
 ]
 
 
@@ -100,16 +121,23 @@ _lib.lora_profile_reset.restype = ctypes.c_int
 _lib.lora_profile_reset.argtypes = [_P]
 _lib.lora_status_string.restype = ctypes.c_char_p
 _lib.lora_status_string.argtypes = [ctypes.c_int]
+_lib.lora_last_hip_error.restype = ctypes.c_char_p
+_lib.lora_last_hip_error.argtypes = []
 
 
 class LoraError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {lora_status_string(status)} (status {status})")
+        detail = f" [{lora_last_hip_error()}]" if status == LORA_ERR_HIP else ""
+        super().__init__(f"{where}: {lora_status_string(status)} (status {status}){detail}")
 
 
 def lora_status_string(status: int) -> str:
     return _lib.lora_status_string(int(status)).decode()
+
+
+def lora_last_hip_error() -> str:
+    return _lib.lora_last_hip_error().decode()
 
 
 def make_config(proj: Sequence[Tuple[int, int]], n_slots: int, max_rank: int, max_tokens: int,

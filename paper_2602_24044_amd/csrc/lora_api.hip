@@ -13,6 +13,17 @@ using namespace lora;
 
 namespace {
 
+thread_local std::string g_last_hip_error;
+
+inline bool hip_fail(hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return false;
+    g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return true;
+}
+#define HIP_FAIL(call) hip_fail((call), #call)
+
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -195,6 +206,8 @@ struct LaunchScope {
 
 extern "C" {
 
+const char* lora_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
 const char* lora_status_string(lora_status s)
 {
     switch (s) {
@@ -253,16 +266,16 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
             return LORA_ERR_OOM;
         }
         c->base = static_cast<char*>(cfg->slab);
-        bool ok = hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming) == hipSuccess &&
-                  hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming) == hipSuccess;
+        bool ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming)) &&
+                  !HIP_FAIL(hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming));
         for (int p = 0; ok && p < cfg->n_proj; ++p)
-            ok = hipEventCreateWithFlags(&c->ev_proj[p], hipEventDisableTiming) == hipSuccess;
-        ok = ok && launch_fill_i32(c->d_slot_rank(), 0, cfg->n_slots, nullptr) == hipSuccess;
-        ok = ok && launch_fill_i32(reinterpret_cast<int32_t*>(c->d_slot_scale()), 0, cfg->n_slots, nullptr) == hipSuccess;
-        ok = ok && launch_fill_i32(c->d_id2slot(), -1, (size_t)cfg->max_adapter_id + 1, nullptr) == hipSuccess;
-        ok = ok && launch_fill_i32(c->dev<int32_t>(c->L.off_header), 0, 64, nullptr) == hipSuccess;
-        ok = ok && launch_fill_i32(c->dev<int32_t>(c->L.off_piece_start), 0, 1, nullptr) == hipSuccess;
-        ok = ok && hipDeviceSynchronize() == hipSuccess;
+            ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_proj[p], hipEventDisableTiming));
+        ok = ok && !HIP_FAIL(launch_fill_i32(c->d_slot_rank(), 0, cfg->n_slots, nullptr));
+        ok = ok && !HIP_FAIL(launch_fill_i32(reinterpret_cast<int32_t*>(c->d_slot_scale()), 0, cfg->n_slots, nullptr));
+        ok = ok && !HIP_FAIL(launch_fill_i32(c->d_id2slot(), -1, (size_t)cfg->max_adapter_id + 1, nullptr));
+        ok = ok && !HIP_FAIL(launch_fill_i32(c->dev<int32_t>(c->L.off_header), 0, 64, nullptr));
+        ok = ok && !HIP_FAIL(launch_fill_i32(c->dev<int32_t>(c->L.off_piece_start), 0, 1, nullptr));
+        ok = ok && !HIP_FAIL(hipDeviceSynchronize());
         if (!ok) {
             (void)hipGetLastError();
             lora_destroy(c);
@@ -407,8 +420,8 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     hipStream_t cs = static_cast<hipStream_t>(copy_stream_v);
     if (c->have_fwd && c->last_fwd_stream != cs) {
         // earlier steps may still read the slots about to be overwritten
-        if (hipEventRecord(c->ev_fwd, c->last_fwd_stream) != hipSuccess) return LORA_ERR_HIP;
-        if (hipStreamWaitEvent(cs, c->ev_fwd, 0) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipEventRecord(c->ev_fwd, c->last_fwd_stream))) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamWaitEvent(cs, c->ev_fwd, 0))) return LORA_ERR_HIP;
     }
     for (size_t b = 0; b < steps.size(); b += kMetaBatch) {
         MetaUpdates u;
@@ -422,10 +435,10 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             u.rank[i] = st.rank;
             u.scale[i] = st.scale;
         }
-        if (launch_meta_update(u, c->d_slot_rank(), c->d_slot_scale(), c->d_id2slot(), cs) != hipSuccess)
+        if (HIP_FAIL(launch_meta_update(u, c->d_slot_rank(), c->d_slot_scale(), c->d_id2slot(), cs)))
             return LORA_ERR_HIP;
     }
-    if (hipEventRecord(c->ev_meta, cs) != hipSuccess) return LORA_ERR_HIP;
+    if (HIP_FAIL(hipEventRecord(c->ev_meta, cs))) return LORA_ERR_HIP;
     c->meta_pending = true;
     char* slots = c->base + c->L.off_slots;
     for (int p = 0; p < n_proj; ++p) {
@@ -434,12 +447,12 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             if (!out_copied[i] || descs[i].rank <= 0) continue;
             const size_t r = descs[i].rank;
             char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
-            if (hipMemcpyAsync(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2, hipMemcpyHostToDevice, cs) != hipSuccess)
+            if (HIP_FAIL(hipMemcpyAsync(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2, hipMemcpyHostToDevice, cs)))
                 return LORA_ERR_HIP;
-            if (hipMemcpyAsync(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2, hipMemcpyHostToDevice, cs) != hipSuccess)
+            if (HIP_FAIL(hipMemcpyAsync(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2, hipMemcpyHostToDevice, cs)))
                 return LORA_ERR_HIP;
         }
-        if (hipEventRecord(c->ev_proj[p], cs) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipEventRecord(c->ev_proj[p], cs))) return LORA_ERR_HIP;
         c->proj_pending[p] = true;
     }
     c->copy_stream = cs;
@@ -455,7 +468,7 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     if (c->host_only) return LORA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream_v);
     if (c->meta_pending && s != c->copy_stream) {
-        if (hipStreamWaitEvent(s, c->ev_meta, 0) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_meta, 0))) return LORA_ERR_HIP;
     }
     BucketArgs a;
     a.ids = d_token_adapter;
@@ -477,7 +490,7 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     c->last_launches.clear();
     {
         LaunchScope ls(c, s, "bucket");
-        if (launch_bucket(a, s) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(launch_bucket(a, s))) return LORA_ERR_HIP;
     }
     c->epoch += 1;
     c->seg_T = T;
@@ -509,7 +522,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         return LORA_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream_v);
     if (c->proj_pending[p] && s != c->copy_stream) {
-        if (hipStreamWaitEvent(s, c->ev_proj[p], 0) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[p], 0))) return LORA_ERR_HIP;
     }
     const int K = c->proj[p].d_in, N = c->proj[p].d_out;
 
@@ -558,7 +571,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
         const int grid = (int)std::max<long>(1, std::min<long>((items + 3) / 4, 2048));
         LaunchScope ls(c, s, "shrink");
-        if (launch_shrink(sa, grid, s) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
     }
 
     // ---- base GEMM (+ expand) ----
@@ -579,13 +592,13 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     if (!split) {
         LaunchScope ls(c, s, "gemm_fused");
         const char* name = nullptr;
-        if (launch_gemm_fused(ga, s, &name) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(launch_gemm_fused(ga, s, &name))) return LORA_ERR_HIP;
         ls.rename(name);
     } else {
         {
             LaunchScope ls(c, s, "gemm_splitk");
             const char* name = nullptr;
-            if (launch_gemm_splitk(ga, s, &name) != hipSuccess) return LORA_ERR_HIP;
+            if (HIP_FAIL(launch_gemm_splitk(ga, s, &name))) return LORA_ERR_HIP;
             ls.rename(name);
         }
         ReduceArgs ra;
@@ -603,7 +616,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * ra.n_chunks;
         const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
         LaunchScope ls(c, s, "reduce_expand");
-        if (launch_reduce_expand(ra, grid, s) != hipSuccess) return LORA_ERR_HIP;
+        if (HIP_FAIL(launch_reduce_expand(ra, grid, s))) return LORA_ERR_HIP;
     }
     c->last_fwd_stream = s;
     c->have_fwd = true;
@@ -616,9 +629,9 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     if (c->host_only) return LORA_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream_v);
     uint32_t word = 0;
-    if (hipMemcpyAsync(&word, c->d_flags(), sizeof word, hipMemcpyDeviceToHost, s) != hipSuccess) return LORA_ERR_HIP;
-    if (launch_fill_i32(reinterpret_cast<int32_t*>(c->d_flags()), 0, 1, s) != hipSuccess) return LORA_ERR_HIP;
-    if (hipStreamSynchronize(s) != hipSuccess) return LORA_ERR_HIP;
+    if (HIP_FAIL(hipMemcpyAsync(&word, c->d_flags(), sizeof word, hipMemcpyDeviceToHost, s))) return LORA_ERR_HIP;
+    if (HIP_FAIL(launch_fill_i32(reinterpret_cast<int32_t*>(c->d_flags()), 0, 1, s))) return LORA_ERR_HIP;
+    if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
     if (flags) *flags = word;
     return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
 }
@@ -639,7 +652,7 @@ lora_status lora_profile_enable(lora_ctx* c, int32_t on)
         c->prof_pool.resize(8192);
         for (auto& sl : c->prof_pool) {
             sl.name = nullptr;
-            if (hipEventCreate(&sl.beg) != hipSuccess || hipEventCreate(&sl.end) != hipSuccess) return LORA_ERR_HIP;
+            if (HIP_FAIL(hipEventCreate(&sl.beg)) || HIP_FAIL(hipEventCreate(&sl.end))) return LORA_ERR_HIP;
         }
     }
     c->profiling = on != 0;
@@ -652,8 +665,8 @@ int32_t lora_profile_collect(lora_ctx* c, const char** names, double* total_ms, 
     for (size_t i = 0; i < c->prof_used; ++i) {
         ProfileSlot& sl = c->prof_pool[i];
         float ms = 0.f;
-        if (hipEventSynchronize(sl.end) != hipSuccess) continue;
-        if (hipEventElapsedTime(&ms, sl.beg, sl.end) != hipSuccess) continue;
+        if (HIP_FAIL(hipEventSynchronize(sl.end))) continue;
+        if (HIP_FAIL(hipEventElapsedTime(&ms, sl.beg, sl.end))) continue;
         size_t k = 0;
         for (; k < c->prof_names.size(); ++k)
             if (c->prof_names[k] == sl.name) break;
