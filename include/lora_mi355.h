@@ -180,6 +180,14 @@ lora_status lora_poll_device_flags(lora_ctx *ctx, uint32_t *flags, void *stream)
 int32_t lora_slot_of(const lora_ctx *ctx, int32_t adapter_id);      /* slot or -1 */
 int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter id or -1 */
 
+/* Kernel-variant selection for experiments and autotuning; value 0 is always the default variant and
+ * unknown values fall back to it.  Every variant computes the same result to the same tolerance. */
+enum {
+    LORA_TUNE_FUSED_VARIANT = 0, /* tile shape / wave layout of the fused GEMM */
+    LORA_TUNE_SPLIT_VARIANT = 1  /* tile shape / wave layout of the split-K GEMM */
+};
+lora_status lora_set_tuning(lora_ctx *ctx, int32_t key, int32_t value);
+
 /* Kernel launches made by the most recent lora_layer_forward on this context: fills up to `cap`
  * entries of names[] (static strings) and returns the count.  For benchmarks and profiling. */
 int32_t lora_last_launches(const lora_ctx *ctx, const char **names, int32_t cap);

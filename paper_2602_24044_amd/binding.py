@@ -63,8 +63,10 @@ EXPORTS = [
     "lora_slab_bytes", "lora_create", "lora_destroy", "lora_slots_load", "lora_bucket", "lora_layer_forward",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error",
+    "lora_last_hip_error", "lora_set_tuning",
 ]
+LORA_TUNE_FUSED_VARIANT = 0
+LORA_TUNE_SPLIT_VARIANT = 1
 
 
 class lora_proj_shape(ctypes.Structure):
@@ -121,6 +123,8 @@ _lib.lora_profile_reset.restype = ctypes.c_int
 _lib.lora_profile_reset.argtypes = [_P]
 _lib.lora_status_string.restype = ctypes.c_char_p
 _lib.lora_status_string.argtypes = [ctypes.c_int]
+_lib.lora_set_tuning.restype = ctypes.c_int
+_lib.lora_set_tuning.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
 _lib.lora_last_hip_error.restype = ctypes.c_char_p
 _lib.lora_last_hip_error.argtypes = []
 
@@ -229,6 +233,12 @@ def lora_slot_of(ctx: int, adapter_id: int) -> int:
 
 def lora_slot_adapter(ctx: int, slot: int) -> int:
     return int(_lib.lora_slot_adapter(_P(ctx), int(slot)))
+
+
+def lora_set_tuning(ctx: int, key: int, value: int) -> None:
+    st = _lib.lora_set_tuning(_P(ctx), int(key), int(value))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_set_tuning")
 
 
 def lora_last_launches(ctx: int) -> List[str]:

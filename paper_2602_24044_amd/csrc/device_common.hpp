@@ -1,0 +1,205 @@
+// Device-side helpers shared by the HIP kernels: vector types, the MFMA 32x32x16 bf16 lane layout,
+// the per-wavefront LoRA shrink work loop and the per-block LoRA expand.
+#pragma once
+
+#include "lora_internal.hpp"
+
+namespace lora {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline u32x4 load16(const uint16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] B[16x32].  Lane l = 32 h + i supplies A[i][8h..8h+7]
+// and B[8h..8h+7][i]; it receives D[8 g + 4 h + e][i] in register 4 g + e (g, e in 0..3).
+__device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LoRA shrink, one work item per wavefront: item = (piece, K chunk).
+//   vpart[kc][m][0:r] = sum_{k in chunk kc} x[perm[m], k] A_slot[j, k]        (paper Sec. 2.2)
+// Operands come straight from global memory in MFMA layout.  Within a 64-wide K step lane (i, h)
+// reads 64 contiguous bytes of row i at k0 + 32 h; MFMA q of the step consumes bytes [16 q, 16 q + 16)
+// of both halves.  A and x use the same assignment, so the K order inside a step is permuted
+// identically on both sides.  Two K steps are kept in flight.
+// ---------------------------------------------------------------------------------------------------
+struct ShrinkStep {
+    u32x4 x[4], a0[4], a1[4];
+};
+
+template <bool R64>
+__device__ inline void shrink_fetch(ShrinkStep& s, const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1,
+                                    bool x_ok, bool a0_ok, bool a1_ok, int k0)
+{
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        s.x[q] = x_ok ? load16(xrow + k0 + q * 8) : zero;
+        s.a0[q] = a0_ok ? load16(arow0 + k0 + q * 8) : zero;
+        if (R64) s.a1[q] = a1_ok ? load16(arow1 + k0 + q * 8) : zero;
+    }
+}
+
+template <bool R64>
+__device__ inline void shrink_mma(const ShrinkStep& s, f32x16& acc0, f32x16& acc1)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        acc0 = mfma32(as_bf16x8(s.a0[q]), as_bf16x8(s.x[q]), acc0);
+        if (R64) acc1 = mfma32(as_bf16x8(s.a1[q]), as_bf16x8(s.x[q]), acc1);
+    }
+}
+
+template <bool R64>
+__device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1, bool x_ok,
+                                    bool a0_ok, bool a1_ok, int k_begin, int k_end, f32x16& acc0, f32x16& acc1)
+{
+    ShrinkStep s0, s1;
+    shrink_fetch<R64>(s0, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin);
+    int k0 = k_begin;
+    while (true) {
+        const bool more1 = k0 + kBK < k_end;
+        if (more1) shrink_fetch<R64>(s1, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + kBK);
+        shrink_mma<R64>(s0, acc0, acc1);
+        if (!more1) break;
+        const bool more2 = k0 + 2 * kBK < k_end;
+        if (more2) shrink_fetch<R64>(s0, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + 2 * kBK);
+        shrink_mma<R64>(s1, acc0, acc1);
+        if (!more2) break;
+        k0 += 2 * kBK;
+    }
+}
+
+// Processes wave items first_item, first_item + stride, ... (all lanes of the wavefront call this
+// together; every branch on item data is wave-uniform).
+__device__ inline void shrink_wave_items(const ShrinkArgs& a, int first_item, int stride)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    const int n_items = *a.dv.n_pieces * a.n_kc;
+    const int K = a.K;
+    for (int item = first_item; item < n_items; item += stride) {
+        const int piece = item / a.n_kc;
+        const int kc = item - piece * a.n_kc;
+        const int slot = a.dv.piece_slot[piece];
+        if (slot < 0) continue;
+        const int r = a.dv.slot_rank[slot];
+        if (r <= 0) continue;
+        const int m_begin = a.dv.piece_start[piece];
+        const int nrows = a.dv.piece_start[piece + 1] - m_begin;
+        const int k_begin = kc * a.kc_len;
+        int k_end = k_begin + a.kc_len;
+        if (k_end > K) k_end = K;
+        if (k_begin >= k_end) continue;
+
+        const bool x_ok = i < nrows;
+        const uint16_t* xrow = a.x + (size_t)(x_ok ? a.dv.perm[m_begin + i] : 0) * K + h * 32;
+        const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + a.a_off;
+        const bool a0_ok = i < r, a1_ok = (32 + i) < r;
+        const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
+        const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
+
+        f32x16 acc0, acc1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+        if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+        else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+
+        // accumulator: column = grouped row m_begin + i, register 4 g + e = rank index 8 g + 4 h + e
+        if (x_ok) {
+            float* vrow = a.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + i)) * a.dv.max_rank;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j = g * 8 + h * 4;
+                if (j < r) {
+                    f32x4 o = {acc0[g * 4 + 0], acc0[g * 4 + 1], acc0[g * 4 + 2], acc0[g * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(vrow + j) = o;
+                }
+            }
+            if (r > 32) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int j = 32 + g * 8 + h * 4;
+                    if (j < r) {
+                        f32x4 o = {acc1[g * 4 + 0], acc1[g * 4 + 1], acc1[g * 4 + 2], acc1[g * 4 + 3]};
+                        *reinterpret_cast<f32x4*>(vrow + j) = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LoRA expand for one 32-row window of grouped rows (paper Sec. 2.2: the second low-rank matrix maps
+// the adapter's activations back to the layer output, where they are added to the backbone result).
+// acc[nb] is a 32x32 accumulator block in "W-first" orientation: lane (i, h) holds grouped row
+// m = window + i (the block's column) and output columns n_first + 32 nb + 8 g + 4 h + e in register
+// 4 g + e.  For every distinct slot among the window's rows, that slot's B rows and the rows' scaled
+// shrink results (rounded to bf16) are fed as extra K steps of 16.
+//   VS: functor (k, mine) -> bf16x8 with the lane's scaled v[m][k .. k+7] (zeros when !mine).
+// ---------------------------------------------------------------------------------------------------
+template <int NB, typename VS>
+__device__ inline void expand_window(f32x16 (&acc)[NB], int my_slot, int n_first, int N, const DeviceView& dv,
+                                     size_t b_off, VS&& vfrag)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    unsigned long long todo = __ballot(my_slot >= 0);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int s = __shfl(my_slot, leader, kWave);
+        todo &= ~__ballot(my_slot == s);
+        const int r = dv.slot_rank[s];
+        if (r <= 0) continue;
+        const float sc = dv.slot_scale[s];
+        const uint16_t* Bs = dv.slots + (size_t)s * dv.slot_stride + b_off;
+        const bool mine = (my_slot == s);
+        for (int kq = 0; kq < r; kq += 16) {
+            const int k = kq + h * 8;
+            const bool k_ok = k < r;
+            const bf16x8 vf = vfrag(k, mine && k_ok, sc);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int n = n_first + nb * 32 + i;
+                u32x4 bv = {0u, 0u, 0u, 0u};
+                if (k_ok && n < N) bv = load16(Bs + (size_t)n * r + k);
+                acc[nb] = mfma32(as_bf16x8(bv), vf, acc[nb]);
+            }
+        }
+    }
+}
+
+// v fragment straight from the shrink partials in global memory: sums the K chunks, scales, rounds.
+struct VFromGlobal {
+    const float* vpart;
+    int n_kc, T, max_rank, m;
+    __device__ inline bf16x8 operator()(int k, bool on, float sc) const
+    {
+        f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+        if (on) {
+            for (int c = 0; c < n_kc; ++c) {
+                const float* vp = vpart + ((size_t)c * T + m) * max_rank + k;
+                lo += *reinterpret_cast<const f32x4*>(vp);
+                hi += *reinterpret_cast<const f32x4*>(vp + 4);
+            }
+        }
+        bf16x8 vf;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            vf[e] = (__bf16)(lo[e] * sc);
+            vf[4 + e] = (__bf16)(hi[e] * sc);
+        }
+        return vf;
+    }
+};
+
+}  // namespace lora

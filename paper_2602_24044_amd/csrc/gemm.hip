@@ -1,50 +1,61 @@
-// Base projection x W^T on the bf16 matrix cores with the LoRA expand folded into the epilogue
-// (paper Sec. 2.2: the adapter's activations are added to the backbone layer's output; Sec. 1: the
-// backbone is shared, adapters stay unmerged).
+// Base projection x W^T on the bf16 matrix cores (paper Sec. 2.2: the adapter's activations are added
+// to the backbone layer's output; Sec. 1: the backbone is shared, adapters stay unmerged).
 //
 // Rows of the GEMM are grouped positions m (token perm[m]); x rows are gathered through perm when the
 // tile is staged and output rows are scattered back through it, so `out` is in token order.
 //
-// Tiling: BM x BN output tile per workgroup, K walked in 64-wide LDS tiles, double buffered; the next
-// tile is fetched into registers while the current one feeds the MFMAs.  LDS rows are 128 bytes
-// (8 chunks of 16 bytes); chunk c of row rr is stored at position c ^ (rr & 7), which makes both the
-// 16-byte row-major writes and the MFMA-layout reads (32 rows x one chunk) bank-conflict free.
+// Tiling: BM x BN output tile per workgroup, K walked in 64-wide tiles through two LDS stages.  Tiles
+// are copied global -> LDS directly (global_load_lds, 16 bytes per lane, no staging registers and no
+// LDS store instructions): one wave instruction fills 1 KB = 8 LDS rows of 128 bytes.  Chunk c (16
+// bytes) of row rr is kept at position c ^ (rr & 7); because the copy engine places lane l at byte
+// 16 l of the wave's 1 KB, the swizzle is applied on the global side (lane l fetches the chunk that
+// belongs at its position).  The MFMA-layout reads (32 rows x one chunk) are then bank-conflict free.
+// The copy of tile j + 2 is issued as soon as every wave has finished reading tile j and is in
+// flight during the whole of tile j + 1 (see the main loop for the schedule).
 //
 // MFMA 32x32x16 bf16 with W as the first operand and x as the second: the accumulator of a lane then
 // holds one grouped row m (its column index) and, per group of four registers, four consecutive
 // output columns n, so results leave as 8-byte (bf16) or 16-byte (fp32) stores.
 //
-// FUSED: K is walked in full; then for every distinct slot among the 32 rows of an accumulator block
-// the shrink result v (scaled, rounded to bf16) and that slot's B rows are fed as extra K steps
-// straight from global memory in MFMA layout; result is rounded once to bf16.
-// SPLITK: blockIdx selects a K range; fp32 partial tiles are written for the reduce + expand kernel.
-#include "lora_internal.hpp"
+// FUSED: K is walked in full; the LoRA expand runs on the accumulators (expand_window) and the result
+//        is rounded once to bf16.
+// SPLITK: blockIdx selects a K range; fp32 partial tiles go to the reduce + expand kernel.  After its
+//        tile, every workgroup takes a share of the LoRA shrink work items of the same projection, so
+//        shrink and base GEMM share one launch.
+#include "device_common.hpp"
+
+#include <type_traits>
+#include <utility>
 
 namespace lora {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+template <typename F, int... Is>
+__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ inline void static_for(F&& f)
+{
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
-__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-template <int BM, int BN, int WGM, int WGN, bool FUSED>
-__global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a)
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int D>
+__global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
 {
     constexpr int NT = WGM * WGN * kWave;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wave tile
     constexpr int MB = WTM / 32, NB = WTN / 32;     // 32x32 accumulator blocks per wave
     constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;  // 16-byte chunks per thread per tile
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads");
-    static_assert(NT % 8 == 0, "threads");
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* sX = smem;                       // [2][BM*64]
-    uint16_t* sW = smem + 2 * BM * kBK;        // [2][BN*64]
+    // one static array per stage and operand: distinct objects let the compiler keep copies into one
+    // stage in flight while the other stage is being read
+    __shared__ __attribute__((aligned(1024))) uint16_t sX0[BM * kBK];
+    __shared__ __attribute__((aligned(1024))) uint16_t sX1[BM * kBK];
+    __shared__ __attribute__((aligned(1024))) uint16_t sW0[BN * kBK];
+    __shared__ __attribute__((aligned(1024))) uint16_t sW1[BN * kBK];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
@@ -72,86 +83,115 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a)
         kt_begin = (int)((long long)kt_total * split / a.split_k);
         kt_end = (int)((long long)kt_total * (split + 1) / a.split_k);
     }
+    const int nk = kt_end - kt_begin;
 
-    // global source rows for the staging loads (clamped: rows past T or N are computed, never stored)
-    const int ld_chunk = tid & 7, ld_row = tid >> 3;
-    const uint16_t* xsrc[XCH];
-    const uint16_t* wsrc[WCH];
+    // Copy assignment: wave instruction q of wave w fills LDS rows 8 (w XQ + q) .. + 7 of the X tile
+    // (same for W with WQ); lane l owns row l / 8 of those and chunk position l % 8.  Rows past T or N are
+    // clamped to the last valid row: they are computed, never stored.
+    constexpr int NWV = NT / kWave;
+    constexpr int XQ = BM / 8 / NWV, WQ = BN / 8 / NWV;     // wave instructions per stage
+    static_assert(BM % (8 * NWV) == 0 && BN % (8 * NWV) == 0, "tile/waves");
+    const int cp_row = lane >> 3;
+    const int cp_chunk = (lane & 7) ^ cp_row;               // (row & 7) == cp_row: row blocks start at multiples of 8
+    uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes at k = 0
 #pragma unroll
-    for (int q = 0; q < XCH; ++q) {
-        int m = m0 + ld_row + q * (NT / 8);
+    for (int q = 0; q < XQ; ++q) {
+        int m = m0 + (wave * XQ + q) * 8 + cp_row;
         if (m > T - 1) m = T - 1;
-        xsrc[q] = a.x + (size_t)a.dv.perm[m] * K + ld_chunk * 8;
+        xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kBK);
     }
 #pragma unroll
-    for (int q = 0; q < WCH; ++q) {
-        int n = n0 + ld_row + q * (NT / 8);
+    for (int q = 0; q < WQ; ++q) {
+        int n = n0 + (wave * WQ + q) * 8 + cp_row;
         if (n > N - 1) n = N - 1;
-        wsrc[q] = a.W + (size_t)n * K + ld_chunk * 8;
+        woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kBK);
     }
 
-    f32x16 acc[NB][MB];
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    // ---- software-pipelined main loop ----
+    // State at the top of iteration j: tile j is complete in stage j & 1, the fragments of its first K
+    // step are in F[0], and the copy of tile j + 1 into the other stage is in flight.  Each K step issues
+    // the LDS reads of the following step before its own MFMAs.  The single barrier of the iteration
+    // sits between K step 2 and 3: every wave has then read all of tile j (its last fragments are in
+    // registers) and its own share of tile j + 1 has landed, so after the barrier tile j + 1 is complete
+    // for everyone and stage j & 1 is free: the copy of tile j + 2 starts there, the first fragments of
+    // tile j + 1 are read, and the MFMAs of step 3 cover the barrier skew and the LDS latency.
+    bf16x8 Fw[2][NB], Fx[2][MB];
+    auto copy_tile = [&](auto st_c, int j) {
+        constexpr int ST = decltype(st_c)::value;
+        uint16_t* dx = ST ? sX1 : sX0;
+        uint16_t* dw = ST ? sW1 : sW0;
+        const uint32_t k0 = (uint32_t)j * kBK;
+#pragma unroll
+        for (int q = 0; q < XQ; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(a.x + (xoff[q] + k0)),
+                (__attribute__((address_space(3))) void*)(dx + (wave * XQ + q) * 512), 16, 0, 0);
+#pragma unroll
+        for (int q = 0; q < WQ; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(a.W + (woff[q] + k0)),
+                (__attribute__((address_space(3))) void*)(dw + (wave * WQ + q) * 512), 16, 0, 0);
+    };
+    auto read_frags = [&](auto f_c, auto st_c, int kk) {
+        constexpr int Fi = decltype(f_c)::value;
+        constexpr int ST = decltype(st_c)::value;
+        const uint16_t* bx = ST ? sX1 : sX0;
+        const uint16_t* bw = ST ? sW1 : sW0;
+        const int c = kk * 2 + h;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int rr = wn * WTN + nb * 32 + i;
+            Fw[Fi][nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bw + (rr * 8 + (c ^ (rr & 7))) * 8));
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int rr = wm * WTM + mb * 32 + i;
+            Fx[Fi][mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bx + (rr * 8 + (c ^ (rr & 7))) * 8));
+        }
+    };
+    auto mma = [&](auto f_c) {
+        constexpr int Fi = decltype(f_c)::value;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
-
-    u32x4 xr[XCH], wr[WCH];
-    auto fetch = [&](int kt) {
-        const int k0 = kt * kBK;
-#pragma unroll
-        for (int q = 0; q < XCH; ++q) xr[q] = *reinterpret_cast<const u32x4*>(xsrc[q] + k0);
-#pragma unroll
-        for (int q = 0; q < WCH; ++q) wr[q] = *reinterpret_cast<const u32x4*>(wsrc[q] + k0);
+            for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(Fw[Fi][nb], Fx[Fi][mb], acc[mb][nb]);
     };
-    auto stage = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < XCH; ++q) {
-            const int rr = ld_row + q * (NT / 8);
-            *reinterpret_cast<u32x4*>(sX + buf * BM * kBK + (rr * 8 + (ld_chunk ^ (rr & 7))) * 8) = xr[q];
-        }
-#pragma unroll
-        for (int q = 0; q < WCH; ++q) {
-            const int rr = ld_row + q * (NT / 8);
-            *reinterpret_cast<u32x4*>(sW + buf * BN * kBK + (rr * 8 + (ld_chunk ^ (rr & 7))) * 8) = wr[q];
-        }
-    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
 
-    if (kt_begin < kt_end) {
-        fetch(kt_begin);
-        stage(0);
-    }
-    __syncthreads();
-
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        const int buf = (kt - kt_begin) & 1;
-        if (kt + 1 < kt_end) fetch(kt + 1);
-        const uint16_t* bx = sX + buf * BM * kBK;
-        const uint16_t* bw = sW + buf * BN * kBK;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int c = kk * 2 + h;
-            bf16x8 wf[NB], xf[MB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int rr = wn * WTN + nb * 32 + i;
-                wf[nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bw + (rr * 8 + (c ^ (rr & 7))) * 8));
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int rr = wm * WTM + mb * 32 + i;
-                xf[mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bx + (rr * 8 + (c ^ (rr & 7))) * 8));
-            }
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
-        }
-        if (kt + 1 < kt_end) stage(buf ^ 1);
+    auto iteration = [&](auto par_c, int j) {
+        constexpr int PAR = decltype(par_c)::value;
+        using Cur = std::integral_constant<int, PAR>;
+        using Oth = std::integral_constant<int, PAR ^ 1>;
+        read_frags(I1{}, Cur{}, 1);
+        mma(I0{});
+        read_frags(I0{}, Cur{}, 2);
+        mma(I1{});
+        read_frags(I1{}, Cur{}, 3);
+        mma(I0{});
         __syncthreads();
+        if (j + 2 < nk) copy_tile(Cur{}, j + 2);
+        if (j + 1 < nk) read_frags(I0{}, Oth{}, 0);
+        mma(I1{});
+    };
+
+    if (nk > 0) {
+        copy_tile(I0{}, 0);
+        __syncthreads();
+        if (nk > 1) copy_tile(I1{}, 1);
+        read_frags(I0{}, I0{}, 0);
+    }
+    for (int j = 0; j < nk; j += 2) {
+        iteration(I0{}, j);
+        if (j + 1 < nk) iteration(I1{}, j + 1);
     }
 
     // ---------------- epilogue ----------------
@@ -159,49 +199,12 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a)
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m0 + wm * WTM + mb * 32 + i;      // grouped row of this lane
         const bool m_ok = m < T;
+        const int n_first = n0 + wn * WTN;
 
         if (FUSED) {
             const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
-            unsigned long long todo = __ballot(my_slot >= 0);
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const int s = __shfl(my_slot, leader, kWave);
-                const unsigned long long peers = __ballot(my_slot == s);
-                todo &= ~peers;
-                const int r = a.dv.slot_rank[s];
-                if (r <= 0) continue;
-                const float sc = a.dv.slot_scale[s];
-                const uint16_t* Bs = a.dv.slots + (size_t)s * a.dv.slot_stride + a.b_off;
-                const bool mine = (my_slot == s);
-                for (int kq = 0; kq < r; kq += 16) {
-                    const int k = kq + h * 8;
-                    const bool k_ok = k < r;
-                    // second operand: scaled shrink output of this lane's row, rounded to bf16
-                    bf16x8 vf;
-                    {
-                        f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-                        if (mine && k_ok) {
-                            for (int c = 0; c < a.n_kc; ++c) {
-                                const float* vp = a.vpart + ((size_t)c * T + m) * a.dv.max_rank + k;
-                                lo += *reinterpret_cast<const f32x4*>(vp);
-                                hi += *reinterpret_cast<const f32x4*>(vp + 4);
-                            }
-                        }
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            vf[e] = (__bf16)(lo[e] * sc);
-                            vf[4 + e] = (__bf16)(hi[e] * sc);
-                        }
-                    }
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const int n = n0 + wn * WTN + nb * 32 + i;
-                        u32x4 bv = {0u, 0u, 0u, 0u};
-                        if (k_ok && n < N) bv = *reinterpret_cast<const u32x4*>(Bs + (size_t)n * r + k);
-                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(bv), vf, acc[nb][mb], 0, 0, 0);
-                    }
-                }
-            }
+            VFromGlobal vs{a.vpart, a.n_kc, T, a.dv.max_rank, m};
+            expand_window<NB>(acc[mb], my_slot, n_first, N, a.dv, a.b_off, vs);
         }
 
         if (m_ok) {
@@ -211,11 +214,11 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a)
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int n = n0 + wn * WTN + nb * 32 + g * 8 + h * 4;
+                        const int n = n_first + nb * 32 + g * 8 + h * 4;
                         if (n < N) {
                             bf16x4 o;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[nb][mb][g * 4 + e];
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[mb][nb][g * 4 + e];
                             *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
                         }
                     }
@@ -225,56 +228,82 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a)
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int n = n0 + wn * WTN + nb * 32 + g * 8 + h * 4;
+                        const int n = n_first + nb * 32 + g * 8 + h * 4;
                         if (n < N) {
-                            f32x4 o = {acc[nb][mb][g * 4 + 0], acc[nb][mb][g * 4 + 1], acc[nb][mb][g * 4 + 2],
-                                       acc[nb][mb][g * 4 + 3]};
+                            f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
+                                       acc[mb][nb][g * 4 + 3]};
                             *reinterpret_cast<f32x4*>(prow + n) = o;
                         }
                     }
             }
         }
     }
+
+    // split path: this workgroup's share of the shrink work items of the same projection
+    if (!FUSED && sa.vpart != nullptr) {
+        constexpr int waves = NT / kWave;
+        shrink_wave_items(sa, blockIdx.x * waves + wave, gridDim.x * waves);
+    }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED>
-hipError_t launch_one(const GemmArgs& a, hipStream_t stream)
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int D>
+hipError_t launch_one(const GemmArgs& a, const ShrinkArgs& sa, hipStream_t stream)
 {
     constexpr int NT = WGM * WGN * kWave;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(uint16_t);
-    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, D>;
     const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), lds, stream, a);
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), 0, stream, a, sa);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gemm_fused(const GemmArgs& a0, hipStream_t stream, const char** name)
+hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream, const char** name)
 {
     GemmArgs a = a0;
-    constexpr int BM = 256, BN = 256;
-    a.tiles_m = (a.dv.T + BM - 1) / BM;
-    a.tiles_n = (a.N + BN - 1) / BN;
-    *name = "gemm_fused_256x256";
-    return launch_one<BM, BN, 2, 4, true>(a, stream);
+    ShrinkArgs none{};
+    auto tiles = [&](int BM, int BN) {
+        a.tiles_m = (a.dv.T + BM - 1) / BM;
+        a.tiles_n = (a.N + BN - 1) / BN;
+    };
+    switch (variant) {
+        case 1:
+            tiles(256, 256);
+            *name = "gemm_fused_256x256_w4";
+            return launch_one<256, 256, 2, 2, true, 1>(a, none, stream);
+        case 2:
+            tiles(256, 256);
+            *name = "gemm_fused_256x256_w4_d2";
+            return launch_one<256, 256, 2, 2, true, 2>(a, none, stream);
+        case 3:
+            tiles(128, 128);
+            *name = "gemm_fused_128x128_w4_d3";
+            return launch_one<128, 128, 2, 2, true, 3>(a, none, stream);
+        default:
+            tiles(256, 256);
+            *name = "gemm_fused_256x256_w8";
+            return launch_one<256, 256, 2, 4, true, 1>(a, none, stream);
+    }
 }
 
-hipError_t launch_gemm_splitk(const GemmArgs& a0, hipStream_t stream, const char** name)
+hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int variant, hipStream_t stream,
+                              const char** name)
 {
     GemmArgs a = a0;
-    constexpr int BM = 256, BN = 128;
-    a.tiles_m = (a.dv.T + BM - 1) / BM;
-    a.tiles_n = (a.N + BN - 1) / BN;
-    *name = "gemm_splitk_256x128";
-    return launch_one<BM, BN, 4, 2, false>(a, stream);
+    auto tiles = [&](int BM, int BN) {
+        a.tiles_m = (a.dv.T + BM - 1) / BM;
+        a.tiles_n = (a.N + BN - 1) / BN;
+    };
+    switch (variant) {
+        case 1:
+            tiles(256, 128);
+            *name = "gemm_splitk_shrink_256x128_w4";
+            return launch_one<256, 128, 2, 2, false, 2>(a, sa, stream);
+        default:
+            tiles(256, 128);
+            *name = "gemm_splitk_shrink_256x128_w8";
+            return launch_one<256, 128, 4, 2, false, 3>(a, sa, stream);
+    }
 }
 
 }  // namespace lora

@@ -136,6 +136,8 @@ struct lora_ctx {
     hipStream_t last_fwd_stream = nullptr;
     bool have_fwd = false;
 
+    int32_t tune[8] = {0};
+
     // current segment map
     uint64_t epoch = 0;
     int32_t seg_T = -1, seg_mode = 0;
@@ -557,24 +559,16 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     float* vpart = c->dev<float>(c->L.off_vpart);
     float* part = c->dev<float>(c->L.off_part);
 
-    // ---- shrink ----
-    if (c->n_resident > 0) {
-        ShrinkArgs sa;
-        sa.dv = dv;
-        sa.x = static_cast<const uint16_t*>(d_x);
-        sa.K = K;
-        sa.a_off = c->L.a_off[p];
-        sa.n_kc = n_kc;
-        sa.kc_len = kc_len;
-        sa.vpart = vpart;
-        const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
-        const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
-        const int grid = (int)std::max<long>(1, std::min<long>((items + 3) / 4, 2048));
-        LaunchScope ls(c, s, "shrink");
-        if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
-    }
+    ShrinkArgs sa;
+    std::memset(&sa, 0, sizeof sa);
+    sa.dv = dv;
+    sa.x = static_cast<const uint16_t*>(d_x);
+    sa.K = K;
+    sa.a_off = c->L.a_off[p];
+    sa.n_kc = n_kc;
+    sa.kc_len = kc_len;
+    sa.vpart = c->n_resident > 0 ? vpart : nullptr;   // no adapter resident: nothing to shrink
 
-    // ---- base GEMM (+ expand) ----
     GemmArgs ga;
     ga.dv = dv;
     ga.x = static_cast<const uint16_t*>(d_x);
@@ -589,16 +583,26 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     ga.out = static_cast<uint16_t*>(d_out);
     ga.part = part;
     ga.Mpad = Mpad;
+
     if (!split) {
+        // ---- shrink, then base GEMM with the expand in its epilogue ----
+        if (sa.vpart) {
+            const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
+            const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
+            const int grid = (int)std::max<long>(1, std::min<long>((items + 3) / 4, 2048));
+            LaunchScope ls(c, s, "shrink");
+            if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
+        }
         LaunchScope ls(c, s, "gemm_fused");
         const char* name = nullptr;
-        if (HIP_FAIL(launch_gemm_fused(ga, s, &name))) return LORA_ERR_HIP;
+        if (HIP_FAIL(launch_gemm_fused(ga, c->tune[LORA_TUNE_FUSED_VARIANT], s, &name))) return LORA_ERR_HIP;
         ls.rename(name);
     } else {
+        // ---- split-K base GEMM + shrink in one launch, then reduce + expand ----
         {
             LaunchScope ls(c, s, "gemm_splitk");
             const char* name = nullptr;
-            if (HIP_FAIL(launch_gemm_splitk(ga, s, &name))) return LORA_ERR_HIP;
+            if (HIP_FAIL(launch_gemm_splitk(ga, sa, c->tune[LORA_TUNE_SPLIT_VARIANT], s, &name))) return LORA_ERR_HIP;
             ls.rename(name);
         }
         ReduceArgs ra;
@@ -611,10 +615,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         ra.n_kc = n_kc;
         ra.b_off = c->L.b_off[p];
         ra.out = static_cast<uint16_t*>(d_out);
-        ra.n_chunks = (N + 1023) / 1024;
-        const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
-        const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * ra.n_chunks;
-        const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
+        const int grid = ((T + kPieceRows - 1) / kPieceRows) * ((N + 127) / 128);
         LaunchScope ls(c, s, "reduce_expand");
         if (HIP_FAIL(launch_reduce_expand(ra, grid, s))) return LORA_ERR_HIP;
     }
@@ -634,6 +635,13 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
     if (flags) *flags = word;
     return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
+}
+
+lora_status lora_set_tuning(lora_ctx* c, int32_t key, int32_t value)
+{
+    if (!c || key < 0 || key >= 8) return LORA_ERR_INVALID_ARG;
+    c->tune[key] = value;
+    return LORA_OK;
 }
 
 int32_t lora_last_launches(const lora_ctx* c, const char** names, int32_t cap)

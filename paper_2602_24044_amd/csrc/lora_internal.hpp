@@ -98,7 +98,6 @@ struct ReduceArgs {
     int32_t n_kc;
     size_t b_off;
     uint16_t* out;       // [T, N] bf16
-    int32_t n_chunks;    // column chunks of 1024
 };
 
 // launchers (defined next to their kernels); every launch is asynchronous on `stream`
@@ -107,8 +106,8 @@ hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* s
                               hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stream);
 hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);
-hipError_t launch_gemm_fused(const GemmArgs& a, hipStream_t stream, const char** name);
-hipError_t launch_gemm_splitk(const GemmArgs& a, hipStream_t stream, const char** name);
+hipError_t launch_gemm_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
+hipError_t launch_gemm_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 hipError_t launch_reduce_expand(const ReduceArgs& a, int grid, hipStream_t stream);
 
 }  // namespace lora

@@ -1,113 +1,112 @@
 // Split-K reduction fused with the LoRA expand and the output rounding:
-//   out[perm[m], n] = bf16( sum_s part[s][m][n] + scale * sum_j v[m][j] B_slot[n][j] )
+//   out[perm[m], n] = bf16( sum_s part[s][m][n] + scale * sum_j v[m][j] B_slot(m)[n][j] )
 // (paper Sec. 2.2: the second low-rank matrix maps the adapter's activations back to the layer's
 // output, where they are added to the backbone result).
 //
-// Memory-bound.  A work item is (piece, 1024-column chunk): the piece's rows all use one slot, so the
-// chunk of B is read once per piece, 16 bytes per lane and contiguous across lanes; v (summed over
-// the shrink's K chunks and scaled, fp32) is staged in LDS and broadcast.
-#include "lora_internal.hpp"
+// Memory-bound.  One workgroup of four wavefronts owns a 32-row window of grouped rows and 128 output
+// columns.  The window's shrink results are summed over the shrink's K chunks, scaled, rounded to bf16
+// and parked in LDS once; each wavefront then sums the fp32 partial tiles of its 32 columns directly
+// in MFMA accumulator layout and runs the expand as extra MFMA K steps, one pass per distinct slot in
+// the window, reading that slot's B rows once.
+#include "device_common.hpp"
 
 namespace lora {
 namespace {
 
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-
-constexpr int kRT = 256;          // threads
-constexpr int kCols = kRT * 4;    // columns per work item
-constexpr int kRowGroup = 8;
-
-__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+constexpr int kRT = 256;
+constexpr int kVStride = kMaxRank + 8;   // bf16 elements per LDS row: 144 bytes, conflict-free 16-byte reads
 
 __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float sV[kPieceRows][kMaxRank];
-    const int tid = threadIdx.x;
+    __shared__ __attribute__((aligned(16))) uint16_t sV[kPieceRows * kVStride];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, h = lane >> 5;
     const int T = a.dv.T, N = a.N;
-    const int n_pieces = *a.dv.n_pieces;
-    const int n_items = n_pieces * a.n_chunks;
+    const int n_win = (T + kPieceRows - 1) / kPieceRows;
+    const int win = blockIdx.x % n_win, group = blockIdx.x / n_win;
+    const int m = win * kPieceRows + i;
+    const bool m_ok = m < T;
+    const int n_first = group * 128 + wave * 32;
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int piece = item / a.n_chunks;
-        const int chunk = item - piece * a.n_chunks;
-        const int slot = a.dv.piece_slot[piece];
-        const int r = slot >= 0 ? a.dv.slot_rank[slot] : 0;
-        const int m_begin = a.dv.piece_start[piece];
-        const int nrows = a.dv.piece_start[piece + 1] - m_begin;
-        const int n = chunk * kCols + tid * 4;
-        const bool n_ok = n < N;
-
-        if (r > 0) {
-            const float sc = a.dv.slot_scale[slot];
-            for (int e = tid; e < nrows * r; e += kRT) {
-                const int row = e / r, j = e - row * r;
-                float s = 0.f;
-                for (int c = 0; c < a.n_kc; ++c)
-                    s += a.vpart[((size_t)c * T + (m_begin + row)) * a.dv.max_rank + j];
-                sV[row][j] = s * sc;
-            }
-        }
-        __syncthreads();
-
-        const uint16_t* Bs = a.dv.slots + (size_t)(slot >= 0 ? slot : 0) * a.dv.slot_stride + a.b_off
-                             + (size_t)n * r;
-        for (int row0 = 0; row0 < nrows; row0 += kRowGroup) {
-            const int nr = (nrows - row0) < kRowGroup ? (nrows - row0) : kRowGroup;
-            f32x4 acc[kRowGroup];
+    // partial sums first: the loads are independent of the LDS staging below
+    f32x16 acc[1];
 #pragma unroll
-            for (int rr = 0; rr < kRowGroup; ++rr) {
-                acc[rr] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (rr < nr && n_ok) {
-                    const size_t m = (size_t)(m_begin + row0 + rr);
-                    for (int s = 0; s < a.split_k; ++s)
-                        acc[rr] += *reinterpret_cast<const f32x4*>(a.part + ((size_t)s * a.Mpad + m) * N + n);
+    for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
+    if (m_ok) {
+        // four splits (16 independent 16-byte loads per lane) in flight at a time
+        for (int s0 = 0; s0 < a.split_k; s0 += 4) {
+            f32x4 p[4][4];
+#pragma unroll
+            for (int ds = 0; ds < 4; ++ds) {
+                const int s = (s0 + ds < a.split_k) ? s0 + ds : s0;
+                const float* prow = a.part + ((size_t)s * a.Mpad + m) * N;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n_first + g * 8 + h * 4;
+                    p[ds][g] = (n < N) ? *reinterpret_cast<const f32x4*>(prow + n) : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
             }
-            if (r > 0 && n_ok) {
-                for (int jc = 0; jc < r; jc += 8) {
-                    u32x4 b[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) b[q] = *reinterpret_cast<const u32x4*>(Bs + (size_t)q * r + jc);
+            for (int ds = 0; ds < 4; ++ds) {
+                if (s0 + ds < a.split_k) {
 #pragma unroll
-                    for (int rr = 0; rr < kRowGroup; ++rr) {
-                        if (rr < nr) {
-                            const f32x4 v0 = *reinterpret_cast<const f32x4*>(&sV[row0 + rr][jc]);
-                            const f32x4 v1 = *reinterpret_cast<const f32x4*>(&sV[row0 + rr][jc + 4]);
+                    for (int g = 0; g < 4; ++g)
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                float d = acc[rr][q];
-                                d += v0[0] * bf16_lo(b[q][0]);
-                                d += v0[1] * bf16_hi(b[q][0]);
-                                d += v0[2] * bf16_lo(b[q][1]);
-                                d += v0[3] * bf16_hi(b[q][1]);
-                                d += v1[0] * bf16_lo(b[q][2]);
-                                d += v1[1] * bf16_hi(b[q][2]);
-                                d += v1[2] * bf16_lo(b[q][3]);
-                                d += v1[3] * bf16_hi(b[q][3]);
-                                acc[rr][q] = d;
-                            }
-                        }
-                    }
-                }
-            }
-            if (n_ok) {
-#pragma unroll
-                for (int rr = 0; rr < kRowGroup; ++rr) {
-                    if (rr < nr) {
-                        const int tok = a.dv.perm[m_begin + row0 + rr];
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[rr][e];
-                        *reinterpret_cast<u32x2*>(a.out + (size_t)tok * N + n) = __builtin_bit_cast(u32x2, o);
-                    }
+                        for (int e = 0; e < 4; ++e) acc[0][g * 4 + e] += p[ds][g][e];
                 }
             }
         }
-        __syncthreads();
+    }
+
+    // stage the window's scaled shrink results: thread -> (row, 8 ranks)
+    {
+        const int row = tid >> 3, seg = tid & 7;
+        const int mr = win * kPieceRows + row;
+        u32x4 packed = {0u, 0u, 0u, 0u};
+        if (mr < T && seg * 8 < a.dv.max_rank) {
+            const int slot = a.dv.row_slot[mr];
+            const int r = slot >= 0 ? a.dv.slot_rank[slot] : 0;
+            if (seg * 8 < r) {
+                const float sc = a.dv.slot_scale[slot];
+                f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < a.n_kc; ++c) {
+                    const float* vp = a.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
+                    lo += *reinterpret_cast<const f32x4*>(vp);
+                    hi += *reinterpret_cast<const f32x4*>(vp + 4);
+                }
+                bf16x8 vb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vb[e] = (__bf16)(lo[e] * sc);
+                    vb[4 + e] = (__bf16)(hi[e] * sc);
+                }
+                packed = __builtin_bit_cast(u32x4, vb);
+            }
+        }
+        *reinterpret_cast<u32x4*>(sV + row * kVStride + seg * 8) = packed;
+    }
+    __syncthreads();
+
+    const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
+    auto vfrag = [&](int k, bool on, float) -> bf16x8 {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStride + k);
+        return as_bf16x8(v);
+    };
+    expand_window<1>(acc, my_slot, n_first, N, a.dv, a.b_off, vfrag);
+
+    if (m_ok) {
+        uint16_t* orow = a.out + (size_t)a.dv.perm[m] * N;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n_first + g * 8 + h * 4;
+            if (n < N) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[0][g * 4 + e];
+                *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
+            }
+        }
     }
 }
 
