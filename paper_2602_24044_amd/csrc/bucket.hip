@@ -147,6 +147,13 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     }
     __syncthreads();
 
+    // per-row adapter metadata, so that the projection kernels never chase slot -> rank / scale
+    for (int m = tid; m < T; m += kBT) {
+        const int s = a.row_slot[m];
+        a.row_rank[m] = s >= 0 ? a.slot_rank[s] : 0;
+        a.row_scale[m] = s >= 0 ? a.slot_scale[s] : 0.f;
+    }
+
     rle(a.row_slot, T, 0, a.seg_start, a.seg_slot, a.n_seg, s_wave);
     rle(a.row_slot, T, kPieceRows, a.piece_start, a.piece_slot, a.n_pieces, s_wave);
 }

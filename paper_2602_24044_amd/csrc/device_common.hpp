@@ -78,11 +78,18 @@ __device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0,
     }
 }
 
-// Processes wave items first_item, first_item + stride, ... (all lanes of the wavefront call this
-// together; every branch on item data is wave-uniform).
-__device__ inline void shrink_wave_items(const ShrinkArgs& a, int first_item, int stride)
+constexpr int kRedStride = 36;   // floats per LDS row of the cross-wave reduction (144 bytes: conflict-free)
+constexpr int kRedFloatsPerWave = kPieceRows * kRedStride;
+
+// Processes work items first_item, first_item + stride, ... with the whole workgroup of NW wavefronts:
+// the waves split the item's K chunk between them, then the NW partial 32 x r blocks are summed
+// through LDS (sRed: NW * kRedFloatsPerWave floats) and written as one partial result per chunk.
+// Every branch on item data is uniform over the workgroup.
+template <int NW>
+__device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, int stride, float* sRed)
 {
-    const int lane = threadIdx.x & (kWave - 1);
+    constexpr int NT = NW * kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
     const int n_items = *a.dv.n_pieces * a.n_kc;
     const int K = a.K;
@@ -91,14 +98,18 @@ __device__ inline void shrink_wave_items(const ShrinkArgs& a, int first_item, in
         const int kc = item - piece * a.n_kc;
         const int slot = a.dv.piece_slot[piece];
         if (slot < 0) continue;
-        const int r = a.dv.slot_rank[slot];
-        if (r <= 0) continue;
         const int m_begin = a.dv.piece_start[piece];
+        const int r = a.dv.row_rank[m_begin];
+        if (r <= 0) continue;
         const int nrows = a.dv.piece_start[piece + 1] - m_begin;
-        const int k_begin = kc * a.kc_len;
-        int k_end = k_begin + a.kc_len;
-        if (k_end > K) k_end = K;
-        if (k_begin >= k_end) continue;
+        const int c_begin = kc * a.kc_len;
+        int c_end = c_begin + a.kc_len;
+        if (c_end > K) c_end = K;
+        const int steps = (c_end - c_begin) / kBK;
+        const int per_wave = (steps + NW - 1) / NW;
+        const int k_begin = c_begin + wave * per_wave * kBK;
+        int k_end = k_begin + per_wave * kBK;
+        if (k_end > c_end) k_end = c_end;
 
         const bool x_ok = i < nrows;
         const uint16_t* xrow = a.x + (size_t)(x_ok ? a.dv.perm[m_begin + i] : 0) * K + h * 32;
@@ -110,30 +121,34 @@ __device__ inline void shrink_wave_items(const ShrinkArgs& a, int first_item, in
         f32x16 acc0, acc1;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
-        if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
-        else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+        if (k_begin < k_end) {
+            if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+            else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+        }
 
         // accumulator: column = grouped row m_begin + i, register 4 g + e = rank index 8 g + 4 h + e
-        if (x_ok) {
-            float* vrow = a.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + i)) * a.dv.max_rank;
+        const int halves = r > 32 ? 2 : 1;
+        for (int half = 0; half < halves; ++half) {
+            float* mine = sRed + wave * kRedFloatsPerWave + i * kRedStride;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int j = g * 8 + h * 4;
-                if (j < r) {
-                    f32x4 o = {acc0[g * 4 + 0], acc0[g * 4 + 1], acc0[g * 4 + 2], acc0[g * 4 + 3]};
-                    *reinterpret_cast<f32x4*>(vrow + j) = o;
-                }
-            }
-            if (r > 32) {
+                f32x4 o;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int j = 32 + g * 8 + h * 4;
-                    if (j < r) {
-                        f32x4 o = {acc1[g * 4 + 0], acc1[g * 4 + 1], acc1[g * 4 + 2], acc1[g * 4 + 3]};
-                        *reinterpret_cast<f32x4*>(vrow + j) = o;
-                    }
-                }
+                for (int e = 0; e < 4; ++e) o[e] = half ? acc1[g * 4 + e] : acc0[g * 4 + e];
+                *reinterpret_cast<f32x4*>(mine + g * 8 + h * 4) = o;
             }
+            __syncthreads();
+            for (int idx = tid; idx < kPieceRows * 8; idx += NT) {
+                const int row = idx >> 3, j4 = (idx & 7) * 4;
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+                    sum += *reinterpret_cast<const f32x4*>(sRed + w * kRedFloatsPerWave + row * kRedStride + j4);
+                const int j = half * 32 + j4;
+                if (row < nrows && j < r)
+                    *reinterpret_cast<f32x4*>(a.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + row)) * a.dv.max_rank + j) = sum;
+            }
+            __syncthreads();
         }
     }
 }
@@ -145,22 +160,22 @@ __device__ inline void shrink_wave_items(const ShrinkArgs& a, int first_item, in
 // m = window + i (the block's column) and output columns n_first + 32 nb + 8 g + 4 h + e in register
 // 4 g + e.  For every distinct slot among the window's rows, that slot's B rows and the rows' scaled
 // shrink results (rounded to bf16) are fed as extra K steps of 16.
-//   VS: functor (k, mine) -> bf16x8 with the lane's scaled v[m][k .. k+7] (zeros when !mine).
+//   VS: functor (k, on, scale) -> bf16x8 with the lane's scaled v[m][k .. k+7] (zeros when !on).
+// my_rank / my_scale are the per-row copies of the slot's rank and scale.
 // ---------------------------------------------------------------------------------------------------
 template <int NB, typename VS>
-__device__ inline void expand_window(f32x16 (&acc)[NB], int my_slot, int n_first, int N, const DeviceView& dv,
-                                     size_t b_off, VS&& vfrag)
+__device__ inline void expand_window(f32x16 (&acc)[NB], int my_slot, int my_rank, float my_scale, int n_first, int N,
+                                     const DeviceView& dv, size_t b_off, VS&& vfrag)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
-    unsigned long long todo = __ballot(my_slot >= 0);
+    unsigned long long todo = __ballot(my_slot >= 0 && my_rank > 0);
     while (todo) {
         const int leader = __ffsll((long long)todo) - 1;
         const int s = __shfl(my_slot, leader, kWave);
+        const int r = __shfl(my_rank, leader, kWave);
+        const float sc = __shfl(my_scale, leader, kWave);
         todo &= ~__ballot(my_slot == s);
-        const int r = dv.slot_rank[s];
-        if (r <= 0) continue;
-        const float sc = dv.slot_scale[s];
         const uint16_t* Bs = dv.slots + (size_t)s * dv.slot_stride + b_off;
         const bool mine = (my_slot == s);
         for (int kq = 0; kq < r; kq += 16) {

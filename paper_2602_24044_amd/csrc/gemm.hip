@@ -203,8 +203,10 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
 
         if (FUSED) {
             const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
+            const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
+            const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
             VFromGlobal vs{a.vpart, a.n_kc, T, a.dv.max_rank, m};
-            expand_window<NB>(acc[mb], my_slot, n_first, N, a.dv, a.b_off, vs);
+            expand_window<NB>(acc[mb], my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vs);
         }
 
         if (m_ok) {
@@ -223,26 +225,31 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
                         }
                     }
             } else {
-                float* prow = a.part + ((size_t)split * a.Mpad + m) * N;
+                // fp32 partial tiles are kept block by block in accumulator order: block (m / 32, n / 32)
+                // of split s is 1024 consecutive floats, lane (i, h) owning floats 256 g + 8 i + 4 h .. + 3,
+                // so every store (and the matching load in the reduce kernel) covers 1 KB contiguously
+                const int nblk = (N + 31) / 32;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int bn = (n_first + nb * 32) / 32;
+                    if (bn < nblk) {
+                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)(m / 32)) * nblk + bn) * 1024;
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = n_first + nb * 32 + g * 8 + h * 4;
-                        if (n < N) {
+                        for (int g = 0; g < 4; ++g) {
                             f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
                                        acc[mb][nb][g * 4 + 3]};
-                            *reinterpret_cast<f32x4*>(prow + n) = o;
+                            *reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4) = o;
                         }
                     }
+                }
             }
         }
     }
 
     // split path: this workgroup's share of the shrink work items of the same projection
-    if (!FUSED && sa.vpart != nullptr) {
-        constexpr int waves = NT / kWave;
-        shrink_wave_items(sa, blockIdx.x * waves + wave, gridDim.x * waves);
+    if (!FUSED) {
+        __shared__ __attribute__((aligned(16))) float sRed[(FUSED ? 1 : NT / kWave) * kRedFloatsPerWave];
+        if (sa.vpart != nullptr) shrink_block_items<NT / kWave>(sa, blockIdx.x, gridDim.x, sRed);
     }
 }
 
@@ -299,6 +306,14 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w4";
             return launch_one<256, 128, 2, 2, false, 2>(a, sa, stream);
+        case 2:
+            tiles(256, 64);
+            *name = "gemm_splitk_shrink_256x64_w4";
+            return launch_one<256, 64, 4, 1, false, 2>(a, sa, stream);
+        case 3:
+            tiles(128, 128);
+            *name = "gemm_splitk_shrink_128x128_w4";
+            return launch_one<128, 128, 2, 2, false, 2>(a, sa, stream);
         default:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w8";

@@ -32,6 +32,7 @@ struct Layout {
     size_t a_off[kMaxProj] = {0};          // element offsets inside a slot
     size_t b_off[kMaxProj] = {0};
     size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
+    size_t off_row_rank = 0, off_row_scale = 0;
     size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
            off_piece_slot = 0, off_tok_key = 0, off_vpart = 0, off_part = 0;
     size_t vpart_elems = 0, part_elems = 0;
@@ -84,6 +85,8 @@ Layout make_layout(const lora_config* c)
     L.off_header = take(256);
     L.off_perm = take(4 * Tm);
     L.off_row_slot = take(4 * Tm);
+    L.off_row_rank = take(4 * Tm);
+    L.off_row_scale = take(4 * Tm);
     L.off_seg_start = take(4 * (Tm + 1));
     L.off_seg_slot = take(4 * Tm);
     const size_t max_pieces = Tm + Tm / kPieceRows + 2;
@@ -97,7 +100,7 @@ Layout make_layout(const lora_config* c)
     size_t part_cols = 0;
     for (int p = 0; p < c->n_proj; ++p) {
         const int s = c->split_k > 0 ? c->split_k : auto_split_cap(c->proj[p].d_out);
-        part_cols = std::max(part_cols, (size_t)c->proj[p].d_out * (size_t)s);
+        part_cols = std::max(part_cols, align_up((size_t)c->proj[p].d_out, 32) * (size_t)s);
     }
     L.part_elems = align_up(Ts, 256) * part_cols;
     L.off_part = take(4 * L.part_elems);
@@ -168,6 +171,8 @@ struct lora_ctx {
         v.slot_scale = d_slot_scale();
         v.perm = dev<int32_t>(L.off_perm);
         v.row_slot = dev<int32_t>(L.off_row_slot);
+        v.row_rank = dev<int32_t>(L.off_row_rank);
+        v.row_scale = dev<float>(L.off_row_scale);
         v.piece_start = dev<int32_t>(L.off_piece_start);
         v.piece_slot = dev<int32_t>(L.off_piece_slot);
         v.n_pieces = d_n_pieces();
@@ -481,6 +486,10 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     a.n_slots = c->cfg.n_slots;
     a.perm = c->dev<int32_t>(c->L.off_perm);
     a.row_slot = c->dev<int32_t>(c->L.off_row_slot);
+    a.row_rank = c->dev<int32_t>(c->L.off_row_rank);
+    a.row_scale = c->dev<float>(c->L.off_row_scale);
+    a.slot_rank = c->d_slot_rank();
+    a.slot_scale = c->d_slot_scale();
     a.seg_start = c->dev<int32_t>(c->L.off_seg_start);
     a.seg_slot = c->dev<int32_t>(c->L.off_seg_slot);
     a.n_seg = c->d_n_seg();
@@ -540,12 +549,15 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     const int Mpad = (T + 255) / 256 * 256;
     int S = 1;
     if (split) {
-        const int tiles = ((T + 255) / 256) * ((N + 127) / 128);
+        const int sv = c->tune[LORA_TUNE_SPLIT_VARIANT];
+        const int bm = sv == 3 ? 128 : 256, bn = sv == 2 ? 64 : 128;
+        const int tiles = ((T + bm - 1) / bm) * ((N + bn - 1) / bn);
         S = c->cfg.split_k > 0 ? c->cfg.split_k : std::max(1, std::min(16, (256 + tiles / 2) / tiles));
         S = std::min(S, std::max(1, (K / kBK) / 2));
-        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)N);
+        const size_t Npad = align_up((size_t)N, 32);
+        const size_t cap = c->L.part_elems / ((size_t)Mpad * Npad);
         S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
-        if ((size_t)S * Mpad * N > c->L.part_elems) return LORA_ERR_OOM;
+        if ((size_t)S * Mpad * Npad > c->L.part_elems) return LORA_ERR_OOM;
     }
     int n_kc = 1, kc_len = K;
     if (T <= kSplitMaxTokens) {
@@ -589,7 +601,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         if (sa.vpart) {
             const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
             const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
-            const int grid = (int)std::max<long>(1, std::min<long>((items + 3) / 4, 2048));
+            const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
             LaunchScope ls(c, s, "shrink");
             if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
         }

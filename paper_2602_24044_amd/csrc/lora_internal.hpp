@@ -15,7 +15,7 @@ constexpr int kMaxProj = 16;
 constexpr int kMaxRank = 64;
 constexpr int kMetaBatch = 16;       // slot-metadata updates carried by one kernel launch
 constexpr int kSplitMaxTokens = 1024;// largest T served by the split-K path
-constexpr int kShrinkKC = 512;       // K extent of one shrink work item on the split-K path
+constexpr int kShrinkKC = 1024;      // K extent of one shrink work item on the split-K path
 constexpr int kMaxShrinkChunks = 64;
 
 // Device-side view of a context: everything the kernels need, passed by value.
@@ -28,6 +28,8 @@ struct DeviceView {
     // segment map of the current step (grouped order)
     const int32_t* perm;       // [T]
     const int32_t* row_slot;   // [T] slot of each grouped position
+    const int32_t* row_rank;   // [T] rank of that slot's adapter (0 for backbone-only rows)
+    const float* row_scale;    // [T] scale of that slot's adapter
     const int32_t* piece_start;// [n_pieces + 1]
     const int32_t* piece_slot; // [n_pieces]
     const int32_t* n_pieces;   // [1]
@@ -44,6 +46,10 @@ struct BucketArgs {
     int32_t n_slots;
     int32_t* perm;
     int32_t* row_slot;
+    int32_t* row_rank;
+    float* row_scale;
+    const int32_t* slot_rank;
+    const float* slot_scale;
     int32_t* seg_start;
     int32_t* seg_slot;
     int32_t* n_seg;
@@ -68,8 +74,8 @@ struct ShrinkArgs {
     const uint16_t* x;   // [T, K] bf16
     int32_t K;
     size_t a_off;        // element offset of this projection's A inside a slot
-    int32_t n_kc;        // K chunks
-    int32_t kc_len;      // K extent of a chunk (multiple of 64)
+    int32_t n_kc;        // K chunks (one partial result each)
+    int32_t kc_len;      // K extent of a chunk (multiple of 64); the waves of a workgroup share a chunk
     float* vpart;        // [n_kc][T][max_rank] fp32
 };
 

@@ -32,19 +32,20 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     f32x16 acc[1];
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
-    if (m_ok) {
-        // four splits (16 independent 16-byte loads per lane) in flight at a time
+    // partial tiles are stored block by block in accumulator order (see the split-K GEMM): block
+    // (window, n / 32) of split s is 1 KB-contiguous per register group, so these loads are fully
+    // coalesced; four splits (16 independent 16-byte loads per lane) are kept in flight
+    const int nblk = (N + 31) / 32;
+    const int bn = n_first / 32;
+    if (bn < nblk) {
         for (int s0 = 0; s0 < a.split_k; s0 += 4) {
             f32x4 p[4][4];
 #pragma unroll
             for (int ds = 0; ds < 4; ++ds) {
                 const int s = (s0 + ds < a.split_k) ? s0 + ds : s0;
-                const float* prow = a.part + ((size_t)s * a.Mpad + m) * N;
+                const float* blk = a.part + (((size_t)s * (a.Mpad / 32) + (size_t)win) * nblk + bn) * 1024;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n_first + g * 8 + h * 4;
-                    p[ds][g] = (n < N) ? *reinterpret_cast<const f32x4*>(prow + n) : f32x4{0.f, 0.f, 0.f, 0.f};
-                }
+                for (int g = 0; g < 4; ++g) p[ds][g] = *reinterpret_cast<const f32x4*>(blk + g * 256 + i * 8 + h * 4);
             }
 #pragma unroll
             for (int ds = 0; ds < 4; ++ds) {
@@ -64,16 +65,18 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         const int mr = win * kPieceRows + row;
         u32x4 packed = {0u, 0u, 0u, 0u};
         if (mr < T && seg * 8 < a.dv.max_rank) {
-            const int slot = a.dv.row_slot[mr];
-            const int r = slot >= 0 ? a.dv.slot_rank[slot] : 0;
+            // rank, scale and the partial results are fetched together; what lies past the row's rank
+            // is discarded by the select below, never used in arithmetic that is kept
+            const int r = a.dv.row_rank[mr];
+            const float sc = a.dv.row_scale[mr];
+            f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+            for (int c = 0; c < a.n_kc; ++c) {
+                const float* vp = a.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
+                lo += *reinterpret_cast<const f32x4*>(vp);
+                hi += *reinterpret_cast<const f32x4*>(vp + 4);
+            }
             if (seg * 8 < r) {
-                const float sc = a.dv.slot_scale[slot];
-                f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-                for (int c = 0; c < a.n_kc; ++c) {
-                    const float* vp = a.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
-                    lo += *reinterpret_cast<const f32x4*>(vp);
-                    hi += *reinterpret_cast<const f32x4*>(vp + 4);
-                }
                 bf16x8 vb;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -88,12 +91,14 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     __syncthreads();
 
     const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
+    const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
+    const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
     auto vfrag = [&](int k, bool on, float) -> bf16x8 {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStride + k);
         return as_bf16x8(v);
     };
-    expand_window<1>(acc, my_slot, n_first, N, a.dv, a.b_off, vfrag);
+    expand_window<1>(acc, my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vfrag);
 
     if (m_ok) {
         uint16_t* orow = a.out + (size_t)a.dv.perm[m] * N;

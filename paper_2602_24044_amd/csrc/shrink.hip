@@ -1,5 +1,5 @@
 // Stand-alone LoRA shrink launch (used ahead of the fused GEMM; the split-K GEMM runs the same work
-// loop inside its own workgroups).  Memory-bound; no LDS, no barriers.
+// loop inside its own workgroups).  Memory-bound.
 #include "device_common.hpp"
 
 namespace lora {
@@ -9,8 +9,9 @@ constexpr int kShrinkThreads = 256;
 
 __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(ShrinkArgs a)
 {
-    const int waves_per_block = kShrinkThreads / kWave;
-    shrink_wave_items(a, blockIdx.x * waves_per_block + (int)(threadIdx.x / kWave), gridDim.x * waves_per_block);
+    constexpr int NW = kShrinkThreads / kWave;
+    __shared__ __attribute__((aligned(16))) float sRed[NW * kRedFloatsPerWave];
+    shrink_block_items<NW>(a, blockIdx.x, gridDim.x, sRed);
 }
 
 }  // namespace
