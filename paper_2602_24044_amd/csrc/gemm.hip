@@ -4,14 +4,16 @@
 // Rows of the GEMM are grouped positions m (token perm[m]); x rows are gathered through perm when the
 // tile is staged and output rows are scattered back through it, so `out` is in token order.
 //
-// Tiling: BM x BN output tile per workgroup, K walked in 64-wide tiles through two LDS stages.  Tiles
-// are copied global -> LDS directly (global_load_lds, 16 bytes per lane, no staging registers and no
-// LDS store instructions): one wave instruction fills 1 KB = 8 LDS rows of 128 bytes.  Chunk c (16
-// bytes) of row rr is kept at position c ^ (rr & 7); because the copy engine places lane l at byte
-// 16 l of the wave's 1 KB, the swizzle is applied on the global side (lane l fetches the chunk that
-// belongs at its position).  The MFMA-layout reads (32 rows x one chunk) are then bank-conflict free.
-// The copy of tile j + 2 is issued as soon as every wave has finished reading tile j and is in
-// flight during the whole of tile j + 1 (see the main loop for the schedule).
+// Tiling: BM x BN output tile per workgroup, K walked in 32-wide tiles through a ring of NS LDS stages.
+// Tiles are copied global -> LDS directly (global_load_lds, 16 bytes per lane: no staging registers, no
+// LDS store instructions); one wave instruction fills 1 KB = 16 LDS rows of 64 bytes.  A stage holds the
+// BM x-rows followed by the BN W-rows.  Chunk c (16 bytes) of row rr sits at position c ^ ((rr >> 2) & 3);
+// because the copy engine places lane l at byte 16 l of the wave's 1 KB, the swizzle is applied on the
+// global side (lane l fetches the chunk that belongs at its position).  The LDS serves a 128-bit read 16
+// lanes per cycle over 64 banks, the 16 lanes being those of a 32-lane half whose lane-index bits 2, 3, 4
+// have equal parity; with this swizzle the 16 rows of such a group fall on 16 different 16-byte bank
+// groups, so the MFMA-layout reads (32 rows x one chunk) are bank-conflict free.  NS - 2 tile copies stay in flight behind the tile being
+// multiplied, which is what covers the HBM latency (see the main loop for the schedule).
 //
 // MFMA 32x32x16 bf16 with W as the first operand and x as the second: the accumulator of a lane then
 // holds one grouped row m (its column index) and, per group of four registers, four consecutive
@@ -30,6 +32,8 @@
 namespace lora {
 namespace {
 
+constexpr int kTK = 32;   // K extent of one LDS tile (bf16 elements): 64-byte rows
+
 template <typename F, int... Is>
 __device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
 {
@@ -41,21 +45,39 @@ __device__ inline void static_for(F&& f)
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int D>
+// One global -> LDS copy instruction: every lane hands in the address of its 16 bytes, the wave's 1 KB
+// lands at lds_addr (wave-uniform) + 16 * lane.  Issued from inline assembly so that the only ordering
+// against later LDS reads is the explicit vmcnt wait + barrier of the main loop (the compiler would
+// otherwise drain all copies before any LDS read whose stage it cannot tell apart).
+__device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+template <int N>
+__device__ inline void wait_copies_then_barrier()
+{
+    // at most N of this wave's tile-copy instructions may still be in flight; then meet the other waves
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
 __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
 {
     constexpr int NT = WGM * WGN * kWave;
-    constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wave tile
-    constexpr int MB = WTM / 32, NB = WTN / 32;     // 32x32 accumulator blocks per wave
-    constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;  // 16-byte chunks per thread per tile
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads");
+    constexpr int NWV = NT / kWave;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
+    constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
+    constexpr int STAGE = (BM + BN) * kTK;                  // elements per stage
+    constexpr int XQ = BM / 16 / NWV, WQ = BN / 16 / NWV;   // copy instructions per wave and tile
+    constexpr int QPT = XQ + WQ;
+    static_assert(BM % (16 * NWV) == 0 && BN % (16 * NWV) == 0, "tile/waves");
+    static_assert(NS >= 3 && NS <= 5, "stages");
+    static_assert((NS - 2) * QPT <= 63, "vmcnt range");
 
-    // one static array per stage and operand: distinct objects let the compiler keep copies into one
-    // stage in flight while the other stage is being read
-    __shared__ __attribute__((aligned(1024))) uint16_t sX0[BM * kBK];
-    __shared__ __attribute__((aligned(1024))) uint16_t sX1[BM * kBK];
-    __shared__ __attribute__((aligned(1024))) uint16_t sW0[BN * kBK];
-    __shared__ __attribute__((aligned(1024))) uint16_t sW1[BN * kBK];
+    // ring of NS stages; the copy instructions address it by LDS byte address, the MFMA loop reads it
+    __shared__ __attribute__((aligned(1024))) uint16_t ring[NS * STAGE];
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
@@ -77,7 +99,7 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int kt_total = K / kBK;
+    const int kt_total = K / kTK;
     int kt_begin = 0, kt_end = kt_total;
     if (!FUSED) {
         kt_begin = (int)((long long)kt_total * split / a.split_k);
@@ -85,26 +107,23 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     }
     const int nk = kt_end - kt_begin;
 
-    // Copy assignment: wave instruction q of wave w fills LDS rows 8 (w XQ + q) .. + 7 of the X tile
-    // (same for W with WQ); lane l owns row l / 8 of those and chunk position l % 8.  Rows past T or N are
-    // clamped to the last valid row: they are computed, never stored.
-    constexpr int NWV = NT / kWave;
-    constexpr int XQ = BM / 8 / NWV, WQ = BN / 8 / NWV;     // wave instructions per stage
-    static_assert(BM % (8 * NWV) == 0 && BN % (8 * NWV) == 0, "tile/waves");
-    const int cp_row = lane >> 3;
-    const int cp_chunk = (lane & 7) ^ cp_row;               // (row & 7) == cp_row: row blocks start at multiples of 8
-    uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes at k = 0
+    // Copy assignment: copy instruction q of wave w fills stage rows 16 (w XQ + q) .. + 15 (x part; same
+    // for the W part with WQ); lane l owns row l / 4 of those and chunk position l % 4.  Rows past T or N
+    // are clamped to the last valid row: they are computed, never stored.
+    const int cp_row = lane >> 2;
+    const int cp_chunk = (lane & 3) ^ ((cp_row >> 2) & 3);
+    uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes in tile 0
 #pragma unroll
     for (int q = 0; q < XQ; ++q) {
-        int m = m0 + (wave * XQ + q) * 8 + cp_row;
+        int m = m0 + (wave * XQ + q) * 16 + cp_row;
         if (m > T - 1) m = T - 1;
-        xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kBK);
+        xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
     }
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
-        int n = n0 + (wave * WQ + q) * 8 + cp_row;
+        int n = n0 + (wave * WQ + q) * 16 + cp_row;
         if (n > N - 1) n = N - 1;
-        woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kBK);
+        woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
     }
 
     f32x16 acc[MB][NB];
@@ -116,82 +135,152 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
     // ---- software-pipelined main loop ----
-    // State at the top of iteration j: tile j is complete in stage j & 1, the fragments of its first K
-    // step are in F[0], and the copy of tile j + 1 into the other stage is in flight.  Each K step issues
-    // the LDS reads of the following step before its own MFMAs.  The single barrier of the iteration
-    // sits between K step 2 and 3: every wave has then read all of tile j (its last fragments are in
-    // registers) and its own share of tile j + 1 has landed, so after the barrier tile j + 1 is complete
-    // for everyone and stage j & 1 is free: the copy of tile j + 2 starts there, the first fragments of
-    // tile j + 1 are read, and the MFMAs of step 3 cover the barrier skew and the LDS latency.
+    // Tile j lives in stage j % NS.  State at the top of iteration j: tile j has landed for every wave,
+    // the fragments of its first K step are in F[0], and the copies of tiles j + 1 .. j + NS - 2 are in
+    // flight or landed.  K step 0 runs its MFMAs with the LDS reads of step 1 spread between them.  The
+    // wave then waits until its own share of tile j + 1 has landed (younger copies stay in flight) and
+    // meets the other waves at the barrier: tile j + 1 is now complete for everyone and the stage of tile
+    // j - 1 is free.  K step 1 runs its MFMAs with the copy instructions of tile j + NS - 1 (into the freed
+    // stage) and the LDS reads of tile j + 1's first fragments spread between them, so neither the copy
+    // issue nor the LDS latency ever leaves the matrix core idle.  Instruction order is pinned with
+    // scheduling barriers; without them the compiler batches all MFMAs of a step together.
     bf16x8 Fw[2][NB], Fx[2][MB];
-    auto copy_tile = [&](auto st_c, int j) {
-        constexpr int ST = decltype(st_c)::value;
-        uint16_t* dx = ST ? sX1 : sX0;
-        uint16_t* dw = ST ? sW1 : sW0;
-        const uint32_t k0 = (uint32_t)j * kBK;
-#pragma unroll
-        for (int q = 0; q < XQ; ++q)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(a.x + (xoff[q] + k0)),
-                (__attribute__((address_space(3))) void*)(dx + (wave * XQ + q) * 512), 16, 0, 0);
-#pragma unroll
-        for (int q = 0; q < WQ; ++q)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(a.W + (woff[q] + k0)),
-                (__attribute__((address_space(3))) void*)(dw + (wave * WQ + q) * 512), 16, 0, 0);
+    const int sw = (i >> 2) & 3;                              // (row >> 2) & 3 of every row this lane reads
+    constexpr int NM = MB * NB;                               // MFMAs per K step
+    constexpr int NR = MB + NB;                               // LDS reads per K step
+    const uint32_t cp_x = ring_addr + wave * XQ * 1024;       // this wave's first x / W copy target in stage 0
+    const uint32_t cp_w = ring_addr + BM * kTK * 2 + wave * WQ * 1024;
+    const int rd_lane[2] = {i * kTK + ((0 * 2 + h) ^ sw) * 8, i * kTK + ((1 * 2 + h) ^ sw) * 8};
+
+    auto copy_one = [&](int stage, int q, uint32_t k0) {      // q: compile-time constant at every call site
+        const uint32_t so = (uint32_t)stage * (STAGE * 2);
+        if (q < XQ)
+            copy16_to_lds(a.x + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
+        else
+            copy16_to_lds(a.W + (woff[q - XQ] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + (q - XQ) * 1024));
     };
-    auto read_frags = [&](auto f_c, auto st_c, int kk) {
+    auto read_one = [&](auto f_c, int stage, int kk, int r) { // kk, r: compile-time constants at every call site
         constexpr int Fi = decltype(f_c)::value;
-        constexpr int ST = decltype(st_c)::value;
-        const uint16_t* bx = ST ? sX1 : sX0;
-        const uint16_t* bw = ST ? sW1 : sW0;
-        const int c = kk * 2 + h;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int rr = wn * WTN + nb * 32 + i;
-            Fw[Fi][nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bw + (rr * 8 + (c ^ (rr & 7))) * 8));
-        }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int rr = wm * WTM + mb * 32 + i;
-            Fx[Fi][mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(bx + (rr * 8 + (c ^ (rr & 7))) * 8));
-        }
+        const uint16_t* base = ring + stage * STAGE + rd_lane[kk];
+        if (r < NB)
+            Fw[Fi][r] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + (BM + wn * WTN + r * 32) * kTK));
+        else
+            Fx[Fi][r - NB] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + (wm * WTM + (r - NB) * 32) * kTK));
     };
-    auto mma = [&](auto f_c) {
+    auto mma_one = [&](auto f_c, int t) {                     // t: compile-time constant at every call site
         constexpr int Fi = decltype(f_c)::value;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(Fw[Fi][nb], Fx[Fi][mb], acc[mb][nb]);
+        const int mb = t / NB, nb = t % NB;
+        acc[mb][nb] = mfma32(Fw[Fi][nb], Fx[Fi][mb], acc[mb][nb]);
+    };
+    // young = number of younger tile copies that may stay in flight behind the one being waited for
+    auto wait_barrier = [&](int young) {
+        if (NS > 4 && young >= 3) wait_copies_then_barrier<(NS > 4 ? 3 : 0) * QPT>();
+        else if (NS > 3 && young >= 2) wait_copies_then_barrier<(NS > 3 ? 2 : 0) * QPT>();
+        else if (young >= 1) wait_copies_then_barrier<1 * QPT>();
+        else wait_copies_then_barrier<0>();
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
-    auto iteration = [&](auto par_c, int j) {
-        constexpr int PAR = decltype(par_c)::value;
-        using Cur = std::integral_constant<int, PAR>;
-        using Oth = std::integral_constant<int, PAR ^ 1>;
-        read_frags(I1{}, Cur{}, 1);
-        mma(I0{});
-        read_frags(I0{}, Cur{}, 2);
-        mma(I1{});
-        read_frags(I1{}, Cur{}, 3);
-        mma(I0{});
-        __syncthreads();
-        if (j + 2 < nk) copy_tile(Cur{}, j + 2);
-        if (j + 1 < nk) read_frags(I0{}, Oth{}, 0);
-        mma(I1{});
+    // cur / nxt: stages of tiles j and j + 1.  fre0: stage of tile j - 2, freed at the previous barrier; it
+    // receives the second half of tile j + NS - 2's copy during K step 0.  fre1: stage of tile j - 1, freed
+    // at this iteration's barrier; it receives the first half of tile j + NS - 1's copy during K step 1.
+    // Splitting each tile copy over two K steps keeps the copy issue rate even, so a wave is rarely held
+    // up behind a full memory pipeline with MFMAs waiting behind it.
+    constexpr int QA = (QPT + 1) / 2, QB = QPT - QA;          // first / second half of a tile copy
+    auto iteration = [&](auto copy_c, int j, int cur, int nxt, int fre0, int fre1) {
+        constexpr bool COPY = decltype(copy_c)::value;
+        // K step 0: MFMAs on F[0]; second half of the copy of tile j + NS - 2; reads of step 1 into F[1]
+        {
+            const uint32_t k0 = (uint32_t)(j + NS - 2) * kTK;
+            constexpr int NI = (COPY ? QB : 0) + NR;
+            static_for<NM>([&](auto t) {
+                mma_one(I0{}, t.value);
+                asm volatile("" ::: "memory");
+                static_for<NI>([&](auto it) {
+                    if constexpr (it.value * NM / NI == t.value) {
+                        if constexpr (COPY && it.value >= NR) copy_one(fre0, QA + it.value - NR, k0);
+                        else read_one(I1{}, cur, 1, it.value);
+                    }
+                });
+                asm volatile("" ::: "memory");
+            });
+        }
+        // own share of tile j + 1 landed (younger copy instructions may stay in flight), then barrier
+        if constexpr (COPY) {
+            wait_copies_then_barrier<(NS - 3) * QPT>();
+        } else {
+            int young = nk - 2 - j;           // complete tile copies issued after tile j + 1
+            if (young < 0) young = 0;
+            if (young > NS - 3) young = NS - 3;
+            wait_barrier(young);
+        }
+        // K step 1: MFMAs on F[1]; first half of the copy of tile j + NS - 1; reads of tile j + 1, step 0
+        {
+            const uint32_t k0 = (uint32_t)(j + NS - 1) * kTK;
+            constexpr int NI = (COPY ? QA : 0) + NR;
+            static_for<NM>([&](auto t) {
+                mma_one(I1{}, t.value);
+                asm volatile("" ::: "memory");
+                static_for<NI>([&](auto it) {
+                    if constexpr (it.value * NM / NI == t.value) {
+                        if constexpr (COPY && it.value < QA) copy_one(fre1, it.value, k0);
+                        else read_one(I0{}, nxt, 0, it.value - (COPY ? QA : 0));
+                    }
+                });
+                asm volatile("" ::: "memory");
+            });
+        }
     };
 
+    // Prologue: tiles 0 .. NS - 3 in full and the first half of tile NS - 2 (its second half follows in
+    // K step 0 of iteration 0, exactly as in the steady state).
+    const bool steady = nk >= NS;              // at least one steady-state iteration exists
     if (nk > 0) {
-        copy_tile(I0{}, 0);
-        __syncthreads();
-        if (nk > 1) copy_tile(I1{}, 1);
-        read_frags(I0{}, I0{}, 0);
+        static_for<NS - 2>([&](auto d) {
+            if (d.value < nk) {
+                static_for<QPT>([&](auto q) { copy_one(d.value, q.value, (uint32_t)d.value * kTK); });
+            }
+        });
+        if (NS - 2 < nk) {
+            if (steady) {
+                static_for<QA>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
+            } else {
+                static_for<QPT>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
+            }
+        }
+        // wait for tile 0: everything younger may stay in flight
+        int young_instr = 0;
+        {
+            const int full = (nk - 1 < NS - 3) ? nk - 1 : NS - 3;      // complete younger tiles among 1 .. NS - 3
+            young_instr = (full > 0 ? full : 0) * QPT;
+            if (NS - 2 < nk && NS - 2 >= 1) young_instr += steady ? QA : QPT;
+        }
+        // round the allowance down to a multiple the wait helper knows (waiting for more is always safe)
+        wait_barrier(young_instr / QPT > NS - 2 ? NS - 2 : young_instr / QPT);
+        static_for<NR>([&](auto r) { read_one(I0{}, 0, 0, r.value); });
     }
-    for (int j = 0; j < nk; j += 2) {
-        iteration(I0{}, j);
-        if (j + 1 < nk) iteration(I1{}, j + 1);
+    {
+        int cur = 0, nxt = 1 % NS, fre1 = NS - 1, fre0 = NS - 2;
+        int j = 0;
+        auto advance = [&]() {
+            fre0 = fre1;
+            fre1 = cur;
+            cur = nxt;
+            nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
+        };
+        if (steady) {
+            for (; j + NS - 1 < nk; ++j) {    // steady state: one tile copy issued per iteration
+                iteration(std::true_type{}, j, cur, nxt, fre0, fre1);
+                advance();
+            }
+            // the first half of tile nk - 1 is out; send its second half before draining
+            static_for<QB>([&](auto q) { copy_one(fre0, QA + q.value, (uint32_t)(nk - 1) * kTK); });
+        }
+        for (; j < nk; ++j) {                 // drain: the remaining tiles are already on their way
+            iteration(std::false_type{}, j, cur, nxt, fre0, fre1);
+            advance();
+        }
     }
 
     // ---------------- epilogue ----------------
@@ -248,16 +337,16 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
 
     // split path: this workgroup's share of the shrink work items of the same projection
     if (!FUSED) {
-        __shared__ __attribute__((aligned(16))) float sRed[(FUSED ? 1 : NT / kWave) * kRedFloatsPerWave];
-        if (sa.vpart != nullptr) shrink_block_items<NT / kWave>(sa, blockIdx.x, gridDim.x, sRed);
+        __shared__ __attribute__((aligned(16))) float sRed[(FUSED ? 1 : NWV) * kRedFloatsPerWave];
+        if (sa.vpart != nullptr) shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, sRed);
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int D>
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
 hipError_t launch_one(const GemmArgs& a, const ShrinkArgs& sa, hipStream_t stream)
 {
     constexpr int NT = WGM * WGN * kWave;
-    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, D>;
+    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS>;
     const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), 0, stream, a, sa);
     return hipGetLastError();
@@ -276,20 +365,20 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
     switch (variant) {
         case 1:
             tiles(256, 256);
-            *name = "gemm_fused_256x256_w4";
-            return launch_one<256, 256, 2, 2, true, 1>(a, none, stream);
+            *name = "gemm_fused_256x256_w8";
+            return launch_one<256, 256, 2, 4, true, 4>(a, none, stream);
         case 2:
             tiles(256, 256);
-            *name = "gemm_fused_256x256_w4_d2";
-            return launch_one<256, 256, 2, 2, true, 2>(a, none, stream);
+            *name = "gemm_fused_256x256_w4_s3";
+            return launch_one<256, 256, 2, 2, true, 3>(a, none, stream);
         case 3:
             tiles(128, 128);
-            *name = "gemm_fused_128x128_w4_d3";
-            return launch_one<128, 128, 2, 2, true, 3>(a, none, stream);
+            *name = "gemm_fused_128x128_w4";
+            return launch_one<128, 128, 2, 2, true, 4>(a, none, stream);
         default:
             tiles(256, 256);
-            *name = "gemm_fused_256x256_w8";
-            return launch_one<256, 256, 2, 4, true, 1>(a, none, stream);
+            *name = "gemm_fused_256x256_w4";
+            return launch_one<256, 256, 2, 2, true, 4>(a, none, stream);
     }
 }
 
@@ -305,19 +394,19 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
         case 1:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w4";
-            return launch_one<256, 128, 2, 2, false, 2>(a, sa, stream);
+            return launch_one<256, 128, 2, 2, false, 5>(a, sa, stream);
         case 2:
             tiles(256, 64);
             *name = "gemm_splitk_shrink_256x64_w4";
-            return launch_one<256, 64, 4, 1, false, 2>(a, sa, stream);
+            return launch_one<256, 64, 4, 1, false, 5>(a, sa, stream);
         case 3:
             tiles(128, 128);
             *name = "gemm_splitk_shrink_128x128_w4";
-            return launch_one<128, 128, 2, 2, false, 2>(a, sa, stream);
+            return launch_one<128, 128, 2, 2, false, 5>(a, sa, stream);
         default:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w8";
-            return launch_one<256, 128, 4, 2, false, 3>(a, sa, stream);
+            return launch_one<256, 128, 4, 2, false, 5>(a, sa, stream);
     }
 }
 
