@@ -85,7 +85,7 @@ typedef struct {
     int32_t max_rank;       /* S_max: slot size in rank units, multiple of 8, 8 .. 64 */
     int32_t n_proj;         /* targeted projections per layer, 1 .. 16 */
     const lora_proj_shape *proj; /* host, n_proj entries, copied by lora_create */
-    int32_t max_tokens;     /* largest T of any step */
+    int32_t max_tokens;     /* largest T of any step; max_tokens * d_in and d_out * d_in must stay below 2^32 */
     int32_t max_adapter_id; /* adapter ids are 0 .. max_adapter_id */
     void *slab;             /* device memory owned by the caller, 256-byte aligned, lora_slab_bytes() long;
                                holds the slot region and all scratch; must outlive the context */

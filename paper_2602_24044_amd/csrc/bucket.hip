@@ -156,6 +156,19 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
 
     rle(a.row_slot, T, 0, a.seg_start, a.seg_slot, a.n_seg, s_wave);
     rle(a.row_slot, T, kPieceRows, a.piece_start, a.piece_slot, a.n_pieces, s_wave);
+    __syncthreads();
+
+    // one 16-byte record per piece for the shrink work loop
+    const int n_pieces = *a.n_pieces;
+    for (int p = tid; p < n_pieces; p += kBT) {
+        const int begin = a.piece_start[p], end = a.piece_start[p + 1], s = a.piece_slot[p];
+        int4 rec;
+        rec.x = begin;
+        rec.y = end - begin;
+        rec.z = s;
+        rec.w = s >= 0 ? a.slot_rank[s] : 0;
+        reinterpret_cast<int4*>(a.piece_info)[p] = rec;
+    }
 }
 
 __global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot)

@@ -81,27 +81,55 @@ __device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0,
 constexpr int kRedStride = 36;   // floats per LDS row of the cross-wave reduction (144 bytes: conflict-free)
 constexpr int kRedFloatsPerWave = kPieceRows * kRedStride;
 
+// What the first work item of a workgroup needs before it can issue its operand loads; fetched at kernel
+// start so that the chain item -> piece record -> perm -> x is off the critical path later.
+struct ShrinkPrefetch {
+    int n_items;
+    int4 rec;      // piece record of the first item (undefined when first_item >= n_items)
+    int tok;       // perm[rec.x + lane % 32]
+};
+
+__device__ inline ShrinkPrefetch shrink_prefetch(const ShrinkArgs& a, int first_item)
+{
+    ShrinkPrefetch pf;
+    const int i = threadIdx.x & 31;
+    pf.n_items = *a.dv.n_pieces * a.n_kc;
+    pf.rec = int4{0, 0, -1, 0};
+    pf.tok = 0;
+    if (first_item < pf.n_items) {
+        pf.rec = reinterpret_cast<const int4*>(a.dv.piece_info)[first_item / a.n_kc];
+        if (i < pf.rec.y) pf.tok = a.dv.perm[pf.rec.x + i];
+    }
+    return pf;
+}
+
 // Processes work items first_item, first_item + stride, ... with the whole workgroup of NW wavefronts:
 // the waves split the item's K chunk between them, then the NW partial 32 x r blocks are summed
 // through LDS (sRed: NW * kRedFloatsPerWave floats) and written as one partial result per chunk.
 // Every branch on item data is uniform over the workgroup.
 template <int NW>
-__device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, int stride, float* sRed)
+__device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, int stride, float* sRed,
+                                          const ShrinkPrefetch& pf)
 {
     constexpr int NT = NW * kWave;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const int n_items = *a.dv.n_pieces * a.n_kc;
+    const int n_items = pf.n_items;
     const int K = a.K;
     for (int item = first_item; item < n_items; item += stride) {
         const int piece = item / a.n_kc;
         const int kc = item - piece * a.n_kc;
-        const int slot = a.dv.piece_slot[piece];
-        if (slot < 0) continue;
-        const int m_begin = a.dv.piece_start[piece];
-        const int r = a.dv.row_rank[m_begin];
-        if (r <= 0) continue;
-        const int nrows = a.dv.piece_start[piece + 1] - m_begin;
+        int4 rec;
+        int tok;
+        if (item == first_item) {
+            rec = pf.rec;
+            tok = pf.tok;
+        } else {
+            rec = reinterpret_cast<const int4*>(a.dv.piece_info)[piece];
+            tok = (i < rec.y) ? a.dv.perm[rec.x + i] : 0;
+        }
+        const int m_begin = rec.x, nrows = rec.y, slot = rec.z, r = rec.w;
+        if (slot < 0 || r <= 0) continue;
         const int c_begin = kc * a.kc_len;
         int c_end = c_begin + a.kc_len;
         if (c_end > K) c_end = K;
@@ -112,7 +140,7 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
         if (k_end > c_end) k_end = c_end;
 
         const bool x_ok = i < nrows;
-        const uint16_t* xrow = a.x + (size_t)(x_ok ? a.dv.perm[m_begin + i] : 0) * K + h * 32;
+        const uint16_t* xrow = a.x + (size_t)tok * K + h * 32;
         const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + a.a_off;
         const bool a0_ok = i < r, a1_ok = (32 + i) < r;
         const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
@@ -190,6 +218,68 @@ __device__ inline void expand_window(f32x16 (&acc)[NB], int my_slot, int my_rank
                 acc[nb] = mfma32(as_bf16x8(bv), vf, acc[nb]);
             }
         }
+    }
+}
+
+// Same as expand_window for a single 32-column block, with the B fragments of the next distinct slot
+// fetched while the current slot's MFMAs run (a 32-row decode window holds many slots, and each slot's
+// fragments are a dependent global load: without the look-ahead the loop pays one memory latency per slot).
+template <typename VS>
+__device__ inline void expand_window_pipelined(f32x16& acc, int my_slot, int my_rank, float my_scale, int n_first,
+                                               int N, const DeviceView& dv, size_t b_off, VS&& vfrag)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    const int n = n_first + i;
+    const bool n_ok = n < N;
+    unsigned long long todo = __ballot(my_slot >= 0 && my_rank > 0);
+    struct Slot {
+        int s, r;
+        float sc;
+        bool valid;
+    };
+    auto next_slot = [&]() {
+        Slot q{-1, 0, 0.f, false};
+        if (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            q.s = __shfl(my_slot, leader, kWave);
+            q.r = __shfl(my_rank, leader, kWave);
+            q.sc = __shfl(my_scale, leader, kWave);
+            q.valid = true;
+            todo &= ~__ballot(my_slot == q.s);
+        }
+        return q;
+    };
+    auto fetch = [&](const Slot& q, u32x4 (&fb)[4]) {
+        const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int k = ks * 16 + h * 8;
+            fb[ks] = u32x4{0u, 0u, 0u, 0u};
+            if (q.valid && n_ok && k < q.r) fb[ks] = load16(Bs + k);
+        }
+    };
+    auto apply = [&](const Slot& q, const u32x4 (&fb)[4]) {
+        const bool mine = (my_slot == q.s);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks * 16 < q.r) {
+                const int k = ks * 16 + h * 8;
+                acc = mfma32(as_bf16x8(fb[ks]), vfrag(k, mine && k < q.r, q.sc), acc);
+            }
+        }
+    };
+    u32x4 f0[4], f1[4];
+    Slot q0 = next_slot();
+    fetch(q0, f0);
+    while (q0.valid) {
+        Slot q1 = next_slot();
+        fetch(q1, f1);
+        apply(q0, f0);
+        if (!q1.valid) break;
+        q0 = next_slot();
+        fetch(q0, f0);
+        apply(q1, f1);
     }
 }
 

@@ -69,10 +69,15 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
     constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
     constexpr int STAGE = (BM + BN) * kTK;                  // elements per stage
-    constexpr int XQ = BM / 16 / NWV, WQ = BN / 16 / NWV;   // copy instructions per wave and tile
+    // On the fused path only the first CW waves (one per SIMD) issue tile copies.  A wave that is held at a
+    // copy instruction by a full memory pipeline cannot issue its MFMAs; with two waves per SIMD the other
+    // one keeps the matrix core busy meanwhile (measured: a few percent on the compute-bound shapes, none
+    // on the split path, where every wave copies).
+    constexpr int CW = (FUSED && NWV > 4) ? 4 : NWV;
+    constexpr int XQ = BM / 16 / CW, WQ = BN / 16 / CW;     // copy instructions per copying wave and tile
     constexpr int QPT = XQ + WQ;
-    static_assert(BM % (16 * NWV) == 0 && BN % (16 * NWV) == 0, "tile/waves");
-    static_assert(NS >= 3 && NS <= 5, "stages");
+    static_assert(BM % (16 * CW) == 0 && BN % (16 * CW) == 0, "tile/waves");
+    static_assert(NS >= 3 && NS <= 8, "stages");
     static_assert((NS - 2) * QPT <= 63, "vmcnt range");
 
     // ring of NS stages; the copy instructions address it by LDS byte address, the MFMA loop reads it
@@ -98,6 +103,10 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
         tile_n = b / a.tiles_m;
     }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    // split path: metadata of this workgroup's first shrink work item, fetched before the main loop
+    ShrinkPrefetch spf{};
+    if (!FUSED && sa.vpart != nullptr) spf = shrink_prefetch(sa, blockIdx.x);
 
     const int kt_total = K / kTK;
     int kt_begin = 0, kt_end = kt_total;
@@ -152,7 +161,9 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     const uint32_t cp_w = ring_addr + BM * kTK * 2 + wave * WQ * 1024;
     const int rd_lane[2] = {i * kTK + ((0 * 2 + h) ^ sw) * 8, i * kTK + ((1 * 2 + h) ^ sw) * 8};
 
+    const bool copier = wave < CW;
     auto copy_one = [&](int stage, int q, uint32_t k0) {      // q: compile-time constant at every call site
+        if (!copier) return;
         const uint32_t so = (uint32_t)stage * (STAGE * 2);
         if (q < XQ)
             copy16_to_lds(a.x + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
@@ -174,7 +185,11 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     };
     // young = number of younger tile copies that may stay in flight behind the one being waited for
     auto wait_barrier = [&](int young) {
-        if (NS > 4 && young >= 3) wait_copies_then_barrier<(NS > 4 ? 3 : 0) * QPT>();
+        // waiting with a smaller allowance than necessary is always safe
+        if (NS > 7 && young >= 6) wait_copies_then_barrier<(NS > 7 ? 6 : 0) * QPT>();
+        else if (NS > 6 && young >= 5) wait_copies_then_barrier<(NS > 6 ? 5 : 0) * QPT>();
+        else if (NS > 5 && young >= 4) wait_copies_then_barrier<(NS > 5 ? 4 : 0) * QPT>();
+        else if (NS > 4 && young >= 3) wait_copies_then_barrier<(NS > 4 ? 3 : 0) * QPT>();
         else if (NS > 3 && young >= 2) wait_copies_then_barrier<(NS > 3 ? 2 : 0) * QPT>();
         else if (young >= 1) wait_copies_then_barrier<1 * QPT>();
         else wait_copies_then_barrier<0>();
@@ -338,7 +353,7 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     // split path: this workgroup's share of the shrink work items of the same projection
     if (!FUSED) {
         __shared__ __attribute__((aligned(16))) float sRed[(FUSED ? 1 : NWV) * kRedFloatsPerWave];
-        if (sa.vpart != nullptr) shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, sRed);
+        if (sa.vpart != nullptr) shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, sRed, spf);
     }
 }
 
@@ -365,8 +380,8 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
     switch (variant) {
         case 1:
             tiles(256, 256);
-            *name = "gemm_fused_256x256_w8";
-            return launch_one<256, 256, 2, 4, true, 4>(a, none, stream);
+            *name = "gemm_fused_256x256_w4";
+            return launch_one<256, 256, 2, 2, true, 4>(a, none, stream);
         case 2:
             tiles(256, 256);
             *name = "gemm_fused_256x256_w4_s3";
@@ -377,8 +392,8 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
             return launch_one<128, 128, 2, 2, true, 4>(a, none, stream);
         default:
             tiles(256, 256);
-            *name = "gemm_fused_256x256_w4";
-            return launch_one<256, 256, 2, 2, true, 4>(a, none, stream);
+            *name = "gemm_fused_256x256_w8";
+            return launch_one<256, 256, 2, 4, true, 4>(a, none, stream);
     }
 }
 
@@ -403,6 +418,10 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
             tiles(128, 128);
             *name = "gemm_splitk_shrink_128x128_w4";
             return launch_one<128, 128, 2, 2, false, 5>(a, sa, stream);
+        case 4:
+            tiles(128, 128);
+            *name = "gemm_splitk_shrink_128x128_w4_s8";
+            return launch_one<128, 128, 2, 2, false, 8>(a, sa, stream);
         default:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w8";

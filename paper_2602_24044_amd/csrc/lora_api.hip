@@ -34,7 +34,7 @@ struct Layout {
     size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
     size_t off_row_rank = 0, off_row_scale = 0;
     size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
-           off_piece_slot = 0, off_tok_key = 0, off_vpart = 0, off_part = 0;
+           off_piece_slot = 0, off_piece_info = 0, off_tok_key = 0, off_vpart = 0, off_part = 0;
     size_t vpart_elems = 0, part_elems = 0;
     size_t total = 0;
 };
@@ -58,6 +58,9 @@ bool valid_config(const lora_config* c)
     for (int p = 0; p < c->n_proj; ++p) {
         if (c->proj[p].d_in < 64 || c->proj[p].d_in % 64) return false;
         if (c->proj[p].d_out < 8 || c->proj[p].d_out % 8) return false;
+        // tile copies address x and W with 32-bit element offsets
+        if ((uint64_t)c->max_tokens * (uint64_t)c->proj[p].d_in >= (1ull << 32)) return false;
+        if ((uint64_t)c->proj[p].d_out * (uint64_t)c->proj[p].d_in >= (1ull << 32)) return false;
     }
     return true;
 }
@@ -92,6 +95,7 @@ Layout make_layout(const lora_config* c)
     const size_t max_pieces = Tm + Tm / kPieceRows + 2;
     L.off_piece_start = take(4 * (max_pieces + 1));
     L.off_piece_slot = take(4 * max_pieces);
+    L.off_piece_info = take(16 * max_pieces);
     L.off_tok_key = take(4 * Tm);
     const size_t Ts = std::min<size_t>(Tm, kSplitMaxTokens);
     const size_t kc_max = std::min<size_t>(kMaxShrinkChunks, ((size_t)k_max + kShrinkKC - 1) / kShrinkKC);
@@ -176,6 +180,7 @@ struct lora_ctx {
         v.piece_start = dev<int32_t>(L.off_piece_start);
         v.piece_slot = dev<int32_t>(L.off_piece_slot);
         v.n_pieces = d_n_pieces();
+        v.piece_info = dev<int32_t>(L.off_piece_info);
         v.T = T;
         v.max_rank = cfg.max_rank;
         return v;
@@ -496,6 +501,7 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     a.piece_start = c->dev<int32_t>(c->L.off_piece_start);
     a.piece_slot = c->dev<int32_t>(c->L.off_piece_slot);
     a.n_pieces = c->d_n_pieces();
+    a.piece_info = c->dev<int32_t>(c->L.off_piece_info);
     a.tok_key = c->dev<int32_t>(c->L.off_tok_key);
     a.flags = c->d_flags();
     c->last_launches.clear();
@@ -548,11 +554,15 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     }
     const int Mpad = (T + 255) / 256 * 256;
     int S = 1;
+    int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
     if (split) {
-        const int sv = c->tune[LORA_TUNE_SPLIT_VARIANT];
-        const int bm = sv == 3 ? 128 : 256, bn = sv == 2 ? 64 : 128;
+        // narrow projections (k, v) fill the chip better with square 128 x 128 tiles
+        if (split_variant == 0 && N <= 2048) split_variant = 3;
+        const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
         const int tiles = ((T + bm - 1) / bm) * ((N + bn - 1) / bn);
-        S = c->cfg.split_k > 0 ? c->cfg.split_k : std::max(1, std::min(16, (256 + tiles / 2) / tiles));
+        // enough K splits to give every CU a workgroup, but no more than 8: each split costs a pass of
+        // fp32 partial tiles through memory
+        S = c->cfg.split_k > 0 ? c->cfg.split_k : std::max(1, std::min(8, (256 + tiles / 2) / tiles));
         S = std::min(S, std::max(1, (K / kBK) / 2));
         const size_t Npad = align_up((size_t)N, 32);
         const size_t cap = c->L.part_elems / ((size_t)Mpad * Npad);
@@ -614,7 +624,7 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         {
             LaunchScope ls(c, s, "gemm_splitk");
             const char* name = nullptr;
-            if (HIP_FAIL(launch_gemm_splitk(ga, sa, c->tune[LORA_TUNE_SPLIT_VARIANT], s, &name))) return LORA_ERR_HIP;
+            if (HIP_FAIL(launch_gemm_splitk(ga, sa, split_variant, s, &name))) return LORA_ERR_HIP;
             ls.rename(name);
         }
         ReduceArgs ra;

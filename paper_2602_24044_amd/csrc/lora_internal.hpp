@@ -33,6 +33,7 @@ struct DeviceView {
     const int32_t* piece_start;// [n_pieces + 1]
     const int32_t* piece_slot; // [n_pieces]
     const int32_t* n_pieces;   // [1]
+    const int32_t* piece_info; // [n_pieces][4]: first grouped row, rows, slot, rank (one 16-byte load)
     int32_t T;
     int32_t max_rank;
 };
@@ -56,6 +57,7 @@ struct BucketArgs {
     int32_t* piece_start;
     int32_t* piece_slot;
     int32_t* n_pieces;
+    int32_t* piece_info;
     int32_t* tok_key;
     uint32_t* flags;
 };

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStride + k);
         return as_bf16x8(v);
     };
-    expand_window<1>(acc, my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vfrag);
+    expand_window_pipelined(acc[0], my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vfrag);
 
     if (m_ok) {
         uint16_t* orow = a.out + (size_t)a.dv.perm[m] * N;

@@ -1,0 +1,64 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times (automatic path):
+segment maps bit-exact against the oracle, outputs checked on sampled (token, column) pairs that the
+oracle evaluates one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, announce, check_segments
+from paper_2602_24044_amd import binding as B
+from paper_2602_24044_amd import workloads as wl
+from paper_2602_24044_amd.runtime import Session, bf16_tensor_to_bits
+
+pytestmark = pytest.mark.gpu
+
+N_SAMPLES = 1500
+
+
+def _run_full(w, n_samples=N_SAMPLES):
+    announce(f"full-size {w.name} T={w.T} proj={w.proj}")
+    sess = Session(w)
+    try:
+        sess.load(w.resident)
+        if w.missing:
+            sess.load(w.missing, in_use=w.distinct_adapters())
+        sess.bucket()
+        assert check_segments(sess, w) == 0
+        rng = np.random.default_rng(12345)
+        for p, (d_in, d_out) in enumerate(w.proj):
+            out = sess.forward(p)
+            torch.cuda.synchronize()
+            got_all = bf16_tensor_to_bits(out)
+            ts = rng.integers(0, w.T, size=n_samples).astype(np.int32)
+            ns = rng.integers(0, d_out, size=n_samples).astype(np.int32)
+            # always include the first and last token / column (tile edges)
+            ts[:4] = [0, 0, w.T - 1, w.T - 1]
+            ns[:4] = [0, d_out - 1, 0, d_out - 1]
+            y_ref = oracle.project_at(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p), ts, ns)
+            got = wl.bf16_bits_to_f64(got_all[ts, ns])
+            # scale of the projection: the largest sampled reference magnitude (a lower bound of max|y_ref|)
+            err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
+            announce(f"  proj {p} {w.proj[p]} launches={B.lora_last_launches(sess.ctx)} sampled rel_err={err:.3e}")
+            assert err <= TOL, (p, err)
+            assert np.isfinite(wl.bf16_bits_to_f32(got_all)).all()
+        st, word = B.lora_poll_device_flags(sess.ctx)
+        assert st == B.LORA_OK and word == 0
+    finally:
+        sess.close()
+
+
+def test_config2_full():
+    _run_full(wl.config2())
+
+
+def test_config4_full():
+    _run_full(wl.config4())
+
+
+def test_config3_full():
+    _run_full(wl.config3(), n_samples=800)
+
+
+def test_config5_full():
+    _run_full(wl.config5(), n_samples=800)
