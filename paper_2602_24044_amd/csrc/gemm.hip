@@ -61,11 +61,14 @@ __device__ inline void wait_copies_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
-__global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
+// PW > 0 adds PW producer waves that do nothing but issue the tile copies; the WGM x WGN compute waves
+// then never sit behind a copy instruction that the memory pipeline has not accepted yet.
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PW = 0>
+__global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
 {
-    constexpr int NT = WGM * WGN * kWave;
-    constexpr int NWV = NT / kWave;
+    constexpr int NCW = WGM * WGN;                          // compute waves
+    constexpr int NWV = NCW + PW;                           // all waves
+    constexpr int NT = NWV * kWave;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
     constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
     constexpr int STAGE = (BM + BN) * kTK;                  // elements per stage
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     // copy instruction by a full memory pipeline cannot issue its MFMAs; with two waves per SIMD the other
     // one keeps the matrix core busy meanwhile (measured: a few percent on the compute-bound shapes, none
     // on the split path, where every wave copies).
-    constexpr int CW = (FUSED && NWV > 4) ? 4 : NWV;
+    constexpr int CW = PW > 0 ? PW : ((FUSED && NWV > 4) ? 4 : NWV);
     constexpr int XQ = BM / 16 / CW, WQ = BN / 16 / CW;     // copy instructions per copying wave and tile
     constexpr int QPT = XQ + WQ;
     static_assert(BM % (16 * CW) == 0 && BN % (16 * CW) == 0, "tile/waves");
@@ -86,7 +89,9 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const int wm = wave % WGM, wn = wave / WGM;
+    const bool producer = PW > 0 && wave >= NCW;
+    const int cwave = PW > 0 ? wave - NCW : wave;           // index among the copying waves
+    const int wm = wave % WGM, wn = (wave / WGM) % WGN;
     const int T = a.dv.T, N = a.N, K = a.K;
 
     // blockIdx -> (split, tile_m, tile_n).  Consecutive blockIdx values land on different XCDs, so
@@ -124,13 +129,13 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes in tile 0
 #pragma unroll
     for (int q = 0; q < XQ; ++q) {
-        int m = m0 + (wave * XQ + q) * 16 + cp_row;
+        int m = m0 + (cwave * XQ + q) * 16 + cp_row;
         if (m > T - 1) m = T - 1;
         xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
     }
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
-        int n = n0 + (wave * WQ + q) * 16 + cp_row;
+        int n = n0 + (cwave * WQ + q) * 16 + cp_row;
         if (n > N - 1) n = N - 1;
         woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
     }
@@ -157,11 +162,11 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
     const int sw = (i >> 2) & 3;                              // (row >> 2) & 3 of every row this lane reads
     constexpr int NM = MB * NB;                               // MFMAs per K step
     constexpr int NR = MB + NB;                               // LDS reads per K step
-    const uint32_t cp_x = ring_addr + wave * XQ * 1024;       // this wave's first x / W copy target in stage 0
-    const uint32_t cp_w = ring_addr + BM * kTK * 2 + wave * WQ * 1024;
+    const uint32_t cp_x = ring_addr + cwave * XQ * 1024;      // this wave's first x / W copy target in stage 0
+    const uint32_t cp_w = ring_addr + BM * kTK * 2 + cwave * WQ * 1024;
     const int rd_lane[2] = {i * kTK + ((0 * 2 + h) ^ sw) * 8, i * kTK + ((1 * 2 + h) ^ sw) * 8};
 
-    const bool copier = wave < CW;
+    const bool copier = PW > 0 ? producer : wave < CW;
     auto copy_one = [&](int stage, int q, uint32_t k0) {      // q: compile-time constant at every call site
         if (!copier) return;
         const uint32_t so = (uint32_t)stage * (STAGE * 2);
@@ -248,57 +253,101 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
         }
     };
 
-    // Prologue: tiles 0 .. NS - 3 in full and the first half of tile NS - 2 (its second half follows in
-    // K step 0 of iteration 0, exactly as in the steady state).
-    const bool steady = nk >= NS;              // at least one steady-state iteration exists
-    if (nk > 0) {
-        static_for<NS - 2>([&](auto d) {
-            if (d.value < nk) {
-                static_for<QPT>([&](auto q) { copy_one(d.value, q.value, (uint32_t)d.value * kTK); });
+    if constexpr (PW > 0) {
+        // Specialised waves.  Tile t lives in stage t % NS; barrier b (b = 0 .. nk) publishes tile b and
+        // frees the stage of tile b - 2 ... the producers wait for their own copies of tile b, join the
+        // barrier, then refill the stage of tile b - 1 with tile b + NS - 2.
+        if (producer) {
+            static_for<NS - 1>([&](auto d) {
+                if (d.value < nk) {
+                    static_for<QPT>([&](auto q) { copy_one(d.value, q.value, (uint32_t)d.value * kTK); });
+                }
+            });
+            if (nk > 0) {
+                int young = nk - 1;
+                if (young > NS - 2) young = NS - 2;
+                wait_barrier(young);                                  // barrier 0: tile 0 is complete
             }
-        });
-        if (NS - 2 < nk) {
-            if (steady) {
-                static_for<QA>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
-            } else {
-                static_for<QPT>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
+            int fre = NS - 1;                                          // stage of tile j - 1
+            for (int j = 0; j < nk; ++j) {
+                int young = nk - 2 - j;
+                if (young < 0) young = 0;
+                if (young > NS - 3) young = NS - 3;
+                wait_barrier(young);                                  // barrier j + 1: tile j + 1 is complete
+                if (j + NS - 1 < nk) {
+                    const uint32_t k0 = (uint32_t)(j + NS - 1) * kTK;
+                    static_for<QPT>([&](auto q) { copy_one(fre, q.value, k0); });
+                }
+                fre = (fre + 1 == NS) ? 0 : fre + 1;
+            }
+        } else {
+            if (nk > 0) {
+                wait_copies_then_barrier<0>();                        // barrier 0
+                static_for<NR>([&](auto r) { read_one(I0{}, 0, 0, r.value); });
+            }
+            int cur = 0, nxt = 1 % NS;
+            for (int j = 0; j < nk; ++j) {
+                // compute waves issue no copies: iteration<false> with nothing of their own to wait for
+                iteration(std::false_type{}, nk, cur, nxt, 0, 0);
+                cur = nxt;
+                nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
             }
         }
-        // wait for tile 0: everything younger may stay in flight
-        int young_instr = 0;
+    } else {
+        // Prologue: tiles 0 .. NS - 3 in full and the first half of tile NS - 2 (its second half follows in
+        // K step 0 of iteration 0, exactly as in the steady state).
+        const bool steady = nk >= NS;              // at least one steady-state iteration exists
+        if (nk > 0) {
+            static_for<NS - 2>([&](auto d) {
+                if (d.value < nk) {
+                    static_for<QPT>([&](auto q) { copy_one(d.value, q.value, (uint32_t)d.value * kTK); });
+                }
+            });
+            if (NS - 2 < nk) {
+                if (steady) {
+                    static_for<QA>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
+                } else {
+                    static_for<QPT>([&](auto q) { copy_one(NS - 2, q.value, (uint32_t)(NS - 2) * kTK); });
+                }
+            }
+            // wait for tile 0: everything younger may stay in flight
+            int young_instr = 0;
+            {
+                const int full = (nk - 1 < NS - 3) ? nk - 1 : NS - 3;      // complete younger tiles among 1 .. NS - 3
+                young_instr = (full > 0 ? full : 0) * QPT;
+                if (NS - 2 < nk && NS - 2 >= 1) young_instr += steady ? QA : QPT;
+            }
+            // round the allowance down to a multiple the wait helper knows (waiting for more is always safe)
+            wait_barrier(young_instr / QPT > NS - 2 ? NS - 2 : young_instr / QPT);
+            static_for<NR>([&](auto r) { read_one(I0{}, 0, 0, r.value); });
+        }
         {
-            const int full = (nk - 1 < NS - 3) ? nk - 1 : NS - 3;      // complete younger tiles among 1 .. NS - 3
-            young_instr = (full > 0 ? full : 0) * QPT;
-            if (NS - 2 < nk && NS - 2 >= 1) young_instr += steady ? QA : QPT;
-        }
-        // round the allowance down to a multiple the wait helper knows (waiting for more is always safe)
-        wait_barrier(young_instr / QPT > NS - 2 ? NS - 2 : young_instr / QPT);
-        static_for<NR>([&](auto r) { read_one(I0{}, 0, 0, r.value); });
-    }
-    {
-        int cur = 0, nxt = 1 % NS, fre1 = NS - 1, fre0 = NS - 2;
-        int j = 0;
-        auto advance = [&]() {
-            fre0 = fre1;
-            fre1 = cur;
-            cur = nxt;
-            nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
-        };
-        if (steady) {
-            for (; j + NS - 1 < nk; ++j) {    // steady state: one tile copy issued per iteration
-                iteration(std::true_type{}, j, cur, nxt, fre0, fre1);
+            int cur = 0, nxt = 1 % NS, fre1 = NS - 1, fre0 = NS - 2;
+            int j = 0;
+            auto advance = [&]() {
+                fre0 = fre1;
+                fre1 = cur;
+                cur = nxt;
+                nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
+            };
+            if (steady) {
+                for (; j + NS - 1 < nk; ++j) {    // steady state: one tile copy issued per iteration
+                    iteration(std::true_type{}, j, cur, nxt, fre0, fre1);
+                    advance();
+                }
+                // the first half of tile nk - 1 is out; send its second half before draining
+                static_for<QB>([&](auto q) { copy_one(fre0, QA + q.value, (uint32_t)(nk - 1) * kTK); });
+            }
+            for (; j < nk; ++j) {                 // drain: the remaining tiles are already on their way
+                iteration(std::false_type{}, j, cur, nxt, fre0, fre1);
                 advance();
             }
-            // the first half of tile nk - 1 is out; send its second half before draining
-            static_for<QB>([&](auto q) { copy_one(fre0, QA + q.value, (uint32_t)(nk - 1) * kTK); });
         }
-        for (; j < nk; ++j) {                 // drain: the remaining tiles are already on their way
-            iteration(std::false_type{}, j, cur, nxt, fre0, fre1);
-            advance();
-        }
+
     }
 
     // ---------------- epilogue ----------------
+    if (!producer) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m0 + wm * WTM + mb * 32 + i;      // grouped row of this lane
@@ -350,18 +399,24 @@ __global__ __launch_bounds__(WGM * WGN * kWave) void gemm_kernel(GemmArgs a, Shr
         }
     }
 
-    // split path: this workgroup's share of the shrink work items of the same projection
+    }   // !producer
+
+    // split path: this workgroup's share of the shrink work items of the same projection.  The ring is
+    // idle by now (every copy has landed and been read), so its first bytes serve the cross-wave sums.
     if (!FUSED) {
-        __shared__ __attribute__((aligned(16))) float sRed[(FUSED ? 1 : NWV) * kRedFloatsPerWave];
-        if (sa.vpart != nullptr) shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, sRed, spf);
+        static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
+        if (sa.vpart != nullptr) {
+            __syncthreads();
+            shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
+        }
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PW = 0>
 hipError_t launch_one(const GemmArgs& a, const ShrinkArgs& sa, hipStream_t stream)
 {
-    constexpr int NT = WGM * WGN * kWave;
-    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS>;
+    constexpr int NT = (WGM * WGN + PW) * kWave;
+    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS, PW>;
     const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), 0, stream, a, sa);
     return hipGetLastError();
@@ -422,6 +477,10 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
             tiles(128, 128);
             *name = "gemm_splitk_shrink_128x128_w4_s8";
             return launch_one<128, 128, 2, 2, false, 8>(a, sa, stream);
+        case 5:
+            tiles(256, 128);
+            *name = "gemm_splitk_shrink_256x128_w8p4";
+            return launch_one<256, 128, 4, 2, false, 5, 4>(a, sa, stream);
         default:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w8";
