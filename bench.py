@@ -22,16 +22,18 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def kernel_algorithmic_bytes(w, kernel: str) -> float:
-    """Bytes one layer-step's launches of `kernel` must move (all seven projections): each array
-    counted once, in the kernel that has to touch it; split-K partials and re-reads are not counted."""
+def kernel_algorithmic_bytes(w, kernel: str, projections) -> float:
+    """Bytes one layer-step's launches of `kernel` must move (over the projections that launch it): each
+    array counted once, in the kernel that has to touch it; split-K partials and re-reads are not counted."""
     used = w.distinct_adapters()
     rank_sum = sum(w.adapters[a].rank for a in used)
     T = w.T
     tot = 0.0
-    for (d_in, d_out) in w.proj:
+    for p in projections:
+        d_in, d_out = w.proj[p]
         if kernel.startswith("gemm_splitk"):
-            tot += 2.0 * d_in * d_out + 2.0 * T * d_in
+            # W once, x once, and (the shrink shares this launch) every used adapter's A once
+            tot += 2.0 * d_in * d_out + 2.0 * T * d_in + 2.0 * rank_sum * d_in
         elif kernel.startswith("gemm_fused"):
             tot += 2.0 * d_in * d_out + 2.0 * T * d_in + 2.0 * T * d_out + 2.0 * rank_sum * d_out
         elif kernel == "reduce_expand":
@@ -41,11 +43,62 @@ def kernel_algorithmic_bytes(w, kernel: str) -> float:
     return tot
 
 
-def kernel_flops(w, kernel: str) -> float:
+def kernel_flops(w, kernel: str, projections) -> float:
     T = w.T
     if kernel.startswith("gemm"):
-        return float(sum(2.0 * T * d_in * d_out for (d_in, d_out) in w.proj))
+        return float(sum(2.0 * T * w.proj[p][0] * w.proj[p][1] for p in projections))
     return 0.0
+
+
+def kernel_sources_sha256() -> str:
+    """Hash of the HIP sources: a stored counter measurement only counts while the kernels are unchanged."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2602_24044_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def stored_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE,
+    each scaled by what the same counter reads for a plain copy kernel of known size), or None when there
+    is no summary for this kernel and workload or the kernel sources have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_{kernel}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            k, _, v = line.partition(":")
+            kv[k.strip().strip("`")] = v.strip().strip("`")
+    if kv.get("sources_sha256") != kernel_sources_sha256():
+        return None
+    try:
+        return float(kv["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def calibrate_copy():
+    """A plain device copy kernel of known size (256 MiB read + 256 MiB written per launch), ten launches:
+    run under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` to get the factor between what the counter
+    reads and the bytes actually moved."""
+    import torch
+    n = 256 << 20
+    src = torch.empty(n // 4, dtype=torch.int32, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    # evict the source from the last-level cache between launches with a second, larger pair
+    big_a = torch.empty(n, dtype=torch.int32, device="cuda").fill_(2)
+    big_b = torch.empty_like(big_a)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        big_b.copy_(big_a)
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read_per_launch": n, "copy_bytes_written_per_launch": n,
+                      "big_copy_bytes_per_launch": 4 * n, "launches": 10}))
 
 
 def cpu_baseline(w, budget_s: float = 15.0):
@@ -81,11 +134,17 @@ def main():
     ap.add_argument("--shrink", type=int, default=1, help="divide the model dimensions (debugging only)")
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run plain device copy kernels of known size and exit (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; the path shards by adapter with no exchange, "
               "so --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.calibrate_copy:
+        calibrate_copy()
+        return
 
     import torch
     from paper_2602_24044_amd import binding as B
@@ -160,12 +219,23 @@ def main():
     kernels = {k: {"avg_us": ms / cnt * 1e3, "launches_per_step": cnt / args.steps,
                    "us_per_step": ms / args.steps * 1e3} for k, (ms, cnt) in prof.items() if cnt}
     dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    # which projections launch the dominant kernel
+    launched_by = []
+    s0 = sessions[0]
+    s0.bucket()
+    for p in range(len(w.proj)):
+        s0.forward(p)
+        if dominant in B.lora_last_launches(s0.ctx):
+            launched_by.append(p)
+    torch.cuda.synchronize()
     dom_t = kernels[dominant]["us_per_step"] * 1e-6
-    dom_bytes = kernel_algorithmic_bytes(w, dominant)
-    dom_flops = kernel_flops(w, dominant)
+    dom_bytes = kernel_algorithmic_bytes(w, dominant, launched_by)
+    dom_flops = kernel_flops(w, dominant, launched_by)
     achieved_gbs = dom_bytes / dom_t / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": stored_traffic(dominant, w.name),
+                "projections": [w.proj_names[p] for p in launched_by] if hasattr(w, "proj_names") else launched_by,
+                "algorithmic_bytes_per_launch": dom_bytes / max(1, len(launched_by)),
                 "launch_avg_us": kernels[dominant]["avg_us"],
                 "mfma_tflops": dom_flops / dom_t / 1e12, "mfma_frac": dom_flops / dom_t / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     if args.config in (3, 5):

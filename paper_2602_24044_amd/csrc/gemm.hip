@@ -391,7 +391,8 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
                         for (int g = 0; g < 4; ++g) {
                             f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
                                        acc[mb][nb][g * 4 + 3]};
-                            *reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4) = o;
+                            // read once by another kernel: keep the tiles from lingering dirty in L2
+                            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4));
                         }
                     }
                 }

@@ -572,6 +572,16 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
     int n_kc = 1, kc_len = K;
     if (T <= kSplitMaxTokens) {
         n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
+        if (split) {
+            // The shrink items (piece x K chunk) are shared out over the workgroups of the split GEMM, each
+            // item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup one
+            // item (when there are more pieces than workgroups, fine chunks balance better and stay).  The
+            // piece count is only known on the device; this is its upper bound.
+            const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
+            const long wgs = (long)((T + bm - 1) / bm) * ((N + bn - 1) / bn) * S;
+            const long pieces = std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+            if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
+        }
         kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
         n_kc = (K + kc_len - 1) / kc_len;
     }
