@@ -446,6 +446,10 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
             tiles(128, 128);
             *name = "gemm_fused_128x128_w4";
             return launch_one<128, 128, 2, 2, true, 4>(a, none, stream);
+        case 4:
+            tiles(256, 128);
+            *name = "gemm_fused_256x128_w8";
+            return launch_one<256, 128, 4, 2, true, 5>(a, none, stream);
         default:
             tiles(256, 256);
             *name = "gemm_fused_256x256_w8";

@@ -46,6 +46,21 @@ int auto_split_cap(int N)
     return std::max(1, std::min(16, s));
 }
 
+// Tile shape of the fused GEMM: rounds of workgroups over the 256 CUs times the cost of one tile, with the
+// per-flop efficiencies measured for the three shapes (256x256: 1, 256x128: 0.78, 128x128: 0.65).  Large
+// problems take the big tile; a projection with few big tiles (k/v at a few thousand tokens) fills the chip
+// better with small ones.
+int pick_fused_variant(int T, int N)
+{
+    auto rounds = [&](int bm, int bn) {
+        const long tiles = (long)((T + bm - 1) / bm) * ((N + bn - 1) / bn);
+        return (double)((tiles + 255) / 256);
+    };
+    const double big = rounds(256, 256) * 1.0, mid = rounds(256, 128) * (0.5 / 0.78), small = rounds(128, 128) * (0.25 / 0.65);
+    if (big <= mid * 1.1 && big <= small * 1.1) return 0;      // near ties go to the big tile (measured)
+    return mid <= small ? 4 : 3;
+}
+
 bool valid_config(const lora_config* c)
 {
     if (!c || !c->proj) return false;
@@ -627,7 +642,9 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         }
         LaunchScope ls(c, s, "gemm_fused");
         const char* name = nullptr;
-        if (HIP_FAIL(launch_gemm_fused(ga, c->tune[LORA_TUNE_FUSED_VARIANT], s, &name))) return LORA_ERR_HIP;
+        int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
+        if (fv == 0) fv = pick_fused_variant(T, N);
+        if (HIP_FAIL(launch_gemm_fused(ga, fv, s, &name))) return LORA_ERR_HIP;
         ls.rename(name);
     } else {
         // ---- split-K base GEMM + shrink in one launch, then reduce + expand ----
