@@ -171,6 +171,16 @@ lora_status lora_bucket(lora_ctx *ctx, const int32_t *d_token_adapter, int32_t T
 lora_status lora_layer_forward(lora_ctx *ctx, int32_t proj, const void *d_x, const void *d_W,
                                const lora_segments *seg, void *d_out, void *stream);
 
+/* Packed projections (paper Sec. 2.2 applied to projections that are computed from one layer input side by
+ * side, such as q|k|v and gate|up): the same result as n calls of lora_layer_forward for projs[0..n-1] in
+ * order, served by shared launches.  1 <= n <= 4, the projections must be distinct and share d_in
+ * (LORA_ERR_SHAPE otherwise); d_x[k], d_W[k], d_out[k] are the device pointers of projection projs[k] (the x
+ * pointers may be equal or different), layouts and alignment as for lora_layer_forward; the three pointer
+ * arrays live in host memory and are read before the call returns.  Asynchronous on `stream`. */
+lora_status lora_layer_forward_group(lora_ctx* ctx, int32_t n, const int32_t* projs, const void* const* d_x,
+                                     const void* const* d_W, const lora_segments* seg, void* const* d_out,
+                                     void* stream);
+
 /* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
  * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set, else LORA_OK; *flags (may be NULL)
  * receives the raw word. */

@@ -61,6 +61,7 @@ LORA_CREATE_HOST_ONLY = 1
 
 EXPORTS = [
     "lora_slab_bytes", "lora_create", "lora_destroy", "lora_slots_load", "lora_bucket", "lora_layer_forward",
+    "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
     "lora_last_hip_error", "lora_set_tuning",
@@ -106,6 +107,9 @@ _lib.lora_bucket.restype = ctypes.c_int
 _lib.lora_bucket.argtypes = [_P, _P, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(lora_segments), _P]
 _lib.lora_layer_forward.restype = ctypes.c_int
 _lib.lora_layer_forward.argtypes = [_P, ctypes.c_int32, _P, _P, ctypes.POINTER(lora_segments), _P, _P]
+_lib.lora_layer_forward_group.restype = ctypes.c_int
+_lib.lora_layer_forward_group.argtypes = [_P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_P),
+                                          ctypes.POINTER(_P), ctypes.POINTER(lora_segments), ctypes.POINTER(_P), _P]
 _lib.lora_poll_device_flags.restype = ctypes.c_int
 _lib.lora_poll_device_flags.argtypes = [_P, ctypes.POINTER(ctypes.c_uint32), _P]
 _lib.lora_slot_of.restype = ctypes.c_int32
@@ -216,6 +220,18 @@ def lora_layer_forward(ctx: int, proj: int, d_x: int, d_W: int, seg: lora_segmen
                                  _P(d_out or None), _P(stream or None))
     if st != LORA_OK:
         raise LoraError(st, "lora_layer_forward")
+
+
+def lora_layer_forward_group(ctx: int, projs: Sequence[int], d_x: Sequence[int], d_W: Sequence[int],
+                             seg: lora_segments, d_out: Sequence[int], stream: int = 0) -> None:
+    n = len(projs)
+    pa = (ctypes.c_int32 * n)(*[int(p) for p in projs])
+    xa = (_P * n)(*[_P(v or None) for v in d_x])
+    wa = (_P * n)(*[_P(v or None) for v in d_W])
+    oa = (_P * n)(*[_P(v or None) for v in d_out])
+    st = _lib.lora_layer_forward_group(_P(ctx), n, pa, xa, wa, ctypes.byref(seg), oa, _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_layer_forward_group")
 
 
 def lora_poll_device_flags(ctx: int, stream: int = 0) -> Tuple[int, int]:

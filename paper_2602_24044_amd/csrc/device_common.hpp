@@ -81,6 +81,17 @@ __device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0,
 constexpr int kRedStride = 36;   // floats per LDS row of the cross-wave reduction (144 bytes: conflict-free)
 constexpr int kRedFloatsPerWave = kPieceRows * kRedStride;
 
+// Slice si of a packed group, picked with uniform selects over statically addressed kernel arguments (a
+// dynamically indexed argument array would be fetched per lane and double the register count).
+__device__ inline Slice pick_slice(const GroupArgs& g, int si)
+{
+    Slice r = g.s[0];
+#pragma unroll
+    for (int k = 1; k < kMaxGroup; ++k)
+        if (si == k) r = g.s[k];
+    return r;
+}
+
 // What the first work item of a workgroup needs before it can issue its operand loads; fetched at kernel
 // start so that the chain item -> piece record -> perm -> x is off the critical path later.
 struct ShrinkPrefetch {
@@ -89,15 +100,17 @@ struct ShrinkPrefetch {
     int tok;       // perm[rec.x + lane % 32]
 };
 
+// Work items are numbered (slice, piece, K chunk), the chunk fastest.
 __device__ inline ShrinkPrefetch shrink_prefetch(const ShrinkArgs& a, int first_item)
 {
     ShrinkPrefetch pf;
     const int i = threadIdx.x & 31;
-    pf.n_items = *a.dv.n_pieces * a.n_kc;
+    const int n_pieces = *a.dv.n_pieces;
+    pf.n_items = a.g.n * n_pieces * a.n_kc;
     pf.rec = int4{0, 0, -1, 0};
     pf.tok = 0;
     if (first_item < pf.n_items) {
-        pf.rec = reinterpret_cast<const int4*>(a.dv.piece_info)[first_item / a.n_kc];
+        pf.rec = reinterpret_cast<const int4*>(a.dv.piece_info)[(first_item / a.n_kc) % n_pieces];
         if (i < pf.rec.y) pf.tok = a.dv.perm[pf.rec.x + i];
     }
     return pf;
@@ -116,9 +129,13 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
     const int i = lane & 31, h = lane >> 5;
     const int n_items = pf.n_items;
     const int K = a.K;
+    const int n_pieces = n_items / (a.g.n * a.n_kc);
     for (int item = first_item; item < n_items; item += stride) {
-        const int piece = item / a.n_kc;
-        const int kc = item - piece * a.n_kc;
+        const int pk = item / a.n_kc;
+        const int kc = item - pk * a.n_kc;
+        const int si = pk / n_pieces;                       // slice (projection of a packed group)
+        const int piece = pk - si * n_pieces;
+        const Slice sl = pick_slice(a.g, si);
         int4 rec;
         int tok;
         if (item == first_item) {
@@ -140,8 +157,8 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
         if (k_end > c_end) k_end = c_end;
 
         const bool x_ok = i < nrows;
-        const uint16_t* xrow = a.x + (size_t)tok * K + h * 32;
-        const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + a.a_off;
+        const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
+        const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + sl.a_off;
         const bool a0_ok = i < r, a1_ok = (32 + i) < r;
         const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
         const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
@@ -174,7 +191,7 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
                     sum += *reinterpret_cast<const f32x4*>(sRed + w * kRedFloatsPerWave + row * kRedStride + j4);
                 const int j = half * 32 + j4;
                 if (row < nrows && j < r)
-                    *reinterpret_cast<f32x4*>(a.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + row)) * a.dv.max_rank + j) = sum;
+                    *reinterpret_cast<f32x4*>(sl.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + row)) * a.dv.max_rank + j) = sum;
             }
             __syncthreads();
         }
@@ -191,47 +208,16 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
 //   VS: functor (k, on, scale) -> bf16x8 with the lane's scaled v[m][k .. k+7] (zeros when !on).
 // my_rank / my_scale are the per-row copies of the slot's rank and scale.
 // ---------------------------------------------------------------------------------------------------
+// The B fragments of the next distinct slot are fetched while the current slot's
+// MFMAs run (a 32-row decode window holds many slots, and each slot's fragments are a dependent global
+// load: without the look-ahead the loop pays one memory latency per slot).  The v fragments must be cheap
+// to produce (LDS), they are asked for inside the loop.
 template <int NB, typename VS>
-__device__ inline void expand_window(f32x16 (&acc)[NB], int my_slot, int my_rank, float my_scale, int n_first, int N,
-                                     const DeviceView& dv, size_t b_off, VS&& vfrag)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int i = lane & 31, h = lane >> 5;
-    unsigned long long todo = __ballot(my_slot >= 0 && my_rank > 0);
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int s = __shfl(my_slot, leader, kWave);
-        const int r = __shfl(my_rank, leader, kWave);
-        const float sc = __shfl(my_scale, leader, kWave);
-        todo &= ~__ballot(my_slot == s);
-        const uint16_t* Bs = dv.slots + (size_t)s * dv.slot_stride + b_off;
-        const bool mine = (my_slot == s);
-        for (int kq = 0; kq < r; kq += 16) {
-            const int k = kq + h * 8;
-            const bool k_ok = k < r;
-            const bf16x8 vf = vfrag(k, mine && k_ok, sc);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int n = n_first + nb * 32 + i;
-                u32x4 bv = {0u, 0u, 0u, 0u};
-                if (k_ok && n < N) bv = load16(Bs + (size_t)n * r + k);
-                acc[nb] = mfma32(as_bf16x8(bv), vf, acc[nb]);
-            }
-        }
-    }
-}
-
-// Same as expand_window for a single 32-column block, with the B fragments of the next distinct slot
-// fetched while the current slot's MFMAs run (a 32-row decode window holds many slots, and each slot's
-// fragments are a dependent global load: without the look-ahead the loop pays one memory latency per slot).
-template <typename VS>
-__device__ inline void expand_window_pipelined(f32x16& acc, int my_slot, int my_rank, float my_scale, int n_first,
+__device__ inline void expand_window_pipelined(f32x16 (&acc)[NB], int my_slot, int my_rank, float my_scale, int n_first,
                                                int N, const DeviceView& dv, size_t b_off, VS&& vfrag)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
-    const int n = n_first + i;
-    const bool n_ok = n < N;
     unsigned long long todo = __ballot(my_slot >= 0 && my_rank > 0);
     struct Slot {
         int s, r;
@@ -250,26 +236,32 @@ __device__ inline void expand_window_pipelined(f32x16& acc, int my_slot, int my_
         }
         return q;
     };
-    auto fetch = [&](const Slot& q, u32x4 (&fb)[4]) {
-        const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
+    auto fetch = [&](const Slot& q, u32x4 (&fb)[NB][4]) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int k = ks * 16 + h * 8;
-            fb[ks] = u32x4{0u, 0u, 0u, 0u};
-            if (q.valid && n_ok && k < q.r) fb[ks] = load16(Bs + k);
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = n_first + nb * 32 + i;
+            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int k = ks * 16 + h * 8;
+                fb[nb][ks] = u32x4{0u, 0u, 0u, 0u};
+                if (q.valid && n < N && k < q.r) fb[nb][ks] = load16(Bs + k);
+            }
         }
     };
-    auto apply = [&](const Slot& q, const u32x4 (&fb)[4]) {
+    auto apply = [&](const Slot& q, const u32x4 (&fb)[NB][4]) {
         const bool mine = (my_slot == q.s);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             if (ks * 16 < q.r) {
                 const int k = ks * 16 + h * 8;
-                acc = mfma32(as_bf16x8(fb[ks]), vfrag(k, mine && k < q.r, q.sc), acc);
+                const bf16x8 vf = vfrag(k, mine && k < q.r, q.sc);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(as_bf16x8(fb[nb][ks]), vf, acc[nb]);
             }
         }
     };
-    u32x4 f0[4], f1[4];
+    u32x4 f0[NB][4], f1[NB][4];
     Slot q0 = next_slot();
     fetch(q0, f0);
     while (q0.valid) {
@@ -283,28 +275,42 @@ __device__ inline void expand_window_pipelined(f32x16& acc, int my_slot, int my_
     }
 }
 
-// v fragment straight from the shrink partials in global memory: sums the K chunks, scales, rounds.
-struct VFromGlobal {
-    const float* vpart;
-    int n_kc, T, max_rank, m;
-    __device__ inline bf16x8 operator()(int k, bool on, float sc) const
-    {
-        f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-        if (on) {
-            for (int c = 0; c < n_kc; ++c) {
-                const float* vp = vpart + ((size_t)c * T + m) * max_rank + k;
-                lo += *reinterpret_cast<const f32x4*>(vp);
-                hi += *reinterpret_cast<const f32x4*>(vp + 4);
+// Stages the scaled shrink results of one 32-row window as bf16 in LDS (sV: 32 rows of kVStageStride
+// elements, private to the calling wavefront): v[row][j] = bf16(scale_row * sum_c vpart[c][row][j]) for
+// j < rank_row, zero beyond.  Returns after the wave's LDS writes have completed, so any lane may read.
+constexpr int kVStageStride = kMaxRank + 8;     // 144-byte rows: conflict-free 16-byte reads
+__device__ inline void stage_window_v(uint16_t* sV, const float* vpart, int n_kc, int win0, const DeviceView& dv)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int T = dv.T;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int idx = lane + 64 * q;
+        const int row = idx >> 3, seg = idx & 7;
+        const int mr = win0 + row;
+        u32x4 packed = {0u, 0u, 0u, 0u};
+        if (mr < T && seg * 8 < dv.max_rank) {
+            const int r = dv.row_rank[mr];
+            const float sc = dv.row_scale[mr];
+            if (seg * 8 < r) {
+                f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < n_kc; ++c) {
+                    const float* vp = vpart + ((size_t)c * T + mr) * dv.max_rank + seg * 8;
+                    lo += *reinterpret_cast<const f32x4*>(vp);
+                    hi += *reinterpret_cast<const f32x4*>(vp + 4);
+                }
+                bf16x8 vb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vb[e] = (__bf16)(lo[e] * sc);
+                    vb[4 + e] = (__bf16)(hi[e] * sc);
+                }
+                packed = __builtin_bit_cast(u32x4, vb);
             }
         }
-        bf16x8 vf;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            vf[e] = (__bf16)(lo[e] * sc);
-            vf[4 + e] = (__bf16)(hi[e] * sc);
-        }
-        return vf;
+        *reinterpret_cast<u32x4*>(sV + row * kVStageStride + seg * 8) = packed;
     }
-};
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
 
 }  // namespace lora

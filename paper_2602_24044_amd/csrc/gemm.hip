@@ -62,10 +62,13 @@ __device__ inline void wait_copies_then_barrier()
 }
 
 // PW > 0 adds PW producer waves that do nothing but issue the tile copies; the WGM x WGN compute waves
-// then never sit behind a copy instruction that the memory pipeline has not accepted yet.
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PW = 0>
-__global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
+// then never sit behind a copy instruction that the memory pipeline has not accepted yet.  PW = -1 (fused
+// path only) lets every wave copy, as on the split path: right for small batches, where the copy rate and
+// not the MFMA issue bounds the loop.
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PWA = 0>
+__global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
 {
+    constexpr int PW = PWA > 0 ? PWA : 0;
     constexpr int NCW = WGM * WGN;                          // compute waves
     constexpr int NWV = NCW + PW;                           // all waves
     constexpr int NT = NWV * kWave;
@@ -76,7 +79,7 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
     // copy instruction by a full memory pipeline cannot issue its MFMAs; with two waves per SIMD the other
     // one keeps the matrix core busy meanwhile (measured: a few percent on the compute-bound shapes, none
     // on the split path, where every wave copies).
-    constexpr int CW = PW > 0 ? PW : ((FUSED && NWV > 4) ? 4 : NWV);
+    constexpr int CW = PW > 0 ? PW : ((FUSED && NWV > 4 && PWA == 0) ? 4 : NWV);
     constexpr int XQ = BM / 16 / CW, WQ = BN / 16 / CW;     // copy instructions per copying wave and tile
     constexpr int QPT = XQ + WQ;
     static_assert(BM % (16 * CW) == 0 && BN % (16 * CW) == 0, "tile/waves");
@@ -92,7 +95,7 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
     const bool producer = PW > 0 && wave >= NCW;
     const int cwave = PW > 0 ? wave - NCW : wave;           // index among the copying waves
     const int wm = wave % WGM, wn = (wave / WGM) % WGN;
-    const int T = a.dv.T, N = a.N, K = a.K;
+    const int T = a.dv.T, K = a.K;
 
     // blockIdx -> (split, tile_m, tile_n).  Consecutive blockIdx values land on different XCDs, so
     // the K split is the fastest index on the split path (every XCD keeps one x K-range in its L2)
@@ -107,11 +110,19 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
         tile_m = b % a.tiles_m;
         tile_n = b / a.tiles_m;
     }
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    // the slice (projection of a packed group) this N tile belongs to; uniform over the workgroup
+    int si = 0;
+    for (int k = 1; k < a.g.n; ++k)
+        if (tile_n >= a.g.s[k].tile0) si = k;
+    const Slice sl = pick_slice(a.g, si);
+    const uint16_t* const xg = sl.x;
+    const uint16_t* const Wg = sl.W;
+    const int N = sl.N;
+    const int m0 = tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
 
     // split path: metadata of this workgroup's first shrink work item, fetched before the main loop
     ShrinkPrefetch spf{};
-    if (!FUSED && sa.vpart != nullptr) spf = shrink_prefetch(sa, blockIdx.x);
+    if (!FUSED && sa.on) spf = shrink_prefetch(sa, blockIdx.x);
 
     const int kt_total = K / kTK;
     int kt_begin = 0, kt_end = kt_total;
@@ -171,9 +182,9 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
         if (!copier) return;
         const uint32_t so = (uint32_t)stage * (STAGE * 2);
         if (q < XQ)
-            copy16_to_lds(a.x + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
+            copy16_to_lds(xg + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
         else
-            copy16_to_lds(a.W + (woff[q - XQ] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + (q - XQ) * 1024));
+            copy16_to_lds(Wg + (woff[q - XQ] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + (q - XQ) * 1024));
     };
     auto read_one = [&](auto f_c, int stage, int kk, int r) { // kk, r: compile-time constants at every call site
         constexpr int Fi = decltype(f_c)::value;
@@ -347,6 +358,10 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
     }
 
     // ---------------- epilogue ----------------
+    // Fused path: the ring is idle once every wave has left the main loop; each wave then parks the scaled
+    // shrink results of one 32-row window at a time in its own piece of it and runs the expand from there.
+    static_assert(!FUSED || NS * STAGE * 2 >= NWV * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    if (FUSED) __syncthreads();
     if (!producer) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -358,13 +373,22 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
             const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
             const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
             const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
-            VFromGlobal vs{a.vpart, a.n_kc, T, a.dv.max_rank, m};
-            expand_window<NB>(acc[mb], my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vs);
+            if (__ballot(my_slot >= 0 && my_rank > 0)) {      // uniform over the wave
+                uint16_t* sV = ring + wave * (kPieceRows * kVStageStride);
+                stage_window_v(sV, sl.vpart, a.n_kc, m0 + wm * WTM + mb * 32, a.dv);
+                auto vfrag = [&](int k, bool on, float) -> bf16x8 {
+                    u32x4 v = {0u, 0u, 0u, 0u};
+                    if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStageStride + k);
+                    return as_bf16x8(v);
+                };
+                expand_window_pipelined<NB>(acc[mb], my_slot, my_rank, my_scale, n_first, N, a.dv, sl.b_off, vfrag);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next window is staged
+            }
         }
 
         if (m_ok) {
             if (FUSED) {
-                uint16_t* orow = a.out + (size_t)a.dv.perm[m] * N;
+                uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -381,12 +405,12 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
                 // fp32 partial tiles are kept block by block in accumulator order: block (m / 32, n / 32)
                 // of split s is 1024 consecutive floats, lane (i, h) owning floats 256 g + 8 i + 4 h .. + 3,
                 // so every store (and the matching load in the reduce kernel) covers 1 KB contiguously
-                const int nblk = (N + 31) / 32;
+                const int nblk_slice = (N + 31) / 32;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int bn = (n_first + nb * 32) / 32;
-                    if (bn < nblk) {
-                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)(m / 32)) * nblk + bn) * 1024;
+                    const int bn = (n_first + nb * 32) / 32;          // block inside the slice
+                    if (bn < nblk_slice) {
+                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)(m / 32)) * a.nblk + sl.blk0 + bn) * 1024;
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
@@ -406,7 +430,7 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
     // idle by now (every copy has landed and been read), so its first bytes serve the cross-wave sums.
     if (!FUSED) {
         static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
-        if (sa.vpart != nullptr) {
+        if (sa.on) {
             __syncthreads();
             shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
         }
@@ -416,7 +440,7 @@ __global__ __launch_bounds__((WGM * WGN + PW) * kWave) void gemm_kernel(GemmArgs
 template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PW = 0>
 hipError_t launch_one(const GemmArgs& a, const ShrinkArgs& sa, hipStream_t stream)
 {
-    constexpr int NT = (WGM * WGN + PW) * kWave;
+    constexpr int NT = (WGM * WGN + (PW > 0 ? PW : 0)) * kWave;
     auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS, PW>;
     const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), 0, stream, a, sa);
@@ -429,9 +453,14 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
 {
     GemmArgs a = a0;
     ShrinkArgs none{};
+    none.on = 0;
     auto tiles = [&](int BM, int BN) {
         a.tiles_m = (a.dv.T + BM - 1) / BM;
-        a.tiles_n = (a.N + BN - 1) / BN;
+        a.tiles_n = 0;
+        for (int k = 0; k < a.g.n; ++k) {
+            a.g.s[k].tile0 = a.tiles_n;
+            a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+        }
     };
     switch (variant) {
         case 1:
@@ -450,6 +479,10 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
             tiles(256, 128);
             *name = "gemm_fused_256x128_w8";
             return launch_one<256, 128, 4, 2, true, 5>(a, none, stream);
+        case 5:
+            tiles(256, 128);
+            *name = "gemm_fused_256x128_w8_allcopy";
+            return launch_one<256, 128, 4, 2, true, 5, -1>(a, none, stream);
         default:
             tiles(256, 256);
             *name = "gemm_fused_256x256_w8";
@@ -463,7 +496,11 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
     GemmArgs a = a0;
     auto tiles = [&](int BM, int BN) {
         a.tiles_m = (a.dv.T + BM - 1) / BM;
-        a.tiles_n = (a.N + BN - 1) / BN;
+        a.tiles_n = 0;
+        for (int k = 0; k < a.g.n; ++k) {
+            a.g.s[k].tile0 = a.tiles_n;
+            a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+        }
     };
     switch (variant) {
         case 1:

@@ -50,12 +50,10 @@ int auto_split_cap(int N)
 // per-flop efficiencies measured for the three shapes (256x256: 1, 256x128: 0.78, 128x128: 0.65).  Large
 // problems take the big tile; a projection with few big tiles (k/v at a few thousand tokens) fills the chip
 // better with small ones.
-int pick_fused_variant(int T, int N)
+template <typename TilesOf>
+int pick_fused_variant(int /*T*/, int /*N*/, TilesOf&& tiles_of)
 {
-    auto rounds = [&](int bm, int bn) {
-        const long tiles = (long)((T + bm - 1) / bm) * ((N + bn - 1) / bn);
-        return (double)((tiles + 255) / 256);
-    };
+    auto rounds = [&](int bm, int bn) { return (double)((tiles_of(bm, bn) + 255) / 256); };
     const double big = rounds(256, 256) * 1.0, mid = rounds(256, 128) * (0.5 / 0.78), small = rounds(128, 128) * (0.25 / 0.65);
     if (big <= mid * 1.1 && big <= small * 1.1) return 0;      // near ties go to the big tile (measured)
     return mid <= small ? 4 : 3;
@@ -114,7 +112,7 @@ Layout make_layout(const lora_config* c)
     L.off_tok_key = take(4 * Tm);
     const size_t Ts = std::min<size_t>(Tm, kSplitMaxTokens);
     const size_t kc_max = std::min<size_t>(kMaxShrinkChunks, ((size_t)k_max + kShrinkKC - 1) / kShrinkKC);
-    L.vpart_elems = std::max(Tm * (size_t)c->max_rank, Ts * (size_t)c->max_rank * kc_max);
+    L.vpart_elems = kMaxGroup * std::max(Tm * (size_t)c->max_rank, Ts * (size_t)c->max_rank * kc_max);
     L.off_vpart = take(4 * L.vpart_elems);
     size_t part_cols = 0;
     for (int p = 0; p < c->n_proj; ++p) {
@@ -539,103 +537,142 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     return LORA_OK;
 }
 
-lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const void* d_W, const lora_segments* seg,
-                               void* d_out, void* stream_v)
+lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,
+                                     const void* const* d_W, const lora_segments* seg, void* const* d_out,
+                                     void* stream_v)
 {
-    if (!c || !seg) return LORA_ERR_INVALID_ARG;
-    if (p < 0 || p >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
+    if (!c || !seg || !projs || n < 1 || n > kMaxGroup) return LORA_ERR_INVALID_ARG;
+    for (int k = 0; k < n; ++k) {
+        if (projs[k] < 0 || projs[k] >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
+        for (int j = 0; j < k; ++j)
+            if (projs[j] == projs[k]) return LORA_ERR_INVALID_ARG;
+        if (c->proj[projs[k]].d_in != c->proj[projs[0]].d_in) return LORA_ERR_SHAPE;
+    }
     if (seg->epoch != c->epoch || seg->T != c->seg_T || c->epoch == 0) return LORA_ERR_INVALID_ARG;
     if (c->host_only) return LORA_ERR_HIP;
     const int32_t T = seg->T;
     c->last_launches.clear();
     if (T == 0) return LORA_OK;
     if (!d_x || !d_W || !d_out) return LORA_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(d_x) | reinterpret_cast<uintptr_t>(d_W) | reinterpret_cast<uintptr_t>(d_out)) & 15)
-        return LORA_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream_v);
-    if (c->proj_pending[p] && s != c->copy_stream) {
-        if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[p], 0))) return LORA_ERR_HIP;
+    for (int k = 0; k < n; ++k) {
+        if (!d_x[k] || !d_W[k] || !d_out[k]) return LORA_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(d_x[k]) | reinterpret_cast<uintptr_t>(d_W[k]) |
+             reinterpret_cast<uintptr_t>(d_out[k])) & 15)
+            return LORA_ERR_INVALID_ARG;
     }
-    const int K = c->proj[p].d_in, N = c->proj[p].d_out;
-
-    // ---- plan ----
-    bool split = false;
-    if (T <= kSplitMaxTokens) {
-        if (c->cfg.path == LORA_PATH_SPLITK) split = true;
-        else if (c->cfg.path == LORA_PATH_AUTO) {
-            const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
-            split = tiles256 < 128;
+    hipStream_t s = static_cast<hipStream_t>(stream_v);
+    for (int k = 0; k < n; ++k) {
+        const int p = projs[k];
+        if (c->proj_pending[p] && s != c->copy_stream) {
+            if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[p], 0))) return LORA_ERR_HIP;
         }
     }
+    const int K = c->proj[projs[0]].d_in;
+    // the slices sit side by side along N, each padded to a multiple of 128 columns
+    long n_pad_total = 0;
+    int n_max = 0;
+    for (int k = 0; k < n; ++k) {
+        n_pad_total += (long)align_up((size_t)c->proj[projs[k]].d_out, 128);
+        n_max = std::max(n_max, c->proj[projs[k]].d_out);
+    }
+    auto tiles_of = [&](int bm, int bn) {
+        long t = 0;
+        for (int k = 0; k < n; ++k) t += (c->proj[projs[k]].d_out + bn - 1) / bn;
+        return t * ((T + bm - 1) / bm);
+    };
+
+    // ---- plan ----
     const int Mpad = (T + 255) / 256 * 256;
+    bool split = false;
     int S = 1;
     int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
+    if (T <= kSplitMaxTokens) {
+        if (c->cfg.path == LORA_PATH_SPLITK) split = true;
+        else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < 128;
+    }
     if (split) {
-        // narrow projections (k, v) fill the chip better with square 128 x 128 tiles
-        if (split_variant == 0 && N <= 2048) split_variant = 3;
+        // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
+        if (split_variant == 0 && n_pad_total <= 2048) split_variant = 3;
         const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
-        const int tiles = ((T + bm - 1) / bm) * ((N + bn - 1) / bn);
+        const long tiles = tiles_of(bm, bn);
         // enough K splits to give every CU a workgroup, but no more than 8: each split costs a pass of
         // fp32 partial tiles through memory
-        S = c->cfg.split_k > 0 ? c->cfg.split_k : std::max(1, std::min(8, (256 + tiles / 2) / tiles));
+        S = c->cfg.split_k > 0 ? c->cfg.split_k : (int)std::max<long>(1, std::min<long>(8, (256 + tiles / 2) / tiles));
         S = std::min(S, std::max(1, (K / kBK) / 2));
-        const size_t Npad = align_up((size_t)N, 32);
-        const size_t cap = c->L.part_elems / ((size_t)Mpad * Npad);
+        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
         S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
-        if ((size_t)S * Mpad * Npad > c->L.part_elems) return LORA_ERR_OOM;
+        if ((size_t)S * Mpad * (size_t)n_pad_total > c->L.part_elems) return LORA_ERR_OOM;
+        // a single K range would only add the round trip of the partial tiles: the launch already fills
+        // the chip, take the fused path with the same tile
+        if (S == 1 && c->cfg.path == LORA_PATH_AUTO) split = false;
     }
     int n_kc = 1, kc_len = K;
     if (T <= kSplitMaxTokens) {
         n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
         if (split) {
-            // The shrink items (piece x K chunk) are shared out over the workgroups of the split GEMM, each
-            // item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup one
-            // item (when there are more pieces than workgroups, fine chunks balance better and stay).  The
-            // piece count is only known on the device; this is its upper bound.
+            // The shrink items (slice x piece x K chunk) are shared out over the workgroups of the split GEMM,
+            // each item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup
+            // one item (when there are more pieces than workgroups, fine chunks balance better and stay).
+            // The piece count is only known on the device; this is its upper bound.
             const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
-            const long wgs = (long)((T + bm - 1) / bm) * ((N + bn - 1) / bn) * S;
-            const long pieces = std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+            const long wgs = tiles_of(bm, bn) * S;
+            const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
             if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
         }
         kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
         n_kc = (K + kc_len - 1) / kc_len;
     }
-    if ((size_t)n_kc * T * c->cfg.max_rank > c->L.vpart_elems) return LORA_ERR_OOM;
+    const size_t vslice = (size_t)n_kc * T * c->cfg.max_rank;
+    if (vslice * n > c->L.vpart_elems) return LORA_ERR_OOM;
 
     const DeviceView dv = c->view(T);
     float* vpart = c->dev<float>(c->L.off_vpart);
     float* part = c->dev<float>(c->L.off_part);
 
+    GroupArgs g;
+    std::memset(&g, 0, sizeof g);
+    g.n = n;
+    int blk = 0;
+    for (int k = 0; k < n; ++k) {
+        const int p = projs[k];
+        Slice& sl = g.s[k];
+        sl.x = static_cast<const uint16_t*>(d_x[k]);
+        sl.W = static_cast<const uint16_t*>(d_W[k]);
+        sl.out = static_cast<uint16_t*>(d_out[k]);
+        sl.vpart = vpart + vslice * k;
+        sl.a_off = c->L.a_off[p];
+        sl.b_off = c->L.b_off[p];
+        sl.N = c->proj[p].d_out;
+        sl.tile0 = 0;
+        sl.blk0 = blk;
+        blk += (int)(align_up((size_t)sl.N, 128) / 32);
+    }
+
     ShrinkArgs sa;
     std::memset(&sa, 0, sizeof sa);
     sa.dv = dv;
-    sa.x = static_cast<const uint16_t*>(d_x);
+    sa.g = g;
     sa.K = K;
-    sa.a_off = c->L.a_off[p];
     sa.n_kc = n_kc;
     sa.kc_len = kc_len;
-    sa.vpart = c->n_resident > 0 ? vpart : nullptr;   // no adapter resident: nothing to shrink
+    sa.on = c->n_resident > 0 ? 1 : 0;      // no adapter resident: nothing to shrink
 
     GemmArgs ga;
+    std::memset(&ga, 0, sizeof ga);
     ga.dv = dv;
-    ga.x = static_cast<const uint16_t*>(d_x);
-    ga.W = static_cast<const uint16_t*>(d_W);
-    ga.N = N;
+    ga.g = g;
     ga.K = K;
-    ga.tiles_m = ga.tiles_n = 0;
     ga.split_k = S;
-    ga.b_off = c->L.b_off[p];
-    ga.vpart = vpart;
     ga.n_kc = n_kc;
-    ga.out = static_cast<uint16_t*>(d_out);
+    ga.nblk = blk;
     ga.part = part;
     ga.Mpad = Mpad;
 
     if (!split) {
         // ---- shrink, then base GEMM with the expand in its epilogue ----
-        if (sa.vpart) {
+        if (sa.on) {
             const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
-            const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc;
+            const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc * n;
             const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
             LaunchScope ls(c, s, "shrink");
             if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
@@ -643,7 +680,10 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
         LaunchScope ls(c, s, "gemm_fused");
         const char* name = nullptr;
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
-        if (fv == 0) fv = pick_fused_variant(T, N);
+        if (fv == 0) {
+            fv = pick_fused_variant(T, n_max, tiles_of);
+            if (fv == 4 && T <= kSplitMaxTokens) fv = 5;    // small batch: copy-bound, every wave copies
+        }
         if (HIP_FAIL(launch_gemm_fused(ga, fv, s, &name))) return LORA_ERR_HIP;
         ls.rename(name);
     } else {
@@ -655,22 +695,27 @@ lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const vo
             ls.rename(name);
         }
         ReduceArgs ra;
+        std::memset(&ra, 0, sizeof ra);
         ra.dv = dv;
-        ra.N = N;
+        ra.g = g;
         ra.split_k = S;
         ra.Mpad = Mpad;
+        ra.nblk = blk;
         ra.part = part;
-        ra.vpart = vpart;
         ra.n_kc = n_kc;
-        ra.b_off = c->L.b_off[p];
-        ra.out = static_cast<uint16_t*>(d_out);
-        const int grid = ((T + kPieceRows - 1) / kPieceRows) * ((N + 127) / 128);
+        const int grid = ((T + kPieceRows - 1) / kPieceRows) * (blk / 4);
         LaunchScope ls(c, s, "reduce_expand");
         if (HIP_FAIL(launch_reduce_expand(ra, grid, s))) return LORA_ERR_HIP;
     }
     c->last_fwd_stream = s;
     c->have_fwd = true;
     return LORA_OK;
+}
+
+lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const void* d_W, const lora_segments* seg,
+                               void* d_out, void* stream_v)
+{
+    return lora_layer_forward_group(c, 1, &p, &d_x, &d_W, seg, &d_out, stream_v);
 }
 
 lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)

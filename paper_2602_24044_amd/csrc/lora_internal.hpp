@@ -71,41 +71,57 @@ struct MetaUpdates {
     float scale[kMetaBatch];
 };
 
+// One launch can serve several projections that share d_in ("packed projections": q|k|v, gate|up), each with
+// its own x, W, out and adapter matrices.  The slices sit side by side along N: tiles, 32-column blocks of the
+// split-K partial matrix and shrink work items are numbered across them.
+constexpr int kMaxGroup = 4;
+struct Slice {
+    const uint16_t* x;   // [T, K] bf16
+    const uint16_t* W;   // [N, K] bf16
+    uint16_t* out;       // [T, N] bf16
+    float* vpart;        // [n_kc][T][max_rank] fp32: this slice's shrink results
+    size_t a_off;        // element offsets of this projection's A and B inside a slot
+    size_t b_off;
+    int32_t N;
+    int32_t tile0;       // first N tile of the slice (set by the GEMM launcher for its tile width)
+    int32_t blk0;        // first 32-column block of the slice in the packed partial matrix (multiple of 4)
+    int32_t pad_;
+};
+struct GroupArgs {
+    int32_t n;
+    int32_t pad_;
+    Slice s[kMaxGroup];
+};
+
 struct ShrinkArgs {
     DeviceView dv;
-    const uint16_t* x;   // [T, K] bf16
+    GroupArgs g;         // x, a_off and vpart of every slice
     int32_t K;
-    size_t a_off;        // element offset of this projection's A inside a slot
     int32_t n_kc;        // K chunks (one partial result each)
     int32_t kc_len;      // K extent of a chunk (multiple of 64); the waves of a workgroup share a chunk
-    float* vpart;        // [n_kc][T][max_rank] fp32
+    int32_t on;          // 0: nothing to shrink (no adapter resident)
 };
 
 struct GemmArgs {
     DeviceView dv;
-    const uint16_t* x;   // [T, K]
-    const uint16_t* W;   // [N, K]
-    int32_t N, K;
-    int32_t tiles_m, tiles_n;
+    GroupArgs g;
+    int32_t K;
+    int32_t tiles_m, tiles_n;   // tiles_n counts the tiles of all slices
     int32_t split_k;     // 1 on the fused path
-    size_t b_off;        // element offset of this projection's B inside a slot
-    const float* vpart;  // shrink output
     int32_t n_kc;
-    uint16_t* out;       // fused path: [T, N] bf16
-    float* part;         // split path: [split_k][Mpad][N] fp32
+    int32_t nblk;        // 32-column blocks per row block of the packed partial matrix
+    float* part;         // split path: [split_k][Mpad / 32][nblk][1024] fp32
     int32_t Mpad;
 };
 
 struct ReduceArgs {
     DeviceView dv;
-    int32_t N;
+    GroupArgs g;
     int32_t split_k;
     int32_t Mpad;
+    int32_t nblk;
     const float* part;
-    const float* vpart;
     int32_t n_kc;
-    size_t b_off;
-    uint16_t* out;       // [T, N] bf16
 };
 
 // launchers (defined next to their kernels); every launch is asynchronous on `stream`

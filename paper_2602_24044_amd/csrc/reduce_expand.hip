@@ -21,12 +21,18 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     __shared__ __attribute__((aligned(16))) uint16_t sV[kPieceRows * kVStride];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const int T = a.dv.T, N = a.N;
+    const int T = a.dv.T;
     const int n_win = (T + kPieceRows - 1) / kPieceRows;
-    const int win = blockIdx.x % n_win, group = blockIdx.x / n_win;
+    const int win = blockIdx.x % n_win, group = blockIdx.x / n_win;   // group: 128 packed columns
+    // the slice (projection of a packed group) these columns belong to: slices start on multiples of 128
+    int si = 0;
+    for (int k = 1; k < a.g.n; ++k)
+        if (group * 4 >= a.g.s[k].blk0) si = k;
+    const Slice sl = pick_slice(a.g, si);
+    const int N = sl.N;
     const int m = win * kPieceRows + i;
     const bool m_ok = m < T;
-    const int n_first = group * 128 + wave * 32;
+    const int n_first = (group * 4 - sl.blk0) * 32 + wave * 32;       // column inside the slice
 
     // partial sums first: the loads are independent of the LDS staging below
     f32x16 acc[1];
@@ -35,9 +41,9 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     // partial tiles are stored block by block in accumulator order (see the split-K GEMM): block
     // (window, n / 32) of split s is 1 KB-contiguous per register group, so these loads are fully
     // coalesced; four splits (16 independent 16-byte loads per lane) are kept in flight
-    const int nblk = (N + 31) / 32;
-    const int bn = n_first / 32;
-    if (bn < nblk) {
+    const int nblk = a.nblk;
+    const int bn = group * 4 + wave;                                  // block in the packed partial matrix
+    if (n_first < N) {
         for (int s0 = 0; s0 < a.split_k; s0 += 4) {
             f32x4 p[4][4];
 #pragma unroll
@@ -72,7 +78,7 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
             f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
             for (int c = 0; c < a.n_kc; ++c) {
-                const float* vp = a.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
+                const float* vp = sl.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
                 lo += *reinterpret_cast<const f32x4*>(vp);
                 hi += *reinterpret_cast<const f32x4*>(vp + 4);
             }
@@ -98,10 +104,10 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStride + k);
         return as_bf16x8(v);
     };
-    expand_window_pipelined(acc[0], my_slot, my_rank, my_scale, n_first, N, a.dv, a.b_off, vfrag);
+    expand_window_pipelined<1>(acc, my_slot, my_rank, my_scale, n_first, N, a.dv, sl.b_off, vfrag);
 
     if (m_ok) {
-        uint16_t* orow = a.out + (size_t)a.dv.perm[m] * N;
+        uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int n = n_first + g * 8 + h * 4;

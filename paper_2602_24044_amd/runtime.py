@@ -106,11 +106,44 @@ class Session:
         B.lora_layer_forward(self.ctx, p, x.data_ptr(), W.data_ptr(), self.seg, out.data_ptr(), s)
         return out
 
-    def step(self) -> None:
-        """One pass of the whole path: segment map + every projection."""
+    def forward_group(self, ps: Sequence[int], stream: Optional[torch.cuda.Stream] = None) -> List[torch.Tensor]:
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        B.lora_layer_forward_group(self.ctx, list(ps), [self.x[p].data_ptr() for p in ps],
+                                   [self.W[p].data_ptr() for p in ps], self.seg,
+                                   [self.out[p].data_ptr() for p in ps], s)
+        return [self.out[p] for p in ps]
+
+    def packed_groups(self) -> List[List[int]]:
+        """Projections a decoder layer computes from one input side by side: q|k|v and gate|up."""
+        names = list(self.w.proj_names)
+        groups, used = [], set()
+        for fam in (("q", "k", "v"), ("gate", "up")):
+            g = [names.index(nm) for nm in fam if nm in names]
+            if len(g) > 1 and len({self.w.proj[p][0] for p in g}) == 1:
+                groups.append(g)
+                used.update(g)
+        out = []
+        for p in range(len(names)):
+            if p in used:
+                g = next(g for g in groups if p in g)
+                if g[0] == p:
+                    out.append(g)
+            else:
+                out.append([p])
+        return out
+
+    def step(self, packed: bool = True) -> None:
+        """One pass of the whole path: segment map + every projection (q|k|v and gate|up as packed calls)."""
         self.bucket()
-        for p in range(len(self.w.proj)):
-            self.forward(p)
+        if packed:
+            for g in self.packed_groups():
+                if len(g) == 1:
+                    self.forward(g[0])
+                else:
+                    self.forward_group(g)
+        else:
+            for p in range(len(self.w.proj)):
+                self.forward(p)
 
     # ---- read-back helpers ----
     def _i32_at(self, ptr: int, n: int) -> np.ndarray:

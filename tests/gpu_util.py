@@ -32,9 +32,10 @@ def rel_err(out_bits, y_ref):
     return float(np.max(np.abs(got - y_ref)) / (denom if denom > 0 else 1.0))
 
 
-def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=True, tol=TOL):
-    """Loads the resident adapters, runs one step, compares every projection with the oracle."""
-    announce(f"{w.name} T={w.T} path={path} split_k={split_k} proj={w.proj}")
+def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=True, tol=TOL, packed=False):
+    """Loads the resident adapters, runs one step, compares every projection with the oracle.  packed: q|k|v
+    and gate|up go through lora_layer_forward_group (each projection still has its own x)."""
+    announce(f"{w.name} T={w.T} path={path} split_k={split_k} packed={packed} proj={w.proj}")
     sess = Session(w, path=path, split_k=split_k)
     try:
         resident = w.resident if preload is None else preload
@@ -46,12 +47,23 @@ def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=
             flags = check_segments(sess, w)
             assert flags == 0
         errs = []
+        group_launches = {}
+        if packed:
+            for g in sess.packed_groups():
+                if len(g) > 1:
+                    sess.forward_group(g)
+                else:
+                    sess.forward(g[0])
+                for p in g:
+                    group_launches[p] = B.lora_last_launches(sess.ctx)
+            torch.cuda.synchronize()
         for p in range(len(w.proj)):
-            out = sess.forward(p)
+            out = sess.out[p] if packed else sess.forward(p)
             torch.cuda.synchronize()
             y_ref = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p))
             e = rel_err(bf16_tensor_to_bits(out), y_ref)
-            announce(f"  proj {p} {w.proj[p]} launches={B.lora_last_launches(sess.ctx)} rel_err={e:.3e}")
+            launches = group_launches[p] if packed else B.lora_last_launches(sess.ctx)
+            announce(f"  proj {p} {w.proj[p]} launches={launches} rel_err={e:.3e}")
             errs.append(e)
         st, word = B.lora_poll_device_flags(sess.ctx)
         assert st == B.LORA_OK and word == 0

@@ -144,3 +144,22 @@ def test_host_only_context_refuses_device_work():
         assert e.value.status == B.LORA_ERR_HIP
     finally:
         B.lora_destroy(ctx)
+
+
+def test_group_argument_errors():
+    ctx = _host_ctx(proj=((64, 64), (64, 128), (128, 64)))
+    seg = B.lora_segments()
+    try:
+        def status(projs):
+            n = len(projs)
+            with pytest.raises(B.LoraError) as e:
+                B.lora_layer_forward_group(ctx, projs, [16] * n, [16] * n, seg, [16] * n)
+            return e.value.status
+        assert status([]) == B.LORA_ERR_INVALID_ARG                   # at least one projection
+        assert status([0, 1, 0, 1, 0]) == B.LORA_ERR_INVALID_ARG      # at most four
+        assert status([0, 0]) == B.LORA_ERR_INVALID_ARG               # distinct
+        assert status([0, 3]) == B.LORA_ERR_INVALID_ARG               # in range
+        assert status([0, 2]) == B.LORA_ERR_SHAPE                     # d_in 64 vs 128
+        assert status([0, 1]) == B.LORA_ERR_INVALID_ARG               # no segment map yet
+    finally:
+        B.lora_destroy(ctx)

@@ -241,3 +241,69 @@ def test_stale_segment_map_is_rejected():
             B.lora_layer_forward(sess.ctx, 3, sess.x[0].data_ptr(), sess.W[0].data_ptr(), sess.seg, sess.out[0].data_ptr())
     finally:
         sess.close()
+
+
+# ---- packed projections (q|k|v and gate|up through lora_layer_forward_group) ----
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("n_tokens", [256, 300])
+def test_packed_config2_decode_reduced(path, n_tokens):
+    run_and_check(wl.config2(shrink=8, n_tokens=n_tokens), path=path, packed=True)
+
+
+@pytest.mark.parametrize("path", [B.LORA_PATH_AUTO, B.LORA_PATH_FUSED])
+def test_packed_config3_prefill_reduced(path):
+    run_and_check(wl.config3(shrink=8), path=path, packed=True)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_packed_config4_many_adapters_reduced(path):
+    run_and_check(wl.config4(shrink=8), path=path, packed=True)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_packed_config5_mixed_with_loads_reduced(path):
+    run_and_check(wl.config5(shrink=8), path=path, packed=True)
+
+
+def test_packed_equals_separate_calls_bit_for_bit_on_the_fused_path():
+    # the fused path has no split-K: a projection's result may not depend on what it is packed with
+    w = wl.config2(shrink=8, n_tokens=300)
+    a = Session(w, path=B.LORA_PATH_FUSED)
+    b = Session(w, path=B.LORA_PATH_FUSED)
+    try:
+        for s in (a, b):
+            s.load(w.resident)
+            s.bucket()
+        for g in a.packed_groups():
+            if len(g) > 1:
+                a.forward_group(g)
+            else:
+                a.forward(g[0])
+        for p in range(len(w.proj)):
+            b.forward(p)
+        torch.cuda.synchronize()
+        for p in range(len(w.proj)):
+            assert torch.equal(a.out[p].view(torch.int16), b.out[p].view(torch.int16)), w.proj_names[p]
+    finally:
+        a.close()
+        b.close()
+
+
+def test_group_with_one_shared_input_tensor():
+    # q, k, v reading the very same x tensor
+    w = wl.config2(shrink=8, n_tokens=256)
+    s = Session(w)
+    try:
+        s.load(w.resident)
+        s.bucket()
+        g = [w.proj_names.index(nm) for nm in ("q", "k", "v")]
+        x = s.x[g[0]]
+        B.lora_layer_forward_group(s.ctx, g, [x.data_ptr()] * 3, [s.W[p].data_ptr() for p in g], s.seg,
+                                   [s.out[p].data_ptr() for p in g], torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for p in g:
+            y_ref = oracle.project(w.x[g[0]], w.W[p], w.token_ids, oracle.adapters_of(w, p))
+            assert rel_err(bf16_tensor_to_bits(s.out[p]), y_ref) <= TOL
+    finally:
+        s.close()
