@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of one multi-adapter LoRA layer-step on one MI355X.
 
-A step = lora_bucket + lora_layer_forward for each of the seven projections of one decoder layer
-(q, k, v, o, gate, up, down), on synthetic inputs already resident in HBM.  The default workload is
+A step = lora_bucket + the seven projections of one decoder layer (q, k, v, o, gate, up, down; q|k|v and
+gate|up as packed lora_layer_forward_group calls, o and down as lora_layer_forward calls), each projection
+with its own synthetic input, already resident in HBM.  The default workload is
 the 8B-shape decode step: 256 one-token requests, 32 resident adapters of ranks {8,16,32}, adapter
 ids Zipf(1.0).  Prints ONE JSON line.
 """
@@ -223,10 +224,13 @@ def main():
     launched_by = []
     s0 = sessions[0]
     s0.bucket()
-    for p in range(len(w.proj)):
-        s0.forward(p)
+    for g in s0.packed_groups():
+        if len(g) > 1:
+            s0.forward_group(g)
+        else:
+            s0.forward(g[0])
         if dominant in B.lora_last_launches(s0.ctx):
-            launched_by.append(p)
+            launched_by += g
     torch.cuda.synchronize()
     dom_t = kernels[dominant]["us_per_step"] * 1e-6
     dom_bytes = kernel_algorithmic_bytes(w, dominant, launched_by)
@@ -235,7 +239,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": stored_traffic(dominant, w.name),
                 "projections": [w.proj_names[p] for p in launched_by] if hasattr(w, "proj_names") else launched_by,
-                "algorithmic_bytes_per_launch": dom_bytes / max(1, len(launched_by)),
+                "algorithmic_bytes_per_launch": dom_bytes / max(1.0, kernels[dominant]["launches_per_step"]),
                 "launch_avg_us": kernels[dominant]["avg_us"],
                 "mfma_tflops": dom_flops / dom_t / 1e12, "mfma_frac": dom_flops / dom_t / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     if args.config in (3, 5):
