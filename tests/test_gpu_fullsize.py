@@ -1,6 +1,6 @@
-"""GPU parity at the full workload sizes, in the launch configuration bench.py times (automatic path):
-segment maps bit-exact against the oracle, outputs checked on sampled (token, column) pairs that the
-oracle evaluates one by one."""
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times (automatic path,
+q|k|v and gate|up as packed calls) and with one call per projection: segment maps bit-exact against the
+oracle, outputs checked on sampled (token, column) pairs that the oracle evaluates one by one."""
 import numpy as np
 import pytest
 import torch
@@ -16,8 +16,8 @@ pytestmark = pytest.mark.gpu
 N_SAMPLES = 1500
 
 
-def _run_full(w, n_samples=N_SAMPLES):
-    announce(f"full-size {w.name} T={w.T} proj={w.proj}")
+def _run_full(w, n_samples=N_SAMPLES, packed=True):
+    announce(f"full-size {w.name} T={w.T} packed={packed} proj={w.proj}")
     sess = Session(w)
     try:
         sess.load(w.resident)
@@ -26,8 +26,20 @@ def _run_full(w, n_samples=N_SAMPLES):
         sess.bucket()
         assert check_segments(sess, w) == 0
         rng = np.random.default_rng(12345)
+        launches = {}
+        if packed:
+            for g in sess.packed_groups():
+                if len(g) > 1:
+                    sess.forward_group(g)
+                else:
+                    sess.forward(g[0])
+                for p in g:
+                    launches[p] = B.lora_last_launches(sess.ctx)
         for p, (d_in, d_out) in enumerate(w.proj):
-            out = sess.forward(p)
+            out = sess.out[p]
+            if not packed:
+                out = sess.forward(p)
+                launches[p] = B.lora_last_launches(sess.ctx)
             torch.cuda.synchronize()
             got_all = bf16_tensor_to_bits(out)
             ts = rng.integers(0, w.T, size=n_samples).astype(np.int32)
@@ -39,7 +51,7 @@ def _run_full(w, n_samples=N_SAMPLES):
             got = wl.bf16_bits_to_f64(got_all[ts, ns])
             # scale of the projection: the largest sampled reference magnitude (a lower bound of max|y_ref|)
             err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
-            announce(f"  proj {p} {w.proj[p]} launches={B.lora_last_launches(sess.ctx)} sampled rel_err={err:.3e}")
+            announce(f"  proj {p} {w.proj[p]} launches={launches[p]} sampled rel_err={err:.3e}")
             assert err <= TOL, (p, err)
             assert np.isfinite(wl.bf16_bits_to_f32(got_all)).all()
         st, word = B.lora_poll_device_flags(sess.ctx)
@@ -50,6 +62,10 @@ def _run_full(w, n_samples=N_SAMPLES):
 
 def test_config2_full():
     _run_full(wl.config2())
+
+
+def test_config2_full_one_call_per_projection():
+    _run_full(wl.config2(), packed=False)
 
 
 def test_config4_full():
