@@ -24,7 +24,7 @@
 // SPLITK: blockIdx selects a K range; fp32 partial tiles go to the reduce + expand kernel.  After its
 //        tile, every workgroup takes a share of the LoRA shrink work items of the same projection, so
 //        shrink and base GEMM share one launch.
-#include "device_common.hpp"
+#include "gemm_epilogue.hpp"
 
 #include <type_traits>
 #include <utility>
@@ -358,82 +358,15 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
     }
 
     // ---------------- epilogue ----------------
-    // Fused path: the ring is idle once every wave has left the main loop; each wave then parks the scaled
-    // shrink results of one 32-row window at a time in its own piece of it and runs the expand from there.
+    // every copy has landed and been read once all waves have left the main loop: the ring is free
     static_assert(!FUSED || NS * STAGE * 2 >= NWV * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
-    if (!producer) {
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int m = m0 + wm * WTM + mb * 32 + i;      // grouped row of this lane
-        const bool m_ok = m < T;
-        const int n_first = n0 + wn * WTN;
-
-        if (FUSED) {
-            const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
-            const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
-            const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
-            if (__ballot(my_slot >= 0 && my_rank > 0)) {      // uniform over the wave
-                uint16_t* sV = ring + wave * (kPieceRows * kVStageStride);
-                stage_window_v(sV, sl.vpart, a.n_kc, m0 + wm * WTM + mb * 32, a.dv);
-                auto vfrag = [&](int k, bool on, float) -> bf16x8 {
-                    u32x4 v = {0u, 0u, 0u, 0u};
-                    if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStageStride + k);
-                    return as_bf16x8(v);
-                };
-                expand_window_pipelined<NB>(acc[mb], my_slot, my_rank, my_scale, n_first, N, a.dv, sl.b_off, vfrag);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next window is staged
-            }
-        }
-
-        if (m_ok) {
-            if (FUSED) {
-                uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = n_first + nb * 32 + g * 8 + h * 4;
-                        if (n < N) {
-                            bf16x4 o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[mb][nb][g * 4 + e];
-                            *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
-                        }
-                    }
-            } else {
-                // fp32 partial tiles are kept block by block in accumulator order: block (m / 32, n / 32)
-                // of split s is 1024 consecutive floats, lane (i, h) owning floats 256 g + 8 i + 4 h .. + 3,
-                // so every store (and the matching load in the reduce kernel) covers 1 KB contiguously
-                const int nblk_slice = (N + 31) / 32;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int bn = (n_first + nb * 32) / 32;          // block inside the slice
-                    if (bn < nblk_slice) {
-                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)(m / 32)) * a.nblk + sl.blk0 + bn) * 1024;
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
-                                       acc[mb][nb][g * 4 + 3]};
-                            // read once by another kernel: keep the tiles from lingering dirty in L2
-                            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4));
-                        }
-                    }
-                }
-            }
-        }
-    }
-
-    }   // !producer
-
-    // split path: this workgroup's share of the shrink work items of the same projection.  The ring is
-    // idle by now (every copy has landed and been read), so its first bytes serve the cross-wave sums.
-    if (!FUSED) {
-        static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
-        if (sa.on) {
-            __syncthreads();
-            shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
-        }
+    if (!producer)
+        finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, ring);
+    if (!FUSED && sa.on) {
+        __syncthreads();
+        shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
     }
 }
 

@@ -1,0 +1,242 @@
+// Base projection x W^T for small batches (decode), where the weight stream from HBM and the re-read of x
+// from L2 bound the kernel (paper Sec. 2.2: the adapter's activations are added to the backbone layer's
+// output; Sec. 5.1.2: backbone latency grows linearly with the batch).
+//
+// Same tiling idea as the 32-wide-K kernel - BM x BN tile per workgroup, tiles copied global -> LDS with
+// global_load_lds, MFMA 32x32x16 with W as first operand - but K is walked in 64-wide tiles, so that every
+// row segment a copy instruction fetches is one whole 128-byte cache line (eight lanes per line, eight rows
+// per instruction).  Measured on a stream of W tiles from HBM mixed with x tiles from L2, whole-line
+// segments move 25 - 30 % more bytes per second through a CU's vector cache than 64-byte half lines: with
+// half lines every line is requested twice.
+//
+// LDS rows are 128 bytes; chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & 7).  The copy engine
+// places lane l at byte 16 l of the instruction's 1 KB, so the swizzle is applied on the global side (lane l
+// fetches the chunk that belongs at its position; the eight lanes of a row still cover its whole line).  The
+// LDS serves a 128-bit read 16 lanes per cycle, the 16 lanes being those of a 32-lane half whose lane-index
+// bits 2, 3, 4 have equal parity; among them rows of equal parity differ in (r >> 1) & 7, so the MFMA-layout
+// reads (32 rows x one chunk) are bank-conflict free.
+//
+// Ring of NS stages, one barrier per tile: at the top of iteration j every wave waits for its own copies of
+// tile j (younger ones stay in flight), meets the others, refills the stage tile j - 1 has just left with tile
+// j + NS - 1, then multiplies tile j.  NS - 1 tiles are in flight behind the one being multiplied.
+#include "gemm_epilogue.hpp"
+
+namespace lora {
+namespace {
+
+constexpr int kTK64 = 64;    // K extent of one LDS tile (bf16 elements): 128-byte rows
+constexpr int kRowB = 128;
+
+__device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
+{
+    // issued from inline assembly: the only ordering against later LDS reads is the explicit vmcnt wait +
+    // barrier of the main loop
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+template <int N>
+__device__ inline void wait_copies_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
+__global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs a, ShrinkArgs sa)
+{
+    constexpr int NWV = WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
+    constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
+    constexpr int STAGE_B = (BM + BN) * kRowB;              // bytes per stage
+    constexpr int XQ = BM / 8 / NWV, WQ = BN / 8 / NWV;     // copy instructions (8 rows) per wave and tile
+    constexpr int QPT = XQ + WQ;
+    static_assert(BM % (8 * NWV) == 0 && BN % (8 * NWV) == 0, "tile/waves");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
+    static_assert(NS >= 2 && NS <= 5 && (NS - 1) * QPT <= 63, "stages / vmcnt range");
+    static_assert(NS * STAGE_B <= 160 * 1024, "LDS");
+
+    __shared__ __attribute__((aligned(1024))) uint8_t ring[NS * STAGE_B];
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, h = lane >> 5;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int T = a.dv.T, K = a.K;
+
+    // blockIdx -> (split, tile_m, tile_n): consecutive blockIdx values land on different XCDs, so the K split
+    // is the fastest index on the split path (every XCD keeps one x K-range in its L2)
+    int split = 0, tile_m, tile_n;
+    {
+        int b = blockIdx.x;
+        if (!FUSED) {
+            split = b % a.split_k;
+            b /= a.split_k;
+        }
+        tile_m = b % a.tiles_m;
+        tile_n = b / a.tiles_m;
+    }
+    int si = 0;
+    for (int k = 1; k < a.g.n; ++k)
+        if (tile_n >= a.g.s[k].tile0) si = k;
+    const Slice sl = pick_slice(a.g, si);
+    const uint16_t* const xg = sl.x;
+    const uint16_t* const Wg = sl.W;
+    const int N = sl.N;
+    const int m0 = tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
+
+    ShrinkPrefetch spf{};
+    if (!FUSED && sa.on) spf = shrink_prefetch(sa, blockIdx.x);
+
+    const int kt_total = K / kTK64;
+    int kt_begin = 0, kt_end = kt_total;
+    if (!FUSED) {
+        kt_begin = (int)((long long)kt_total * split / a.split_k);
+        kt_end = (int)((long long)kt_total * (split + 1) / a.split_k);
+    }
+    const int nk = kt_end - kt_begin;
+
+    // Copy assignment: instruction q of wave w fills stage rows 8 (w XQ + q) .. + 7 of the x part (same for
+    // the W part with WQ); lane l owns row l / 8 of those and chunk position l % 8.  Rows past T or N are
+    // clamped to the last valid row: they are computed, never stored.
+    uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes in tile 0
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) {
+        const int r = (wave * XQ + q) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        int m = m0 + r;
+        if (m > T - 1) m = T - 1;
+        xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(c * 8 + kt_begin * kTK64);
+    }
+#pragma unroll
+    for (int q = 0; q < WQ; ++q) {
+        const int r = (wave * WQ + q) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        int n = n0 + r;
+        if (n > N - 1) n = N - 1;
+        woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(c * 8 + kt_begin * kTK64);
+    }
+    const uint32_t cp_x = ring_addr + wave * XQ * 1024;
+    const uint32_t cp_w = ring_addr + BM * kRowB + wave * WQ * 1024;
+    auto copy_tile = [&](int t, int stage) {                // tile t of this workgroup's K range
+        const uint32_t k0 = (uint32_t)t * kTK64, so = (uint32_t)stage * STAGE_B;
+#pragma unroll
+        for (int q = 0; q < XQ; ++q)
+            copy16_to_lds(xg + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
+#pragma unroll
+        for (int q = 0; q < WQ; ++q)
+            copy16_to_lds(Wg + (woff[q] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + q * 1024));
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    // byte offset of this lane's fragment of K step kk inside a 32-row block: row i, chunk 2 kk + h
+    const int sw = (i >> 1) & 7;
+    int rd[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) rd[kk] = i * kRowB + (((2 * kk + h) ^ sw) << 4);
+    const int x_base = wm * WTM * kRowB, w_base = (BM + wn * WTN) * kRowB;
+
+    // prologue: tiles 0 .. NS - 2
+#pragma unroll
+    for (int d = 0; d < NS - 1; ++d)
+        if (d < nk) copy_tile(d, d);
+
+    int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
+    for (int j = 0; j < nk; ++j) {
+        // own copies of tile j landed; the (at most NS - 2) younger tiles stay in flight
+        int young = nk - 1 - j;
+        if (young > NS - 2) young = NS - 2;
+        if (young >= 3) wait_copies_then_barrier<(NS >= 5 ? 3 : 0) * QPT>();
+        else if (young == 2) wait_copies_then_barrier<(NS >= 4 ? 2 : 0) * QPT>();
+        else if (young == 1) wait_copies_then_barrier<QPT>();
+        else wait_copies_then_barrier<0>();
+        // tile j is complete for every wave and every wave has finished tile j - 1: refill its stage
+        if (j + NS - 1 < nk) copy_tile(j + NS - 1, fre);
+
+        const uint8_t* st = ring + cur * STAGE_B;
+        bf16x8 Fw[2][NB], Fx[2][MB];
+        auto read_step = [&](int f, int kk) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                Fw[f][nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + w_base + nb * 32 * kRowB + rd[kk]));
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                Fx[f][mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + x_base + mb * 32 * kRowB + rd[kk]));
+        };
+        read_step(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) read_step((kk + 1) & 1, kk + 1);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(Fw[kk & 1][nb], Fx[kk & 1][mb], acc[mb][nb]);
+        }
+        fre = cur;
+        cur = (cur + 1 == NS) ? 0 : cur + 1;
+    }
+
+    // ---------------- epilogue ----------------
+    static_assert(!FUSED || NS * STAGE_B >= NWV * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
+    if (FUSED) __syncthreads();
+    finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, reinterpret_cast<uint16_t*>(ring));
+    if (!FUSED && sa.on) {
+        __syncthreads();
+        shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
+hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
+{
+    a.tiles_m = (a.dv.T + BM - 1) / BM;
+    a.tiles_n = 0;
+    for (int k = 0; k < a.g.n; ++k) {
+        a.g.s[k].tile0 = a.tiles_n;
+        a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+    }
+    const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
+    hipLaunchKernelGGL((gemm_rows128_kernel<BM, BN, WGM, WGN, FUSED, NS>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream,
+                       a, sa);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_rows128_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name)
+{
+    ShrinkArgs none{};
+    none.on = 0;
+    switch (variant) {
+        case 1:
+            *name = "gemm_fused_128x128x64_w4";
+            return launch_rows128<128, 128, 2, 2, true, 4>(a, none, stream);
+        case 2:
+            *name = "gemm_fused_256x256x64_w8";
+            return launch_rows128<256, 256, 2, 4, true, 2>(a, none, stream);
+        default:
+            *name = "gemm_fused_256x128x64_w8";
+            return launch_rows128<256, 128, 4, 2, true, 3>(a, none, stream);
+    }
+}
+
+hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream,
+                                      const char** name)
+{
+    switch (variant) {
+        case 1:
+            *name = "gemm_splitk_shrink_128x128x64_w4";
+            return launch_rows128<128, 128, 2, 2, false, 4>(a, sa, stream);
+        default:
+            *name = "gemm_splitk_shrink_256x128x64_w8";
+            return launch_rows128<256, 128, 4, 2, false, 3>(a, sa, stream);
+    }
+}
+
+}  // namespace lora

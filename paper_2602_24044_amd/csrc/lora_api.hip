@@ -39,6 +39,9 @@ struct Layout {
     size_t total = 0;
 };
 
+// split-K GEMM variants 3, 4 and 7 use 128-row tiles, the others 256-row tiles; 6 and 7 walk K in 64-wide tiles
+int split_bm(int variant) { return (variant == 3 || variant == 4 || variant == 7) ? 128 : 256; }
+
 int auto_split_cap(int N)
 {
     const int tiles_n = (N + 127) / 128;
@@ -592,8 +595,12 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
     }
     if (split) {
         // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
-        if (split_variant == 0 && n_pad_total <= 2048) split_variant = 3;
-        const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
+        // small batches walk K in 64-wide tiles (whole cache lines per row segment).  Narrow launches (k, v
+        // alone) fill the chip better with square 128 x 128 tiles, and so does a 4096-wide projection over a
+        // short K at up to 256 tokens (half the K splits, half the partial tiles)
+        if (split_variant == 0)
+            split_variant = (n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
+        const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
         const long tiles = tiles_of(bm, bn);
         // enough K splits to give every CU a workgroup, but no more than 8: each split costs a pass of
         // fp32 partial tiles through memory
@@ -614,7 +621,7 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
             // each item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup
             // one item (when there are more pieces than workgroups, fine chunks balance better and stay).
             // The piece count is only known on the device; this is its upper bound.
-            const int bm = (split_variant == 3 || split_variant == 4) ? 128 : 256, bn = split_variant == 2 ? 64 : 128;
+            const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
             const long wgs = tiles_of(bm, bn) * S;
             const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
             if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
@@ -682,16 +689,22 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
         if (fv == 0) {
             fv = pick_fused_variant(T, n_max, tiles_of);
-            if (fv == 4 && T <= kSplitMaxTokens) fv = 5;    // small batch: copy-bound, every wave copies
+            // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
+            if (T <= kSplitMaxTokens) fv = fv == 4 ? 8 : (fv == 3 ? 9 : 10);
         }
-        if (HIP_FAIL(launch_gemm_fused(ga, fv, s, &name))) return LORA_ERR_HIP;
+        const hipError_t le = fv >= 8 ? launch_gemm_rows128_fused(ga, fv - 8, s, &name) : launch_gemm_fused(ga, fv, s, &name);
+        if (HIP_FAIL(le)) return LORA_ERR_HIP;
         ls.rename(name);
     } else {
         // ---- split-K base GEMM + shrink in one launch, then reduce + expand ----
         {
             LaunchScope ls(c, s, "gemm_splitk");
             const char* name = nullptr;
-            if (HIP_FAIL(launch_gemm_splitk(ga, sa, split_variant, s, &name))) return LORA_ERR_HIP;
+            // 6, 7: 64-wide K tiles; 8: the 32-wide 256 x 128 kernel (its own variant 0); 1 .. 5: 32-wide variants
+            const hipError_t le = (split_variant == 6 || split_variant == 7)
+                                      ? launch_gemm_rows128_splitk(ga, sa, split_variant - 6, s, &name)
+                                      : launch_gemm_splitk(ga, sa, split_variant == 8 ? 0 : split_variant, s, &name);
+            if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
         }
         ReduceArgs ra;

@@ -132,6 +132,9 @@ hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stre
 hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);
 hipError_t launch_gemm_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
 hipError_t launch_gemm_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
+// K walked in 64-wide tiles (whole 128-byte lines per row segment): the small-batch kernels
+hipError_t launch_gemm_rows128_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
+hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 hipError_t launch_reduce_expand(const ReduceArgs& a, int grid, hipStream_t stream);
 
 }  // namespace lora

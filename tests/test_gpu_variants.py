@@ -1,0 +1,37 @@
+"""GPU parity of every selectable GEMM kernel variant (lora_set_tuning) against the CPU oracle: the
+automatic choice reaches only some of them at a given shape, the others stay reachable for tuning and must
+compute the same result.  Small workloads with a ragged last tile, packed and single calls."""
+import pytest
+
+from gpu_util import run_and_check
+from paper_2602_24044_amd import binding as B
+from paper_2602_24044_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+# fused GEMM: 0 automatic, 1 - 5 the 32-wide-K tiles, 8 - 10 the 64-wide-K (whole cache line) tiles
+FUSED_VARIANTS = [1, 2, 3, 4, 5, 8, 9, 10]
+# split-K GEMM: 0 automatic, 1 - 5 and 8 the 32-wide-K tiles, 6 and 7 the 64-wide-K tiles
+SPLIT_VARIANTS = [1, 2, 3, 4, 5, 6, 7, 8]
+
+
+@pytest.mark.parametrize("variant", FUSED_VARIANTS)
+def test_fused_variant_decode_and_prefill(variant):
+    tuning = {B.LORA_TUNE_FUSED_VARIANT: variant}
+    run_and_check(wl.config2(shrink=8, n_tokens=300), path=B.LORA_PATH_FUSED, tuning=tuning)
+    run_and_check(wl.config3(shrink=8, n_req=6, len_div=8), path=B.LORA_PATH_FUSED, tuning=tuning, packed=True)
+
+
+@pytest.mark.parametrize("variant", SPLIT_VARIANTS)
+def test_split_variant_decode(variant):
+    tuning = {B.LORA_TUNE_SPLIT_VARIANT: variant}
+    run_and_check(wl.config2(shrink=8, n_tokens=300), path=B.LORA_PATH_SPLITK, tuning=tuning)
+    run_and_check(wl.config4(shrink=8), path=B.LORA_PATH_SPLITK, split_k=3, tuning=tuning, packed=True)
+
+
+@pytest.mark.parametrize("variant", [6, 7])
+def test_whole_line_split_variants_short_k_ranges(variant):
+    # 16 splits of a 512-wide K leave every workgroup fewer K tiles than the ring has stages
+    tuning = {B.LORA_TUNE_SPLIT_VARIANT: variant}
+    run_and_check(wl.config1(), path=B.LORA_PATH_SPLITK, split_k=16, tuning=tuning)
+    run_and_check(wl.config1(), path=B.LORA_PATH_SPLITK, split_k=2, tuning=tuning)
