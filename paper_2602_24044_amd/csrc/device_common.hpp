@@ -58,23 +58,26 @@ __device__ inline void shrink_mma(const ShrinkStep& s, f32x16& acc0, f32x16& acc
     }
 }
 
+// K steps of one wavefront's share of an item, D of them in flight (each step is 8 or 12 independent 16-byte
+// loads per lane; an item is a chain of dependent memory latencies, so the depth sets its duration).
 template <bool R64>
 __device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1, bool x_ok,
                                     bool a0_ok, bool a1_ok, int k_begin, int k_end, f32x16& acc0, f32x16& acc1)
 {
-    ShrinkStep s0, s1;
-    shrink_fetch<R64>(s0, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin);
-    int k0 = k_begin;
-    while (true) {
-        const bool more1 = k0 + kBK < k_end;
-        if (more1) shrink_fetch<R64>(s1, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + kBK);
-        shrink_mma<R64>(s0, acc0, acc1);
-        if (!more1) break;
-        const bool more2 = k0 + 2 * kBK < k_end;
-        if (more2) shrink_fetch<R64>(s0, xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + 2 * kBK);
-        shrink_mma<R64>(s1, acc0, acc1);
-        if (!more2) break;
-        k0 += 2 * kBK;
+    constexpr int D = R64 ? 2 : 4;
+    ShrinkStep st[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (k_begin + d * kBK < k_end) shrink_fetch<R64>(st[d], xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin + d * kBK);
+    for (int k0 = k_begin; k0 < k_end; k0 += D * kBK) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (k0 + d * kBK < k_end) {                      // uniform over the wave
+                shrink_mma<R64>(st[d], acc0, acc1);
+                if (k0 + (D + d) * kBK < k_end)
+                    shrink_fetch<R64>(st[d], xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + (D + d) * kBK);
+            }
+        }
     }
 }
 
@@ -95,8 +98,8 @@ __device__ inline Slice pick_slice(const GroupArgs& g, int si)
 // What the first work item of a workgroup needs before it can issue its operand loads; fetched at kernel
 // start so that the chain item -> piece record -> perm -> x is off the critical path later.
 struct ShrinkPrefetch {
-    int n_items;
-    int4 rec;      // piece record of the first item (undefined when first_item >= n_items)
+    int n_items, n_pieces;
+    int4 rec;      // piece record of the first item ({0, 0, -1, 0} when there is none)
     int tok;       // perm[rec.x + lane % 32]
 };
 
@@ -105,96 +108,115 @@ __device__ inline ShrinkPrefetch shrink_prefetch(const ShrinkArgs& a, int first_
 {
     ShrinkPrefetch pf;
     const int i = threadIdx.x & 31;
-    const int n_pieces = *a.dv.n_pieces;
-    pf.n_items = a.g.n * n_pieces * a.n_kc;
+    pf.n_pieces = *a.dv.n_pieces;
+    pf.n_items = a.g.n * pf.n_pieces * a.n_kc;
     pf.rec = int4{0, 0, -1, 0};
     pf.tok = 0;
     if (first_item < pf.n_items) {
-        pf.rec = reinterpret_cast<const int4*>(a.dv.piece_info)[(first_item / a.n_kc) % n_pieces];
+        pf.rec = reinterpret_cast<const int4*>(a.dv.piece_info)[(first_item / a.n_kc) % pf.n_pieces];
         if (i < pf.rec.y) pf.tok = a.dv.perm[pf.rec.x + i];
     }
     return pf;
 }
 
-// Processes work items first_item, first_item + stride, ... with the whole workgroup of NW wavefronts:
-// the waves split the item's K chunk between them, then the NW partial 32 x r blocks are summed
-// through LDS (sRed: NW * kRedFloatsPerWave floats) and written as one partial result per chunk.
-// Every branch on item data is uniform over the workgroup.
+// One shrink work item, processed by the whole workgroup of NW wavefronts: the waves split the item's K chunk
+// between them, then the NW partial 32 x r blocks are summed through LDS (sRed: NW * kRedFloatsPerWave floats)
+// and written as one partial result for the chunk.  rec / tok: the piece's record and this lane's token
+// (perm[rec.x + lane % 32]).  Every branch on item data is uniform over the workgroup.
 template <int NW>
-__device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, int stride, float* sRed,
-                                          const ShrinkPrefetch& pf)
+__device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_pieces, float* sRed, int4 rec, int tok)
 {
     constexpr int NT = NW * kWave;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const int n_items = pf.n_items;
     const int K = a.K;
-    const int n_pieces = n_items / (a.g.n * a.n_kc);
-    for (int item = first_item; item < n_items; item += stride) {
-        const int pk = item / a.n_kc;
-        const int kc = item - pk * a.n_kc;
-        const int si = pk / n_pieces;                       // slice (projection of a packed group)
-        const int piece = pk - si * n_pieces;
-        const Slice sl = pick_slice(a.g, si);
-        int4 rec;
-        int tok;
-        if (item == first_item) {
-            rec = pf.rec;
-            tok = pf.tok;
-        } else {
-            rec = reinterpret_cast<const int4*>(a.dv.piece_info)[piece];
-            tok = (i < rec.y) ? a.dv.perm[rec.x + i] : 0;
-        }
-        const int m_begin = rec.x, nrows = rec.y, slot = rec.z, r = rec.w;
-        if (slot < 0 || r <= 0) continue;
-        const int c_begin = kc * a.kc_len;
-        int c_end = c_begin + a.kc_len;
-        if (c_end > K) c_end = K;
-        const int steps = (c_end - c_begin) / kBK;
-        const int per_wave = (steps + NW - 1) / NW;
-        const int k_begin = c_begin + wave * per_wave * kBK;
-        int k_end = k_begin + per_wave * kBK;
-        if (k_end > c_end) k_end = c_end;
+    const int pk = item / a.n_kc;
+    const int kc = item - pk * a.n_kc;
+    const int si = pk / n_pieces;                       // slice (projection of a packed group)
+    const Slice sl = pick_slice(a.g, si);
+    const int m_begin = rec.x, nrows = rec.y, slot = rec.z, r = rec.w;
+    if (slot < 0 || r <= 0) return;
+    const int c_begin = kc * a.kc_len;
+    int c_end = c_begin + a.kc_len;
+    if (c_end > K) c_end = K;
+    const int steps = (c_end - c_begin) / kBK;
+    const int per_wave = (steps + NW - 1) / NW;
+    const int k_begin = c_begin + wave * per_wave * kBK;
+    int k_end = k_begin + per_wave * kBK;
+    if (k_end > c_end) k_end = c_end;
 
-        const bool x_ok = i < nrows;
-        const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
-        const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + sl.a_off;
-        const bool a0_ok = i < r, a1_ok = (32 + i) < r;
-        const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
-        const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
+    const bool x_ok = i < nrows;
+    const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
+    const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + sl.a_off;
+    const bool a0_ok = i < r, a1_ok = (32 + i) < r;
+    const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
+    const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
 
-        f32x16 acc0, acc1;
+    f32x16 acc0, acc1;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
-        if (k_begin < k_end) {
-            if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
-            else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
-        }
+    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+    if (k_begin < k_end) {
+        if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+        else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+    }
 
-        // accumulator: column = grouped row m_begin + i, register 4 g + e = rank index 8 g + 4 h + e
-        const int halves = r > 32 ? 2 : 1;
-        for (int half = 0; half < halves; ++half) {
-            float* mine = sRed + wave * kRedFloatsPerWave + i * kRedStride;
+    // accumulator: column = grouped row m_begin + i, register 4 g + e = rank index 8 g + 4 h + e
+    const int halves = r > 32 ? 2 : 1;
+    for (int half = 0; half < halves; ++half) {
+        float* mine = sRed + wave * kRedFloatsPerWave + i * kRedStride;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 o;
+        for (int g = 0; g < 4; ++g) {
+            f32x4 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = half ? acc1[g * 4 + e] : acc0[g * 4 + e];
-                *reinterpret_cast<f32x4*>(mine + g * 8 + h * 4) = o;
-            }
-            __syncthreads();
-            for (int idx = tid; idx < kPieceRows * 8; idx += NT) {
-                const int row = idx >> 3, j4 = (idx & 7) * 4;
-                f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int w = 0; w < NW; ++w)
-                    sum += *reinterpret_cast<const f32x4*>(sRed + w * kRedFloatsPerWave + row * kRedStride + j4);
-                const int j = half * 32 + j4;
-                if (row < nrows && j < r)
-                    *reinterpret_cast<f32x4*>(sl.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + row)) * a.dv.max_rank + j) = sum;
-            }
-            __syncthreads();
+            for (int e = 0; e < 4; ++e) o[e] = half ? acc1[g * 4 + e] : acc0[g * 4 + e];
+            *reinterpret_cast<f32x4*>(mine + g * 8 + h * 4) = o;
         }
+        __syncthreads();
+        for (int idx = tid; idx < kPieceRows * 8; idx += NT) {
+            const int row = idx >> 3, j4 = (idx & 7) * 4;
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+                sum += *reinterpret_cast<const f32x4*>(sRed + w * kRedFloatsPerWave + row * kRedStride + j4);
+            const int j = half * 32 + j4;
+            if (row < nrows && j < r)
+                *reinterpret_cast<f32x4*>(sl.vpart + ((size_t)kc * a.dv.T + (size_t)(m_begin + row)) * a.dv.max_rank + j) = sum;
+        }
+        __syncthreads();
+    }
+}
+
+// Processes work items first_item, first_item + stride, ... below end_item with the whole workgroup.  pf: the
+// prefetched head of first_item.  An item starts with a chain of dependent loads (piece record -> token ->
+// operands), each a full memory latency under the weight stream of the other workgroups; the chain is
+// pipelined over three items: while item t is processed, the token of item t + 1 and the record of item t + 2
+// are on their way.
+template <int NW>
+__device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, int stride, int end_item, float* sRed,
+                                          const ShrinkPrefetch& pf)
+{
+    const int i = threadIdx.x & 31;
+    const int n_pieces = pf.n_pieces;
+    if (end_item > pf.n_items) end_item = pf.n_items;
+    auto record = [&](int item) {
+        int4 rec{0, 0, -1, 0};
+        if (item < end_item) rec = reinterpret_cast<const int4*>(a.dv.piece_info)[(item / a.n_kc) % n_pieces];
+        return rec;
+    };
+    auto token = [&](const int4& rec) { return (i < rec.y) ? a.dv.perm[rec.x + i] : 0; };
+    int it0 = first_item, it1 = first_item + stride, it2 = first_item + 2 * stride;
+    int4 r0 = pf.rec, r1 = record(it1);
+    int t0 = pf.tok;
+    while (it0 < end_item) {                                  // uniform over the workgroup
+        const int4 r2 = record(it2);
+        const int t1 = token(r1);
+        shrink_one_item<NW>(a, it0, n_pieces, sRed, r0, t0);
+        it0 = it1;
+        it1 = it2;
+        it2 += stride;
+        r0 = r1;
+        r1 = r2;
+        t0 = t1;
     }
 }
 
@@ -275,42 +297,146 @@ __device__ inline void expand_window_pipelined(f32x16 (&acc)[NB], int my_slot, i
     }
 }
 
-// Stages the scaled shrink results of one 32-row window as bf16 in LDS (sV: 32 rows of kVStageStride
-// elements, private to the calling wavefront): v[row][j] = bf16(scale_row * sum_c vpart[c][row][j]) for
-// j < rank_row, zero beyond.  Returns after the wave's LDS writes have completed, so any lane may read.
+// This lane's share q (0 .. 3) of the scaled shrink results of one 32-row window, packed as bf16:
+// (row, seg) = ((lane + 64 q) / 8, (lane + 64 q) % 8) -> bf16(scale_row * sum_c vpart[c][row][8 seg .. 8 seg + 7]),
+// zero beyond the row's rank.
 constexpr int kVStageStride = kMaxRank + 8;     // 144-byte rows: conflict-free 16-byte reads
-__device__ inline void stage_window_v(uint16_t* sV, const float* vpart, int n_kc, int win0, const DeviceView& dv)
+__device__ inline u32x4 window_v_share(int q, const float* vpart, int n_kc, int win0, const DeviceView& dv)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int T = dv.T;
+    const int idx = lane + 64 * q;
+    const int row = idx >> 3, seg = idx & 7;
+    const int mr = win0 + row;
+    u32x4 packed = {0u, 0u, 0u, 0u};
+    if (mr < T && seg * 8 < dv.max_rank) {
+        const int r = dv.row_rank[mr];
+        const float sc = dv.row_scale[mr];
+        if (seg * 8 < r) {
+            f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < n_kc; ++c) {
+                const float* vp = vpart + ((size_t)c * T + mr) * dv.max_rank + seg * 8;
+                lo += *reinterpret_cast<const f32x4*>(vp);
+                hi += *reinterpret_cast<const f32x4*>(vp + 4);
+            }
+            bf16x8 vb;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int idx = lane + 64 * q;
-        const int row = idx >> 3, seg = idx & 7;
-        const int mr = win0 + row;
-        u32x4 packed = {0u, 0u, 0u, 0u};
-        if (mr < T && seg * 8 < dv.max_rank) {
-            const int r = dv.row_rank[mr];
-            const float sc = dv.row_scale[mr];
-            if (seg * 8 < r) {
-                f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-                for (int c = 0; c < n_kc; ++c) {
-                    const float* vp = vpart + ((size_t)c * T + mr) * dv.max_rank + seg * 8;
-                    lo += *reinterpret_cast<const f32x4*>(vp);
-                    hi += *reinterpret_cast<const f32x4*>(vp + 4);
-                }
-                bf16x8 vb;
+            for (int e = 0; e < 4; ++e) {
+                vb[e] = (__bf16)(lo[e] * sc);
+                vb[4 + e] = (__bf16)(hi[e] * sc);
+            }
+            packed = __builtin_bit_cast(u32x4, vb);
+        }
+    }
+    return packed;
+}
+
+// Parks share q in the window's LDS image (sV: 32 rows of kVStageStride elements).
+__device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
+{
+    const int idx = (threadIdx.x & (kWave - 1)) + 64 * q;
+    *reinterpret_cast<u32x4*>(sV + (idx >> 3) * kVStageStride + (idx & 7) * 8) = packed;
+}
+
+// Stages the scaled shrink results of one 32-row window as bf16 in LDS (sV private to the calling
+// wavefront).  Returns after the wave's LDS writes have completed, so any lane may read.
+__device__ inline void stage_window_v(uint16_t* sV, const float* vpart, int n_kc, int win0, const DeviceView& dv)
+{
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    vb[e] = (__bf16)(lo[e] * sc);
-                    vb[4 + e] = (__bf16)(hi[e] * sc);
-                }
-                packed = __builtin_bit_cast(u32x4, vb);
+    for (int q = 0; q < 4; ++q) park_v_share(sV, q, window_v_share(q, vpart, n_kc, win0, dv));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LoRA expand for MB consecutive 32-row windows held by one wavefront, as one pipelined pass over the
+// (window, distinct slot) pairs: the B fragments of the next two pairs are in flight while the current
+// pair's MFMAs run, across window boundaries.  slot / rank / scale: the lane's row of each window
+// (slot -1 or rank 0: backbone only).  sV: the windows' scaled shrink results in LDS, window mb at
+// sV + mb * kPieceRows * kVStageStride.
+// ---------------------------------------------------------------------------------------------------
+template <int MB, int NB>
+__device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB],
+                                      const float (&scale)[MB], int n_first, int N, const DeviceView& dv, size_t b_off,
+                                      const uint16_t* sV)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    unsigned long long todo[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) todo[mb] = __ballot(slot[mb] >= 0 && rank[mb] > 0);
+    struct Item {
+        int mb, s, r;
+        bool valid;
+    };
+    auto next_item = [&]() {
+        Item q{0, -1, 0, false};
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if (!q.valid && todo[mb]) {                       // uniform over the wave
+                const int leader = __ffsll((long long)todo[mb]) - 1;
+                q.mb = mb;
+                q.s = __shfl(slot[mb], leader, kWave);
+                q.r = __shfl(rank[mb], leader, kWave);
+                q.valid = true;
+                todo[mb] &= ~__ballot(slot[mb] == q.s);
             }
         }
-        *reinterpret_cast<u32x4*>(sV + row * kVStageStride + seg * 8) = packed;
+        return q;
+    };
+    struct Frag {
+        u32x4 f[NB][4];
+    };
+    auto fetch = [&](const Item& q, Frag& fb) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = n_first + nb * 32 + i;
+            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int k = ks * 16 + h * 8;
+                fb.f[nb][ks] = u32x4{0u, 0u, 0u, 0u};
+                if (q.valid && n < N && k < q.r) fb.f[nb][ks] = load16(Bs + k);
+            }
+        }
+    };
+    auto apply = [&](const Item& q, const Frag& fb) {
+        int my = slot[0];
+#pragma unroll
+        for (int mb = 1; mb < MB; ++mb)
+            if (q.mb == mb) my = slot[mb];
+        const bool mine = my == q.s;
+        const uint16_t* vrow = sV + (q.mb * kPieceRows + i) * kVStageStride;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks * 16 < q.r) {
+                const int k = ks * 16 + h * 8;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (mine && k < q.r) v = *reinterpret_cast<const u32x4*>(vrow + k);
+                const bf16x8 vf = as_bf16x8(v);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    if (q.mb == mb) {                         // uniform over the wave
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(as_bf16x8(fb.f[nb][ks]), vf, acc[mb][nb]);
+                    }
+                }
+            }
+        }
+    };
+    Frag fa, fb, fc;
+    Item qa = next_item();
+    fetch(qa, fa);
+    Item qb = next_item();
+    fetch(qb, fb);
+    while (qa.valid) {
+        Item qc = next_item();
+        fetch(qc, fc);
+        apply(qa, fa);
+        qa = qb;
+        fa = fb;
+        qb = qc;
+        fb = fc;
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
 }  // namespace lora

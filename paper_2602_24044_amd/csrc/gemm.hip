@@ -366,7 +366,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
         finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, ring);
     if (!FUSED && sa.on) {
         __syncthreads();
-        shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
+        shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, spf.n_items, reinterpret_cast<float*>(ring), spf);
     }
 }
 

@@ -8,6 +8,76 @@
 
 namespace lora {
 
+// Fused path, wave tiles of at most two 32-row windows: what the epilogue needs from memory besides the B rows
+// is fetched before the main loop and waits in registers, so that the tail of the kernel - which no other
+// workgroup overlaps when the launch is a single round - holds one memory latency per (window, slot) pair
+// instead of three per window.
+template <int MB>
+struct TilePrefetch {
+    int slot[MB], rank[MB];          // this lane's row of each window
+    float scale[MB];
+    u32x4 v[MB][4];                  // this lane's shares of the windows' scaled shrink results (packed bf16)
+};
+
+template <int MB>
+__device__ __forceinline__ void prefetch_windows(TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int m_first)
+{
+    const int i = threadIdx.x & 31;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = m_first + mb * 32 + i;
+        const bool ok = m < a.dv.T;
+        pf.slot[mb] = ok ? a.dv.row_slot[m] : -1;
+        pf.rank[mb] = ok ? a.dv.row_rank[m] : 0;
+        pf.scale[mb] = ok ? a.dv.row_scale[m] : 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) pf.v[mb][q] = window_v_share(q, sl.vpart, a.n_kc, m_first + mb * 32, a.dv);
+    }
+}
+
+// Epilogue of the fused path from prefetched window data.  ring: LDS free again (the caller has synchronised);
+// this wave parks its MB windows at ring + wave * MB * kPieceRows * kVStageStride.
+template <int MB, int NB>
+__device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], const GemmArgs& a, const Slice& sl,
+                                                       int m_first, int n_first, int wave, uint16_t* ring,
+                                                       const TilePrefetch<MB>& pf)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    const int T = a.dv.T, N = sl.N;
+    bool any = false;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) any = any || __ballot(pf.slot[mb] >= 0 && pf.rank[mb] > 0) != 0;
+    if (any) {                                                    // uniform over the wave
+        uint16_t* sV = ring + wave * (MB * kPieceRows * kVStageStride);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        expand_windows<MB, NB>(acc, pf.slot, pf.rank, pf.scale, n_first, N, a.dv, sl.b_off, sV);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = m_first + mb * 32 + i;
+        if (m < T) {
+            uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n_first + nb * 32 + g * 8 + h * 4;
+                    if (n < N) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[mb][nb][g * 4 + e];
+                        *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
+                    }
+                }
+        }
+    }
+}
+
 // acc[mb][nb]: 32x32 blocks in "W-first" orientation (lane (i, h) holds grouped row m_first + 32 mb + i and
 // output columns n_first + 32 nb + 8 g + 4 h + e in register 4 g + e); n_first is a column inside slice sl.
 // ring: LDS no longer used by the main loop (the caller has synchronised); the fused path parks the scaled

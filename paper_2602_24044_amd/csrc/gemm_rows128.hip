@@ -55,6 +55,20 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     static_assert(NS * STAGE_B <= 160 * 1024, "LDS");
 
     __shared__ __attribute__((aligned(1024))) uint8_t ring[NS * STAGE_B];
+    // split path: the workgroups past the tile grid only do shrink items
+    const int extra = (int)gridDim.x - a.main_grid;          // shrink-only workgroups of this launch
+    if (!FUSED && sa.on && (int)blockIdx.x >= a.main_grid) {
+        const int idx = (int)blockIdx.x - a.main_grid;
+        float* sRed = reinterpret_cast<float*>(ring);
+        const ShrinkPrefetch pa = shrink_prefetch(sa, idx);
+        shrink_block_items<NWV>(sa, idx, extra, extra * a.shrink_q, sRed, pa);
+        const int rest = extra * a.shrink_q + (int)blockIdx.x;
+        if (rest < pa.n_items) {                              // uniform over the workgroup
+            const ShrinkPrefetch pb = shrink_prefetch(sa, rest);
+            shrink_block_items<NWV>(sa, rest, gridDim.x, pb.n_items, sRed, pb);
+        }
+        return;
+    }
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -84,7 +98,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     const int m0 = tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
 
     ShrinkPrefetch spf{};
-    if (!FUSED && sa.on) spf = shrink_prefetch(sa, blockIdx.x);
+    const int rest_first = extra * a.shrink_q + (int)blockIdx.x;     // this workgroup's first item after its tile
+    if (!FUSED && sa.on) spf = shrink_prefetch(sa, rest_first);
 
     const int kt_total = K / kTK64;
     int kt_begin = 0, kt_end = kt_total;
@@ -146,6 +161,11 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     for (int d = 0; d < NS - 1; ++d)
         if (d < nk) copy_tile(d, d);
 
+    // fused path: the epilogue's per-row data travels while the first tiles do
+    constexpr bool PRE = FUSED && MB <= 2;
+    TilePrefetch<PRE ? MB : 1> pre;
+    if constexpr (PRE) prefetch_windows(pre, a, sl, m0 + wm * WTM);
+
     int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
     for (int j = 0; j < nk; ++j) {
         // own copies of tile j landed; the (at most NS - 2) younger tiles stay in flight
@@ -182,13 +202,16 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     }
 
     // ---------------- epilogue ----------------
-    static_assert(!FUSED || NS * STAGE_B >= NWV * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    static_assert(!FUSED || NS * STAGE_B >= NWV * (PRE ? MB : 1) * kPieceRows * kVStageStride * 2, "ring too small for v staging");
     static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
-    finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, reinterpret_cast<uint16_t*>(ring));
+    if constexpr (PRE)
+        finish_tile_prefetched<MB, NB>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, wave, reinterpret_cast<uint16_t*>(ring), pre);
+    else
+        finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, reinterpret_cast<uint16_t*>(ring));
     if (!FUSED && sa.on) {
         __syncthreads();
-        shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, reinterpret_cast<float*>(ring), spf);
+        shrink_block_items<NWV>(sa, rest_first, gridDim.x, spf.n_items, reinterpret_cast<float*>(ring), spf);
     }
 }
 
@@ -201,7 +224,10 @@ hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
         a.g.s[k].tile0 = a.tiles_n;
         a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
     }
-    const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
+    int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
+    const int extra = FUSED ? 0 : a.main_grid;            // on entry: workgroups that only do shrink items
+    a.main_grid = grid;
+    grid += extra;
     hipLaunchKernelGGL((gemm_rows128_kernel<BM, BN, WGM, WGN, FUSED, NS>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream,
                        a, sa);
     return hipGetLastError();

@@ -586,7 +586,7 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
 
     // ---- plan ----
     const int Mpad = (T + 255) / 256 * 256;
-    bool split = false;
+    bool split = false, dyn_shrink = false;
     int S = 1;
     int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
     if (T <= kSplitMaxTokens) {
@@ -602,9 +602,17 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
             split_variant = (n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
         const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
         const long tiles = tiles_of(bm, bn);
+        // The 64-wide-K kernels give a quarter of the CUs workgroups that only shrink, from the start (a shrink
+        // item is a chain of dependent loads: behind the tile it would be a tail that no other work hides).
+        // Only while those workgroups can finish the items meanwhile: a batch spread over hundreds of adapters
+        // has more shrink work than tile work, and every workgroup takes its share after its tile instead.
+        const long pieces_bound = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+        dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7) &&
+                     pieces_bound * std::max(1, K / 2048) <= 512;
+        const long target = dyn_shrink ? 192 : 256;
         // enough K splits to give every CU a workgroup, but no more than 8: each split costs a pass of
         // fp32 partial tiles through memory
-        S = c->cfg.split_k > 0 ? c->cfg.split_k : (int)std::max<long>(1, std::min<long>(8, (256 + tiles / 2) / tiles));
+        S = c->cfg.split_k > 0 ? c->cfg.split_k : (int)std::max<long>(1, std::min<long>(8, (target + tiles / 2) / tiles));
         S = std::min(S, std::max(1, (K / kBK) / 2));
         const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
         S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
@@ -612,11 +620,15 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         // a single K range would only add the round trip of the partial tiles: the launch already fills
         // the chip, take the fused path with the same tile
         if (S == 1 && c->cfg.path == LORA_PATH_AUTO) split = false;
+        if (!split) dyn_shrink = false;
     }
     int n_kc = 1, kc_len = K;
     if (T <= kSplitMaxTokens) {
         n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
-        if (split) {
+        if (split && dyn_shrink) {
+            // chunks of 2048: one round of operand loads per wavefront and item
+            n_kc = std::max(1, std::min<int>(kMaxShrinkChunks, K / 2048));
+        } else if (split) {
             // The shrink items (slice x piece x K chunk) are shared out over the workgroups of the split GEMM,
             // each item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup
             // one item (when there are more pieces than workgroups, fine chunks balance better and stay).
@@ -674,6 +686,17 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
     ga.nblk = blk;
     ga.part = part;
     ga.Mpad = Mpad;
+    ga.main_grid = 0;
+    ga.shrink_q = 0;
+    if (split && dyn_shrink) {
+        const int bm = split_bm(split_variant);
+        const long main_wgs = tiles_of(bm, 128) * S;
+        ga.main_grid = (int)std::max<long>(0, std::min<long>(128, 256 - main_wgs));   // on entry: shrink-only workgroups
+        // items a shrink-only workgroup finishes while a tile workgroup walks its K range: a 64-wide K tile of
+        // the tile workgroup takes about 1 us, an item about 8
+        const int nk = std::max(1, K / kBK / S);
+        ga.shrink_q = std::max(1, nk / 4);
+    }
 
     if (!split) {
         // ---- shrink, then base GEMM with the expand in its epilogue ----

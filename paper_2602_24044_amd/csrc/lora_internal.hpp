@@ -112,6 +112,11 @@ struct GemmArgs {
     int32_t nblk;        // 32-column blocks per row block of the packed partial matrix
     float* part;         // split path: [split_k][Mpad / 32][nblk][1024] fp32
     int32_t Mpad;
+    // split path of the 64-wide-K kernels: workgroups main_grid .. grid - 1 only do shrink items, shrink_q each,
+    // while the tile workgroups stream; what is left is shared out over every workgroup (0: every workgroup
+    // takes the items blockIdx, blockIdx + grid, ... after its tile)
+    int32_t main_grid;
+    int32_t shrink_q;
 };
 
 struct ReduceArgs {

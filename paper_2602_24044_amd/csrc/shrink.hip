@@ -12,7 +12,7 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(ShrinkArgs a)
     constexpr int NW = kShrinkThreads / kWave;
     __shared__ __attribute__((aligned(16))) float sRed[NW * kRedFloatsPerWave];
     const ShrinkPrefetch pf = shrink_prefetch(a, blockIdx.x);
-    shrink_block_items<NW>(a, blockIdx.x, gridDim.x, sRed, pf);
+    shrink_block_items<NW>(a, blockIdx.x, gridDim.x, pf.n_items, sRed, pf);
 }
 
 }  // namespace
