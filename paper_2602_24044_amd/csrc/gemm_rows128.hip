@@ -131,15 +131,19 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     }
     const uint32_t cp_x = ring_addr + wave * XQ * 1024;
     const uint32_t cp_w = ring_addr + BM * kRowB + wave * WQ * 1024;
-    auto copy_tile = [&](int t, int stage) {                // tile t of this workgroup's K range
+    // copy instructions [q_begin, q_end) of tile t of this workgroup's K range; the W rows (from HBM) go first
+    auto copy_part = [&](int t, int stage, int q_begin, int q_end) {
         const uint32_t k0 = (uint32_t)t * kTK64, so = (uint32_t)stage * STAGE_B;
 #pragma unroll
-        for (int q = 0; q < XQ; ++q)
-            copy16_to_lds(xg + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
-#pragma unroll
-        for (int q = 0; q < WQ; ++q)
-            copy16_to_lds(Wg + (woff[q] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + q * 1024));
+        for (int q = 0; q < QPT; ++q) {
+            if (q < q_begin || q >= q_end) continue;
+            if (q < WQ)
+                copy16_to_lds(Wg + (woff[q] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + q * 1024));
+            else
+                copy16_to_lds(xg + (xoff[q - WQ] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + (q - WQ) * 1024));
+        }
     };
+    auto copy_tile = [&](int t, int stage) { copy_part(t, stage, 0, QPT); };
 
     f32x16 acc[MB][NB];
 #pragma unroll
@@ -176,7 +180,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         else if (young == 1) wait_copies_then_barrier<QPT>();
         else wait_copies_then_barrier<0>();
         // tile j is complete for every wave and every wave has finished tile j - 1: refill its stage
-        if (j + NS - 1 < nk) copy_tile(j + NS - 1, fre);
+        // The copy instructions are spread over the four K steps: a wave that is held at a copy instruction
+        // by a full memory pipeline cannot issue its MFMAs meanwhile.
+        const bool refill = j + NS - 1 < nk;
 
         const uint8_t* st = ring + cur * STAGE_B;
         bf16x8 Fw[2][NB], Fx[2][MB];
@@ -192,6 +198,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) read_step((kk + 1) & 1, kk + 1);
+            if (refill) copy_part(j + NS - 1, fre, kk * QPT / 4, (kk + 1) * QPT / 4);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
