@@ -349,15 +349,15 @@ __device__ inline void stage_window_v(uint16_t* sV, const float* vpart, int n_kc
 
 // ---------------------------------------------------------------------------------------------------
 // LoRA expand for MB consecutive 32-row windows held by one wavefront, as one pipelined pass over the
-// (window, distinct slot) pairs: the B fragments of the next two pairs are in flight while the current
-// pair's MFMAs run, across window boundaries.  slot / rank / scale: the lane's row of each window
-// (slot -1 or rank 0: backbone only).  sV: the windows' scaled shrink results in LDS, window mb at
+// (window, distinct slot) pairs: the B fragments of the next D - 1 pairs are in flight while the current
+// pair's MFMAs run, across window boundaries (every pair's fragments are a dependent global load: the depth
+// of the ring sets the duration of the pass).  slot / rank: the lane's row of each window (slot -1 or rank 0:
+// backbone only).  sV: the windows' scaled shrink results in LDS, window mb at
 // sV + mb * kPieceRows * kVStageStride.
 // ---------------------------------------------------------------------------------------------------
-template <int MB, int NB>
-__device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB],
-                                      const float (&scale)[MB], int n_first, int N, const DeviceView& dv, size_t b_off,
-                                      const uint16_t* sV)
+template <int MB, int NB, int D>
+__device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB], int n_first,
+                                      int N, const DeviceView& dv, size_t b_off, const uint16_t* sV)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
@@ -423,19 +423,21 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
             }
         }
     };
-    Frag fa, fb, fc;
-    Item qa = next_item();
-    fetch(qa, fa);
-    Item qb = next_item();
-    fetch(qb, fb);
-    while (qa.valid) {
-        Item qc = next_item();
-        fetch(qc, fc);
-        apply(qa, fa);
-        qa = qb;
-        fa = fb;
-        qb = qc;
-        fb = fc;
+    // ring of D pairs, consumed in ring order; position d is refilled right after its pair has been applied
+    Frag f[D];
+    Item q[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        q[d] = next_item();
+        fetch(q[d], f[d]);
+    }
+    while (q[0].valid) {                                      // a pass without a pair at position 0 has none at all
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (q[d].valid) apply(q[d], f[d]);                // uniform over the wave
+            q[d] = next_item();
+            fetch(q[d], f[d]);
+        }
     }
 }
 

@@ -55,7 +55,7 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
 #pragma unroll
             for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        expand_windows<MB, NB>(acc, pf.slot, pf.rank, pf.scale, n_first, N, a.dv, sl.b_off, sV);
+        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, N, a.dv, sl.b_off, sV);
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {

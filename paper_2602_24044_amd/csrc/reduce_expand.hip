@@ -96,15 +96,11 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     }
     __syncthreads();
 
-    const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
-    const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
-    const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
-    auto vfrag = [&](int k, bool on, float) -> bf16x8 {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStride + k);
-        return as_bf16x8(v);
-    };
-    expand_window_pipelined<1>(acc, my_slot, my_rank, my_scale, n_first, N, a.dv, sl.b_off, vfrag);
+    const int my_slot[1] = {m_ok ? a.dv.row_slot[m] : -1};
+    const int my_rank[1] = {m_ok ? a.dv.row_rank[m] : 0};
+    f32x16 accw[1][1] = {{acc[0]}};
+    expand_windows<1, 1, 6>(accw, my_slot, my_rank, n_first, N, a.dv, sl.b_off, sV);
+    acc[0] = accw[0][0];
 
     if (m_ok) {
         uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
