@@ -45,9 +45,10 @@ __device__ inline int block_excl_scan(int v, int* s_wave, int* total)
     return res;
 }
 
-// Run-length encoding of row_slot[0..T); with align > 0 a run also ends at every multiple of align.
+// Run-length encoding of row_slot[0..T); with align > 0 a run also ends at every multiple of align.  m_start /
+// m_slot (may be NULL): copies of the outputs in LDS for the next phase of the same workgroup.
 __device__ void rle(const int32_t* row_slot, int T, int align, int32_t* out_start, int32_t* out_slot,
-                    int32_t* out_n, int* s_wave)
+                    int32_t* out_n, int* s_wave, int* m_start, int* m_slot)
 {
     int running = 0;
     for (int c = 0; c < T; c += kBT) {
@@ -62,30 +63,57 @@ __device__ void rle(const int32_t* row_slot, int T, int align, int32_t* out_star
         if (head) {
             out_start[running + ex] = m;
             out_slot[running + ex] = s;
+            if (m_start) {
+                m_start[running + ex] = m;
+                m_slot[running + ex] = s;
+            }
         }
         running += total;
     }
     if (threadIdx.x == 0) {
         out_start[running] = T;
+        if (m_start) m_start[running] = T;
         *out_n = running;
     }
 }
+
+// Steps of up to kFastT tokens keep every intermediate array in LDS (keys in registers, grouped slots, the
+// piece list, the slot tables): the kernel is a chain of dependent phases, and a phase that reads back from
+// global memory what the previous one wrote pays a memory round trip each time.
+constexpr int kFastT = 4096;
+constexpr int kFastPieces = kFastT + kFastT / kPieceRows + 2;
 
 __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
 {
     __shared__ int s_run[kMaxKeys];      // histogram, then running output offset per key
     __shared__ int s_wave[kNW + 1];
+    __shared__ int s_row[kFastT];        // fast path: row_slot
+    __shared__ int s_pstart[kFastPieces + 1];
+    __shared__ int s_pslot[kFastPieces];
+    __shared__ int s_rank[kMaxKeys];     // fast path: slot tables
+    __shared__ float s_scale[kMaxKeys];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int T = a.T;
     const int nkeys = a.n_slots + 1;     // key = slot + 1, key 0 = backbone only
     const bool sorted = (a.mode == 0);
+    const bool fast = T <= kFastT;
+    constexpr int kFastChunks = kFastT / kBT;
 
     for (int k = tid; k < nkeys; k += kBT) s_run[k] = 0;
+    if (fast) {
+        for (int k = tid; k < a.n_slots; k += kBT) {
+            s_rank[k] = a.slot_rank[k];
+            s_scale[k] = a.slot_scale[k];
+        }
+    }
     __syncthreads();
 
     // keys, histogram, residency check
     bool bad = false;
-    for (int t = tid; t < T; t += kBT) {
+    int keyreg[kFastChunks];
+#pragma unroll
+    for (int c = 0; c < kFastChunks; ++c) keyreg[c] = 0;
+    auto key_of = [&](int t) {
         const int id = a.ids[t];
         int key = 0;
         if (id >= 0) {
@@ -93,12 +121,34 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
             if (id < a.n_ids) s = a.id2slot[id];
             if (s >= 0 && s < a.n_slots) key = s + 1; else bad = true;
         }
-        if (sorted) {
-            a.tok_key[t] = key;
-            atomicAdd(&s_run[key], 1);
-        } else {
-            a.perm[t] = t;
-            a.row_slot[t] = key - 1;
+        return key;
+    };
+    if (fast) {
+#pragma unroll
+        for (int c = 0; c < kFastChunks; ++c) {
+            const int t = c * kBT + tid;
+            if (t < T) {
+                const int key = key_of(t);
+                keyreg[c] = key;
+                if (sorted) {
+                    atomicAdd(&s_run[key], 1);
+                } else {
+                    a.perm[t] = t;
+                    a.row_slot[t] = key - 1;
+                    s_row[t] = key - 1;
+                }
+            }
+        }
+    } else {
+        for (int t = tid; t < T; t += kBT) {
+            const int key = key_of(t);
+            if (sorted) {
+                a.tok_key[t] = key;
+                atomicAdd(&s_run[key], 1);
+            } else {
+                a.perm[t] = t;
+                a.row_slot[t] = key - 1;
+            }
         }
     }
     if (bad) atomicOr(a.flags, 1u);
@@ -119,10 +169,18 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
 
         // stable scatter: tokens are taken 1024 at a time in index order, wave after wave
         const int nbits = 32 - __clz(a.n_slots);
-        for (int c = 0; c < T; c += kBT) {
+        int chunk = 0;
+        for (int c = 0; c < T; c += kBT, ++chunk) {
             const int t = c + tid;
             const bool valid = t < T;
-            const int key = valid ? a.tok_key[t] : 0;
+            int key = 0;
+            if (fast) {
+#pragma unroll
+                for (int q = 0; q < kFastChunks; ++q)
+                    if (q == chunk) key = keyreg[q];
+            } else if (valid) {
+                key = a.tok_key[t];
+            }
             unsigned long long peers = __ballot(valid);
             for (int b = 0; b < nbits; ++b) {
                 const bool bit = (key >> b) & 1;
@@ -138,6 +196,7 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
                     const int pos = s_run[key] + rank;
                     a.perm[pos] = t;
                     a.row_slot[pos] = key - 1;
+                    if (fast) s_row[pos] = key - 1;
                 }
                 __builtin_amdgcn_wave_barrier();
                 if (wave == w && valid && rank == cw - 1) s_run[key] += cw;
@@ -148,25 +207,43 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     __syncthreads();
 
     // per-row adapter metadata, so that the projection kernels never chase slot -> rank / scale
+    const int32_t* rs = fast ? s_row : a.row_slot;
     for (int m = tid; m < T; m += kBT) {
-        const int s = a.row_slot[m];
-        a.row_rank[m] = s >= 0 ? a.slot_rank[s] : 0;
-        a.row_scale[m] = s >= 0 ? a.slot_scale[s] : 0.f;
+        const int s = rs[m];
+        if (fast) {
+            a.row_rank[m] = s >= 0 ? s_rank[s] : 0;
+            a.row_scale[m] = s >= 0 ? s_scale[s] : 0.f;
+        } else {
+            a.row_rank[m] = s >= 0 ? a.slot_rank[s] : 0;
+            a.row_scale[m] = s >= 0 ? a.slot_scale[s] : 0.f;
+        }
     }
 
-    rle(a.row_slot, T, 0, a.seg_start, a.seg_slot, a.n_seg, s_wave);
-    rle(a.row_slot, T, kPieceRows, a.piece_start, a.piece_slot, a.n_pieces, s_wave);
+    rle(rs, T, 0, a.seg_start, a.seg_slot, a.n_seg, s_wave, nullptr, nullptr);
+    rle(rs, T, kPieceRows, a.piece_start, a.piece_slot, a.n_pieces, s_wave, fast ? s_pstart : nullptr,
+        fast ? s_pslot : nullptr);
     __syncthreads();
 
     // one 16-byte record per piece for the shrink work loop
     const int n_pieces = *a.n_pieces;
     for (int p = tid; p < n_pieces; p += kBT) {
-        const int begin = a.piece_start[p], end = a.piece_start[p + 1], s = a.piece_slot[p];
+        int begin, end, s, r;
+        if (fast) {
+            begin = s_pstart[p];
+            end = s_pstart[p + 1];
+            s = s_pslot[p];
+            r = s >= 0 ? s_rank[s] : 0;
+        } else {
+            begin = a.piece_start[p];
+            end = a.piece_start[p + 1];
+            s = a.piece_slot[p];
+            r = s >= 0 ? a.slot_rank[s] : 0;
+        }
         int4 rec;
         rec.x = begin;
         rec.y = end - begin;
         rec.z = s;
-        rec.w = s >= 0 ? a.slot_rank[s] : 0;
+        rec.w = r;
         reinterpret_cast<int4*>(a.piece_info)[p] = rec;
     }
 }
