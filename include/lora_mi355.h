@@ -142,8 +142,10 @@ lora_status lora_destroy(lora_ctx *ctx);
  * into the GPU's adapter region; load time grows with adapter size, unloading is free).
  * in_use / n_in_use (host): adapter ids of the batch about to run; they are marked used now and
  * are never chosen as victims.  The whole call is planned on the host first: on any error
- * nothing is enqueued and the table is unchanged.  On success the copies (one per matrix),
- * the slot metadata update and the id->slot map update are enqueued on copy_stream; later
+ * nothing is enqueued and the table is unchanged.  On success the copies (one kernel launch per
+ * projection, reading the page-locked host buffers directly; a source that is not page-locked,
+ * device-visible host memory is copied with hipMemcpyAsync instead), the slot metadata update
+ * and the id->slot map update are enqueued on copy_stream; later
  * lora_bucket / lora_layer_forward calls on other streams wait for them through events, and
  * the copies themselves wait for forward work already enqueued (a slot is never overwritten
  * while an earlier step may still read it).

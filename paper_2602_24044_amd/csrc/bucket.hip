@@ -259,6 +259,28 @@ __global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slo
     }
 }
 
+// blockIdx.y: matrix of the batch; the workgroups of a row stride over its 16-byte units.  The sources are
+// pinned host memory read over the host link: enough 16-byte loads in flight per lane to keep it busy.
+constexpr int kCopyThreads = 256, kCopyBlocksPerMatrix = 16, kCopyUnroll = 4;
+__global__ __launch_bounds__(kCopyThreads) void copy_batch_kernel(CopyBatch b)
+{
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const int m = blockIdx.y;
+    const u32x4* src = static_cast<const u32x4*>(b.src[m]);
+    u32x4* dst = static_cast<u32x4*>(b.dst[m]);
+    const uint32_t n = b.bytes[m] / 16;
+    const uint32_t stride = gridDim.x * kCopyThreads;
+    for (uint32_t i0 = blockIdx.x * kCopyThreads + threadIdx.x; i0 < n; i0 += stride * kCopyUnroll) {
+        u32x4 v[kCopyUnroll];
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (i0 + u * stride < n) v[u] = __builtin_nontemporal_load(src + i0 + u * stride);
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (i0 + u * stride < n) dst[i0 + u * stride] = v[u];
+    }
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int32_t value, size_t n)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -277,6 +299,13 @@ hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* s
                               hipStream_t stream)
 {
     hipLaunchKernelGGL(meta_update_kernel, dim3(1), dim3(kWave), 0, stream, u, slot_rank, slot_scale, id2slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_batch(const CopyBatch& b, hipStream_t stream)
+{
+    if (b.n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_batch_kernel, dim3(kCopyBlocksPerMatrix, b.n), dim3(kCopyThreads), 0, stream, b);
     return hipGetLastError();
 }
 

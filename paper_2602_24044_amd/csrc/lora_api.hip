@@ -42,6 +42,20 @@ struct Layout {
 // split-K GEMM variants 3, 4 and 7 use 128-row tiles, the others 256-row tiles; 6 and 7 walk K in 64-wide tiles
 int split_bm(int variant) { return (variant == 3 || variant == 4 || variant == 7) ? 128 : 256; }
 
+// Device-visible address of a pointer into pinned (page-locked, mapped) host memory, or NULL when the pointer
+// is anything else (pageable host memory must never reach a kernel).
+const void* device_view_of_pinned(const void* p)
+{
+    hipPointerAttribute_t at;
+    std::memset(&at, 0, sizeof at);
+    if (hipPointerGetAttributes(&at, p) != hipSuccess) {
+        (void)hipGetLastError();      // an unknown (pageable) pointer is reported as an error: clear it
+        return nullptr;
+    }
+    if (at.type != hipMemoryTypeHost || !at.devicePointer) return nullptr;
+    return at.devicePointer;
+}
+
 int auto_split_cap(int N)
 {
     const int tiles_n = (N + 127) / 128;
@@ -468,18 +482,38 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     }
     if (HIP_FAIL(hipEventRecord(c->ev_meta, cs))) return LORA_ERR_HIP;
     c->meta_pending = true;
+    // The matrices of one projection travel in one launch of a kernel that reads the pinned host memory itself
+    // (a hipMemcpyAsync per matrix costs the host and the copy engine about as much as the matrix's transfer);
+    // a source that is not device-visible pinned host memory goes through hipMemcpyAsync.
     char* slots = c->base + c->L.off_slots;
     for (int p = 0; p < n_proj; ++p) {
         const size_t d_in = c->proj[p].d_in, d_out = c->proj[p].d_out;
+        CopyBatch batch;
+        batch.n = 0;
+        auto flush = [&]() -> bool {
+            if (batch.n > 0 && HIP_FAIL(launch_copy_batch(batch, cs))) return false;
+            batch.n = 0;
+            return true;
+        };
+        auto enqueue = [&](void* dst, const void* src, size_t bytes) -> bool {
+            const void* dev_src = device_view_of_pinned(src);
+            if (!dev_src || bytes % 16 || bytes > 0xffffffffu || (reinterpret_cast<uintptr_t>(src) & 15))
+                return !HIP_FAIL(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, cs));
+            if (batch.n == kCopyBatch && !flush()) return false;
+            batch.src[batch.n] = dev_src;
+            batch.dst[batch.n] = dst;
+            batch.bytes[batch.n] = (uint32_t)bytes;
+            ++batch.n;
+            return true;
+        };
         for (int i = 0; i < n; ++i) {
             if (!out_copied[i] || descs[i].rank <= 0) continue;
             const size_t r = descs[i].rank;
             char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
-            if (HIP_FAIL(hipMemcpyAsync(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2, hipMemcpyHostToDevice, cs)))
-                return LORA_ERR_HIP;
-            if (HIP_FAIL(hipMemcpyAsync(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2, hipMemcpyHostToDevice, cs)))
-                return LORA_ERR_HIP;
+            if (!enqueue(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2)) return LORA_ERR_HIP;
+            if (!enqueue(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2)) return LORA_ERR_HIP;
         }
+        if (!flush()) return LORA_ERR_HIP;
         if (HIP_FAIL(hipEventRecord(c->ev_proj[p], cs))) return LORA_ERR_HIP;
         c->proj_pending[p] = true;
     }

@@ -71,6 +71,17 @@ struct MetaUpdates {
     float scale[kMetaBatch];
 };
 
+// Adapter matrices on their way from pinned host memory into their slots: one launch copies a batch of them,
+// reading the host memory directly (paper Sec. 2.2: adapters are swapped in from CPU memory).
+constexpr int kCopyBatch = 32;
+struct CopyBatch {
+    int32_t n;
+    int32_t pad_;
+    const void* src[kCopyBatch];   // device-visible address of pinned host memory
+    void* dst[kCopyBatch];         // inside a slot
+    uint32_t bytes[kCopyBatch];    // multiple of 16
+};
+
 // One launch can serve several projections that share d_in ("packed projections": q|k|v, gate|up), each with
 // its own x, W, out and adapter matrices.  The slices sit side by side along N: tiles, 32-column blocks of the
 // split-K partial matrix and shrink work items are numbered across them.
@@ -134,6 +145,7 @@ hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream);
 hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot,
                               hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stream);
+hipError_t launch_copy_batch(const CopyBatch& b, hipStream_t stream);
 hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);
 hipError_t launch_gemm_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
 hipError_t launch_gemm_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
