@@ -124,6 +124,11 @@ def shapes_70b(shrink: int = 1):
     return llama_proj_shapes(8192 // shrink, 28672 // shrink, 1024 // shrink)
 
 
+def shapes_qwen_7b(shrink: int = 1):
+    """Qwen2.5-7B, the paper's second backbone (Sec. 8.1): no dimension is a power of two."""
+    return llama_proj_shapes(3584 // shrink, 18944 // shrink, 512 // shrink)
+
+
 # --------------------------------------------------------------------------
 # building blocks
 # --------------------------------------------------------------------------
@@ -255,6 +260,18 @@ def config5(shrink: int = 1, prefill_len: int = 2048, n_decode: int = 384, popul
     ranks = {i: ranks_all[i] for i in sorted(used)}
     return custom(f"cfg5_70b_mixed_s{shrink}", seed, proj, names, n_slots, 32, BUCKET_SORTED, ids, ranks,
                   resident=resident, missing=missing)
+
+
+def qwen_decode(shrink: int = 1, n_tokens: int = 256, mode: int = BUCKET_SORTED) -> Workload:
+    """Config-2-like decode step at Qwen2.5-7B shapes: 32 adapters of ranks {8,16,32}, Zipf(1) ids."""
+    seed = 7
+    rng = np.random.default_rng(1000 + seed)
+    proj, names = shapes_qwen_7b(shrink)
+    ranks = {i: int(r) for i, r in enumerate(rng.choice([8, 16, 32], size=32))}
+    ids = zipf_ids(rng, n_tokens, list(range(32)), 1.0)
+    if mode != BUCKET_SORTED:
+        ids = np.sort(ids)[::-1].copy()          # runs of equal adapters, as contiguous prefill requests would be
+    return custom(f"qwen7b_decode_s{shrink}", seed, proj, names, 32, 32, mode, ids, ranks)
 
 
 def by_index(i: int, **kw) -> Workload:

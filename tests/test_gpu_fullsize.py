@@ -78,3 +78,7 @@ def test_config3_full():
 
 def test_config5_full():
     _run_full(wl.config5(), n_samples=800)
+
+
+def test_qwen_7b_decode_full():
+    _run_full(wl.qwen_decode(), n_samples=800)

@@ -50,6 +50,18 @@ def test_config5_mixed_with_loads_reduced(path):
     run_and_check(w, path=path)
 
 
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("packed", [False, True])
+def test_qwen_shapes_decode_reduced(path, packed):
+    # hidden 896, intermediate 4736, kv 128: ragged last tiles along N for every tile width, K not a power of two
+    run_and_check(wl.qwen_decode(shrink=4, n_tokens=200), path=path, packed=packed)
+
+
+def test_qwen_shapes_prefill_runs_reduced():
+    w = wl.qwen_decode(shrink=4, n_tokens=1300, mode=wl.BUCKET_RUNS)
+    run_and_check(w, path=B.LORA_PATH_AUTO, packed=True)
+
+
 @pytest.mark.parametrize("split_k", [1, 2, 3, 16])
 def test_split_k_values(split_k):
     run_and_check(wl.config2(shrink=8, n_tokens=130), path=B.LORA_PATH_SPLITK, split_k=split_k)
