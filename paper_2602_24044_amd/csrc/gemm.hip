@@ -95,7 +95,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
     const bool producer = PW > 0 && wave >= NCW;
     const int cwave = PW > 0 ? wave - NCW : wave;           // index among the copying waves
     const int wm = wave % WGM, wn = (wave / WGM) % WGN;
-    const int T = a.dv.T, K = a.K;
+    const int T = a.m_end, K = a.K;                         // rows past m_end are computed, never stored
 
     // blockIdx -> (split, tile_m, tile_n).  Consecutive blockIdx values land on different XCDs, so
     // the K split is the fastest index on the split path (every XCD keeps one x K-range in its L2)
@@ -118,7 +118,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
     const uint16_t* const xg = sl.x;
     const uint16_t* const Wg = sl.W;
     const int N = sl.N;
-    const int m0 = tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
+    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
 
     // split path: metadata of this workgroup's first shrink work item, fetched before the main loop
     ShrinkPrefetch spf{};
@@ -388,7 +388,7 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
     ShrinkArgs none{};
     none.on = 0;
     auto tiles = [&](int BM, int BN) {
-        a.tiles_m = (a.dv.T + BM - 1) / BM;
+        a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
         a.tiles_n = 0;
         for (int k = 0; k < a.g.n; ++k) {
             a.g.s[k].tile0 = a.tiles_n;
@@ -428,7 +428,7 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
 {
     GemmArgs a = a0;
     auto tiles = [&](int BM, int BN) {
-        a.tiles_m = (a.dv.T + BM - 1) / BM;
+        a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
         a.tiles_n = 0;
         for (int k = 0; k < a.g.n; ++k) {
             a.g.s[k].tile0 = a.tiles_n;

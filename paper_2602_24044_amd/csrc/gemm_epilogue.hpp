@@ -26,7 +26,7 @@ __device__ __forceinline__ void prefetch_windows(TilePrefetch<MB>& pf, const Gem
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_first + mb * 32 + i;
-        const bool ok = m < a.dv.T;
+        const bool ok = m < a.m_end;
         pf.slot[mb] = ok ? a.dv.row_slot[m] : -1;
         pf.rank[mb] = ok ? a.dv.row_rank[m] : 0;
         pf.scale[mb] = ok ? a.dv.row_scale[m] : 0.f;
@@ -44,7 +44,7 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
-    const int T = a.dv.T, N = sl.N;
+    const int T = a.m_end, N = sl.N;
     bool any = false;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) any = any || __ballot(pf.slot[mb] >= 0 && pf.rank[mb] > 0) != 0;
@@ -88,7 +88,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
-    const int T = a.dv.T, N = sl.N;
+    const int T = a.m_end, N = sl.N;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_first + mb * 32 + i;      // grouped row of this lane
@@ -135,7 +135,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
                 for (int nb = 0; nb < NB; ++nb) {
                     const int bn = (n_first + nb * 32) / 32;          // block inside the slice
                     if (bn < nblk_slice) {
-                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)(m / 32)) * a.nblk + sl.blk0 + bn) * 1024;
+                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)((m - a.m_begin) / 32)) * a.nblk + sl.blk0 + bn) * 1024;
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
     const int wm = wave % WGM, wn = wave / WGM;
-    const int T = a.dv.T, K = a.K;
+    const int T = a.m_end, K = a.K;                         // rows past m_end are computed, never stored
 
     // blockIdx -> (split, tile_m, tile_n): consecutive blockIdx values land on different XCDs, so the K split
     // is the fastest index on the split path (every XCD keeps one x K-range in its L2)
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     const uint16_t* const xg = sl.x;
     const uint16_t* const Wg = sl.W;
     const int N = sl.N;
-    const int m0 = tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
+    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
 
     ShrinkPrefetch spf{};
     const int rest_first = extra * a.shrink_q + (int)blockIdx.x;     // this workgroup's first item after its tile
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
 template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
 hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
 {
-    a.tiles_m = (a.dv.T + BM - 1) / BM;
+    a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
     a.tiles_n = 0;
     for (int k = 0; k < a.g.n; ++k) {
         a.g.s[k].tile0 = a.tiles_n;

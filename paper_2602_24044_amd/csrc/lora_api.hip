@@ -720,6 +720,8 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
     ga.nblk = blk;
     ga.part = part;
     ga.Mpad = Mpad;
+    ga.m_begin = 0;
+    ga.m_end = T;
     ga.main_grid = 0;
     ga.shrink_q = 0;
     if (split && dyn_shrink) {
@@ -732,6 +734,35 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         ga.shrink_q = std::max(1, nk / 4);
     }
 
+    // split-K base GEMM (+ shrink items when shrink.on) over the rows of `a`, then reduce + expand
+    auto launch_split = [&](const GemmArgs& a, const ShrinkArgs& shrink, int variant) -> lora_status {
+        {
+            LaunchScope ls(c, s, "gemm_splitk");
+            const char* name = nullptr;
+            // 6, 7: 64-wide K tiles; 8: the 32-wide 256 x 128 kernel (its own variant 0); 1 .. 5: 32-wide variants
+            const hipError_t le = (variant == 6 || variant == 7)
+                                      ? launch_gemm_rows128_splitk(a, shrink, variant - 6, s, &name)
+                                      : launch_gemm_splitk(a, shrink, variant == 8 ? 0 : variant, s, &name);
+            if (HIP_FAIL(le)) return LORA_ERR_HIP;
+            ls.rename(name);
+        }
+        ReduceArgs ra;
+        std::memset(&ra, 0, sizeof ra);
+        ra.dv = dv;
+        ra.g = g;
+        ra.split_k = a.split_k;
+        ra.Mpad = a.Mpad;
+        ra.nblk = blk;
+        ra.part = part;
+        ra.n_kc = n_kc;
+        ra.m_begin = a.m_begin;
+        ra.m_end = a.m_end;
+        const int grid = ((a.m_end - a.m_begin + kPieceRows - 1) / kPieceRows) * (blk / 4);
+        LaunchScope ls(c, s, "reduce_expand");
+        if (HIP_FAIL(launch_reduce_expand(ra, grid, s))) return LORA_ERR_HIP;
+        return LORA_OK;
+    };
+
     if (!split) {
         // ---- shrink, then base GEMM with the expand in its epilogue ----
         if (sa.on) {
@@ -741,41 +772,63 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
             LaunchScope ls(c, s, "shrink");
             if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
         }
-        LaunchScope ls(c, s, "gemm_fused");
-        const char* name = nullptr;
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
-        if (fv == 0) {
+        const bool auto_variant = fv == 0;
+        if (auto_variant) {
             fv = pick_fused_variant(T, n_max, tiles_of);
             // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
             if (T <= kSplitMaxTokens) fv = fv == 4 ? 8 : (fv == 3 ? 9 : 10);
         }
-        const hipError_t le = fv >= 8 ? launch_gemm_rows128_fused(ga, fv - 8, s, &name) : launch_gemm_fused(ga, fv, s, &name);
-        if (HIP_FAIL(le)) return LORA_ERR_HIP;
-        ls.rename(name);
-    } else {
-        // ---- split-K base GEMM + shrink in one launch, then reduce + expand ----
+        // A last round of 256 x 256 tiles that fills less than half the chip costs as much as a full one.  When
+        // the rows behind the full rounds are few enough for the split-K path, the fused launch stops at the
+        // full rounds and those rows take the split-K path (their shrink results are there already), which
+        // spreads them over every CU.
+        int m_split = T;
+        int tail_S = 1;
+        if (auto_variant && fv == 0 && c->cfg.path == LORA_PATH_AUTO && T > kSplitMaxTokens) {
+            const long tiles_m_big = (T + 255) / 256, tiles_big = tiles_of(256, 256), tiles_n_big = tiles_big / tiles_m_big;
+            const long full = tiles_big / 256, rest = tiles_big % 256;
+            if (full >= 1 && rest > 0 && rest <= 128) {
+                const long m_tiles_main = std::min(tiles_m_big - 1, full * 256 / tiles_n_big);
+                const long tail_rows = (long)T - m_tiles_main * 256;
+                if (m_tiles_main >= 1 && tail_rows > 0 && tail_rows <= kSplitMaxTokens) {
+                    long tail_tiles = 0;
+                    for (int k = 0; k < n; ++k) tail_tiles += (c->proj[projs[k]].d_out + 127) / 128;
+                    tail_tiles *= (tail_rows + 255) / 256;
+                    const long tail_pad = (tail_rows + 255) / 256 * 256;
+                    long ts = std::max<long>(1, std::min<long>(8, (256 + tail_tiles / 2) / tail_tiles));
+                    ts = std::min<long>(ts, std::max(1, (K / kBK) / 2));
+                    ts = std::min<long>(ts, (long)(c->L.part_elems / ((size_t)tail_pad * (size_t)n_pad_total)));
+                    if (ts >= 2) {
+                        m_split = (int)(m_tiles_main * 256);
+                        tail_S = (int)ts;
+                    }
+                }
+            }
+        }
         {
-            LaunchScope ls(c, s, "gemm_splitk");
+            LaunchScope ls(c, s, "gemm_fused");
             const char* name = nullptr;
-            // 6, 7: 64-wide K tiles; 8: the 32-wide 256 x 128 kernel (its own variant 0); 1 .. 5: 32-wide variants
-            const hipError_t le = (split_variant == 6 || split_variant == 7)
-                                      ? launch_gemm_rows128_splitk(ga, sa, split_variant - 6, s, &name)
-                                      : launch_gemm_splitk(ga, sa, split_variant == 8 ? 0 : split_variant, s, &name);
+            GemmArgs a = ga;
+            a.m_end = m_split;
+            const hipError_t le = fv >= 8 ? launch_gemm_rows128_fused(a, fv - 8, s, &name) : launch_gemm_fused(a, fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
         }
-        ReduceArgs ra;
-        std::memset(&ra, 0, sizeof ra);
-        ra.dv = dv;
-        ra.g = g;
-        ra.split_k = S;
-        ra.Mpad = Mpad;
-        ra.nblk = blk;
-        ra.part = part;
-        ra.n_kc = n_kc;
-        const int grid = ((T + kPieceRows - 1) / kPieceRows) * (blk / 4);
-        LaunchScope ls(c, s, "reduce_expand");
-        if (HIP_FAIL(launch_reduce_expand(ra, grid, s))) return LORA_ERR_HIP;
+        if (m_split < T) {
+            GemmArgs a = ga;
+            a.m_begin = m_split;
+            a.m_end = T;
+            a.split_k = tail_S;
+            a.Mpad = (T - m_split + 255) / 256 * 256;
+            ShrinkArgs none = sa;
+            none.on = 0;
+            const lora_status st = launch_split(a, none, 6);
+            if (st != LORA_OK) return st;
+        }
+    } else {
+        const lora_status st = launch_split(ga, sa, split_variant);
+        if (st != LORA_OK) return st;
     }
     c->last_fwd_stream = s;
     c->have_fwd = true;

@@ -121,8 +121,9 @@ struct GemmArgs {
     int32_t split_k;     // 1 on the fused path
     int32_t n_kc;
     int32_t nblk;        // 32-column blocks per row block of the packed partial matrix
-    float* part;         // split path: [split_k][Mpad / 32][nblk][1024] fp32
+    float* part;         // split path: [split_k][Mpad / 32][nblk][1024] fp32, row blocks counted from m_begin
     int32_t Mpad;
+    int32_t m_begin, m_end;     // grouped rows served by this launch (m_begin a multiple of 256); tiles start at m_begin
     // split path of the 64-wide-K kernels: workgroups main_grid .. grid - 1 only do shrink items, shrink_q each,
     // while the tile workgroups stream; what is left is shared out over every workgroup (0: every workgroup
     // takes the items blockIdx, blockIdx + grid, ... after its tile)
@@ -138,6 +139,7 @@ struct ReduceArgs {
     int32_t nblk;
     const float* part;
     int32_t n_kc;
+    int32_t m_begin, m_end;     // grouped rows served by this launch (as in the split-K GEMM before it)
 };
 
 // launchers (defined next to their kernels); every launch is asynchronous on `stream`

@@ -21,8 +21,9 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     __shared__ __attribute__((aligned(16))) uint16_t sV[kPieceRows * kVStride];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const int T = a.dv.T;
-    const int n_win = (T + kPieceRows - 1) / kPieceRows;
+    const int T = a.dv.T;                                             // stride of the shrink results
+    const int m_end = a.m_end;
+    const int n_win = (m_end - a.m_begin + kPieceRows - 1) / kPieceRows;   // windows counted from m_begin
     const int win = blockIdx.x % n_win, group = blockIdx.x / n_win;   // group: 128 packed columns
     // the slice (projection of a packed group) these columns belong to: slices start on multiples of 128
     int si = 0;
@@ -30,8 +31,8 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         if (group * 4 >= a.g.s[k].blk0) si = k;
     const Slice sl = pick_slice(a.g, si);
     const int N = sl.N;
-    const int m = win * kPieceRows + i;
-    const bool m_ok = m < T;
+    const int m = a.m_begin + win * kPieceRows + i;
+    const bool m_ok = m < m_end;
     const int n_first = (group * 4 - sl.blk0) * 32 + wave * 32;       // column inside the slice
 
     // partial sums first: the loads are independent of the LDS staging below
@@ -68,9 +69,9 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     // stage the window's scaled shrink results: thread -> (row, 8 ranks)
     {
         const int row = tid >> 3, seg = tid & 7;
-        const int mr = win * kPieceRows + row;
+        const int mr = a.m_begin + win * kPieceRows + row;
         u32x4 packed = {0u, 0u, 0u, 0u};
-        if (mr < T && seg * 8 < a.dv.max_rank) {
+        if (mr < m_end && seg * 8 < a.dv.max_rank) {
             // rank, scale and the partial results are fetched together; what lies past the row's rank
             // is discarded by the select below, never used in arithmetic that is kept
             const int r = a.dv.row_rank[mr];

@@ -62,6 +62,34 @@ def test_qwen_shapes_prefill_runs_reduced():
     run_and_check(w, path=B.LORA_PATH_AUTO, packed=True)
 
 
+@pytest.mark.parametrize("mode", [wl.BUCKET_SORTED, wl.BUCKET_RUNS])
+def test_poorly_filled_last_round_takes_the_split_path(mode):
+    # 18 x 16 tiles of 256 x 256: one full round of 256 and 32 more.  The fused launch stops after 16 row tiles and
+    # the last 356 rows go through split-K + reduce; both parts must agree with the oracle.
+    rng = np.random.default_rng(11)
+    T = 17 * 256 + 100
+    ids = rng.integers(-1, 6, size=T).astype(np.int32)
+    if mode == wl.BUCKET_RUNS:
+        ids = np.sort(ids)
+    w = wl.custom("tail_rows", 11, [(512, 4096)], ["p"], 8, 32, mode, ids, {i: [8, 16, 32][i % 3] for i in range(6)})
+    sess = Session(w)
+    try:
+        sess.load(w.resident)
+        sess.bucket()
+        assert check_segments(sess, w) == 0
+        out = sess.forward(0)
+        torch.cuda.synchronize()
+        launches = B.lora_last_launches(sess.ctx)
+        announce(f"tail rows mode={mode} launches={launches}")
+        assert "gemm_fused_256x256_w8" in launches and "reduce_expand" in launches, launches
+        y_ref = oracle.project(w.x[0], w.W[0], w.token_ids, oracle.adapters_of(w, 0))
+        e = rel_err(bf16_tensor_to_bits(out), y_ref)
+        announce(f"  rel_err={e:.3e}")
+        assert e <= TOL
+    finally:
+        sess.close()
+
+
 @pytest.mark.parametrize("split_k", [1, 2, 3, 16])
 def test_split_k_values(split_k):
     run_and_check(wl.config2(shrink=8, n_tokens=130), path=B.LORA_PATH_SPLITK, split_k=split_k)
