@@ -220,83 +220,6 @@ __device__ inline void shrink_block_items(const ShrinkArgs& a, int first_item, i
     }
 }
 
-// ---------------------------------------------------------------------------------------------------
-// LoRA expand for one 32-row window of grouped rows (paper Sec. 2.2: the second low-rank matrix maps
-// the adapter's activations back to the layer output, where they are added to the backbone result).
-// acc[nb] is a 32x32 accumulator block in "W-first" orientation: lane (i, h) holds grouped row
-// m = window + i (the block's column) and output columns n_first + 32 nb + 8 g + 4 h + e in register
-// 4 g + e.  For every distinct slot among the window's rows, that slot's B rows and the rows' scaled
-// shrink results (rounded to bf16) are fed as extra K steps of 16.
-//   VS: functor (k, on, scale) -> bf16x8 with the lane's scaled v[m][k .. k+7] (zeros when !on).
-// my_rank / my_scale are the per-row copies of the slot's rank and scale.
-// ---------------------------------------------------------------------------------------------------
-// The B fragments of the next distinct slot are fetched while the current slot's
-// MFMAs run (a 32-row decode window holds many slots, and each slot's fragments are a dependent global
-// load: without the look-ahead the loop pays one memory latency per slot).  The v fragments must be cheap
-// to produce (LDS), they are asked for inside the loop.
-template <int NB, typename VS>
-__device__ inline void expand_window_pipelined(f32x16 (&acc)[NB], int my_slot, int my_rank, float my_scale, int n_first,
-                                               int N, const DeviceView& dv, size_t b_off, VS&& vfrag)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int i = lane & 31, h = lane >> 5;
-    unsigned long long todo = __ballot(my_slot >= 0 && my_rank > 0);
-    struct Slot {
-        int s, r;
-        float sc;
-        bool valid;
-    };
-    auto next_slot = [&]() {
-        Slot q{-1, 0, 0.f, false};
-        if (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            q.s = __shfl(my_slot, leader, kWave);
-            q.r = __shfl(my_rank, leader, kWave);
-            q.sc = __shfl(my_scale, leader, kWave);
-            q.valid = true;
-            todo &= ~__ballot(my_slot == q.s);
-        }
-        return q;
-    };
-    auto fetch = [&](const Slot& q, u32x4 (&fb)[NB][4]) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int n = n_first + nb * 32 + i;
-            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int k = ks * 16 + h * 8;
-                fb[nb][ks] = u32x4{0u, 0u, 0u, 0u};
-                if (q.valid && n < N && k < q.r) fb[nb][ks] = load16(Bs + k);
-            }
-        }
-    };
-    auto apply = [&](const Slot& q, const u32x4 (&fb)[NB][4]) {
-        const bool mine = (my_slot == q.s);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks * 16 < q.r) {
-                const int k = ks * 16 + h * 8;
-                const bf16x8 vf = vfrag(k, mine && k < q.r, q.sc);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(as_bf16x8(fb[nb][ks]), vf, acc[nb]);
-            }
-        }
-    };
-    u32x4 f0[NB][4], f1[NB][4];
-    Slot q0 = next_slot();
-    fetch(q0, f0);
-    while (q0.valid) {
-        Slot q1 = next_slot();
-        fetch(q1, f1);
-        apply(q0, f0);
-        if (!q1.valid) break;
-        q0 = next_slot();
-        fetch(q0, f0);
-        apply(q1, f1);
-    }
-}
-
 // This lane's share q (0 .. 3) of the scaled shrink results of one 32-row window, packed as bf16:
 // (row, seg) = ((lane + 64 q) / 8, (lane + 64 q) % 8) -> bf16(scale_row * sum_c vpart[c][row][8 seg .. 8 seg + 7]),
 // zero beyond the row's rank.
@@ -336,15 +259,6 @@ __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 {
     const int idx = (threadIdx.x & (kWave - 1)) + 64 * q;
     *reinterpret_cast<u32x4*>(sV + (idx >> 3) * kVStageStride + (idx & 7) * 8) = packed;
-}
-
-// Stages the scaled shrink results of one 32-row window as bf16 in LDS (sV private to the calling
-// wavefront).  Returns after the wave's LDS writes have completed, so any lane may read.
-__device__ inline void stage_window_v(uint16_t* sV, const float* vpart, int n_kc, int win0, const DeviceView& dv)
-{
-#pragma unroll
-    for (int q = 0; q < 4; ++q) park_v_share(sV, q, window_v_share(q, vpart, n_kc, win0, dv));
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
 // ---------------------------------------------------------------------------------------------------

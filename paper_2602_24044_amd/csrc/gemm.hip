@@ -359,7 +359,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
 
     // ---------------- epilogue ----------------
     // every copy has landed and been read once all waves have left the main loop: the ring is free
-    static_assert(!FUSED || NS * STAGE * 2 >= NWV * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    static_assert(!FUSED || NS * STAGE * 2 >= NCW * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
     static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
     if (!producer)

@@ -2,26 +2,89 @@
 //   fused path: LoRA expand on the accumulators (paper Sec. 2.2: the adapter's activations are added to the
 //               backbone layer's output), one bf16 rounding, rows scattered back to token order;
 //   split path: fp32 partial tile for the reduce + expand kernel.
+//
+// Accumulator layout ("W-first" orientation): acc[mb][nb] is a 32x32 block, lane (i, h) holds grouped row
+// m_first + 32 mb + i and output columns n_first + 32 nb + 8 g + 4 h + e in register 4 g + e.
+//
+// The fused path works on the wave's windows (32 rows each) two at a time, in the wave's own piece of the LDS
+// ring (free once every wave has left the main loop; the caller has synchronised):
+//   1. the windows' scaled shrink results are parked there as bf16 and the expand runs as one pipelined pass
+//      over the (window, slot) pairs;
+//   2. the finished rows are rounded to bf16 and turned through the same piece of LDS, so that they leave as
+//      16-byte stores in which consecutive lanes cover a whole run of an output row.  Written straight from the
+//      accumulator layout, a store instruction touches 32 rows with 16 bytes each, and the output of a
+//      256 x 256 tile reaches L2 as 8192 sixteen-byte pieces.
 #pragma once
 
 #include "device_common.hpp"
 
 namespace lora {
 
+constexpr int kEpiWindows = 2;                    // windows per pass
+// bytes of the ring one wave uses in the fused epilogue: shrink results of two windows, or two windows of
+// NB * 32 bf16 output columns
+template <int NB>
+constexpr int epilogue_bytes_per_wave()
+{
+    constexpr int v = kEpiWindows * kPieceRows * kVStageStride * 2, o = kEpiWindows * kPieceRows * NB * 64;
+    return v > o ? v : o;
+}
+
+// Rounds WB windows of accumulators to bf16 and stores them to out rows perm[m], through LDS (sT: this wave's
+// piece, WB * 32 rows of NB * 64 bytes).  Chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & (CH - 1)):
+// the 8-byte writes of a half wave then collide two ways at most and the 16-byte reads are contiguous.
+template <int WB, int NB>
+__device__ __forceinline__ void store_windows(const f32x16 (&acc)[WB][NB], const GemmArgs& a, const Slice& sl, int m_first,
+                                              int n_first, uint8_t* sT)
+{
+    constexpr int CH = NB * 4, ROWB = NB * 64;     // 16-byte chunks and bytes per LDS row
+    constexpr int RPI = kWave / CH;                // rows one 16-byte-per-lane instruction covers
+    constexpr int ITER = WB * 32 / RPI;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31, h = lane >> 5;
+    const int T = a.m_end, N = sl.N;
+    // tokens of the rows this lane will store (fetched before the LDS round trip)
+    int tok[ITER];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int m = m_first + it * RPI + lane / CH;
+        tok[it] = m < T ? a.dv.perm[m] : -1;
+    }
+#pragma unroll
+    for (int w = 0; w < WB; ++w)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[w][nb][g * 4 + e];
+                const int pos = (nb * 4 + g) ^ ((i >> 1) & (CH - 1));
+                *reinterpret_cast<u32x2*>(sT + (w * 32 + i) * ROWB + pos * 16 + h * 8) = __builtin_bit_cast(u32x2, o);
+            }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int row = it * RPI + lane / CH, pos = lane % CH;
+        const int n = n_first + (pos ^ ((row >> 1) & (CH - 1))) * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(sT + row * ROWB + pos * 16);
+        if (tok[it] >= 0 && n < N) *reinterpret_cast<u32x4*>(sl.out + (size_t)tok[it] * N + n) = v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");            // reads done before the piece is reused
+}
+
 // Fused path, wave tiles of at most two 32-row windows: what the epilogue needs from memory besides the B rows
-// is fetched before the main loop and waits in registers, so that the tail of the kernel - which no other
-// workgroup overlaps when the launch is a single round - holds one memory latency per (window, slot) pair
-// instead of three per window.
+// is fetched before the main loop and waits in registers.
 template <int MB>
 struct TilePrefetch {
     int slot[MB], rank[MB];          // this lane's row of each window
-    float scale[MB];
     u32x4 v[MB][4];                  // this lane's shares of the windows' scaled shrink results (packed bf16)
 };
 
 template <int MB>
 __device__ __forceinline__ void prefetch_windows(TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int m_first)
 {
+    static_assert(MB <= kEpiWindows, "prefetch covers one pass");
     const int i = threadIdx.x & 31;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -29,59 +92,35 @@ __device__ __forceinline__ void prefetch_windows(TilePrefetch<MB>& pf, const Gem
         const bool ok = m < a.m_end;
         pf.slot[mb] = ok ? a.dv.row_slot[m] : -1;
         pf.rank[mb] = ok ? a.dv.row_rank[m] : 0;
-        pf.scale[mb] = ok ? a.dv.row_scale[m] : 0.f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) pf.v[mb][q] = window_v_share(q, sl.vpart, a.n_kc, m_first + mb * 32, a.dv);
     }
 }
 
-// Epilogue of the fused path from prefetched window data.  ring: LDS free again (the caller has synchronised);
-// this wave parks its MB windows at ring + wave * MB * kPieceRows * kVStageStride.
+// Epilogue of the fused path from prefetched window data.  ring: LDS free again (the caller has synchronised).
 template <int MB, int NB>
 __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], const GemmArgs& a, const Slice& sl,
                                                        int m_first, int n_first, int wave, uint16_t* ring,
                                                        const TilePrefetch<MB>& pf)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int i = lane & 31, h = lane >> 5;
-    const int T = a.m_end, N = sl.N;
+    uint8_t* mine = reinterpret_cast<uint8_t*>(ring) + wave * epilogue_bytes_per_wave<NB>();
     bool any = false;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) any = any || __ballot(pf.slot[mb] >= 0 && pf.rank[mb] > 0) != 0;
     if (any) {                                                    // uniform over the wave
-        uint16_t* sV = ring + wave * (MB * kPieceRows * kVStageStride);
+        uint16_t* sV = reinterpret_cast<uint16_t*>(mine);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, N, a.dv, sl.b_off, sV);
+        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_off, sV);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int m = m_first + mb * 32 + i;
-        if (m < T) {
-            uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n_first + nb * 32 + g * 8 + h * 4;
-                    if (n < N) {
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[mb][nb][g * 4 + e];
-                        *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
-                    }
-                }
-        }
-    }
+    store_windows<MB, NB>(acc, a, sl, m_first, n_first, mine);
 }
 
-// acc[mb][nb]: 32x32 blocks in "W-first" orientation (lane (i, h) holds grouped row m_first + 32 mb + i and
-// output columns n_first + 32 nb + 8 g + 4 h + e in register 4 g + e); n_first is a column inside slice sl.
-// ring: LDS no longer used by the main loop (the caller has synchronised); the fused path parks the scaled
-// shrink results of one 32-row window at a time in this wave's piece of it.
+// ring: LDS no longer used by the main loop (the caller has synchronised).
 template <int MB, int NB, bool FUSED>
 __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArgs& a, const Slice& sl, int m_first,
                                             int n_first, int split, int wave, uint16_t* ring)
@@ -89,61 +128,71 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
     const int T = a.m_end, N = sl.N;
+    if (FUSED) {
+        // Windows two at a time: their rows' metadata and scaled shrink results are fetched together (one memory
+        // latency each instead of one per window), then one pipelined pass over the (window, slot) pairs.
+        constexpr int WB = MB >= kEpiWindows ? kEpiWindows : 1;
+        static_assert(MB % WB == 0, "windows per wave");
+        int slot[MB], rank[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int m = m_first + mb * 32 + i;
+            const bool ok = m < T;
+            slot[mb] = ok ? a.dv.row_slot[m] : -1;
+            rank[mb] = ok ? a.dv.row_rank[m] : 0;
+        }
+        uint8_t* mine = reinterpret_cast<uint8_t*>(ring) + wave * epilogue_bytes_per_wave<NB>();
+        uint16_t* sV = reinterpret_cast<uint16_t*>(mine);
+#pragma unroll
+        for (int p = 0; p < MB / WB; ++p) {
+            f32x16(&pair)[WB][NB] = *reinterpret_cast<f32x16(*)[WB][NB]>(&acc[p * WB]);
+            bool any = false;
+#pragma unroll
+            for (int w = 0; w < WB; ++w) any = any || __ballot(slot[p * WB + w] >= 0 && rank[p * WB + w] > 0) != 0;
+            if (any) {                                            // uniform over the wave
+                u32x4 share[WB][4];
+#pragma unroll
+                for (int w = 0; w < WB; ++w)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        share[w][q] = window_v_share(q, sl.vpart, a.n_kc, m_first + (p * WB + w) * 32, a.dv);
+#pragma unroll
+                for (int w = 0; w < WB; ++w)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) park_v_share(sV + w * kPieceRows * kVStageStride, q, share[w][q]);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                int ps[WB], pr[WB];
+#pragma unroll
+                for (int w = 0; w < WB; ++w) {
+                    ps[w] = slot[p * WB + w];
+                    pr[w] = rank[p * WB + w];
+                }
+                expand_windows<WB, NB, (MB > 2 ? 2 : 3)>(pair, ps, pr, n_first, N, a.dv, sl.b_off, sV);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the piece is reused
+            }
+            store_windows<WB, NB>(pair, a, sl, m_first + p * WB * 32, n_first, mine);
+        }
+        return;
+    }
+    // split path: fp32 partial tiles are kept block by block in accumulator order: block (m / 32, n / 32) of
+    // split s is 1024 consecutive floats, lane (i, h) owning floats 256 g + 8 i + 4 h .. + 3, so every store (and
+    // the matching load in the reduce kernel) covers 1 KB contiguously
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_first + mb * 32 + i;      // grouped row of this lane
-        const bool m_ok = m < T;
-
-        if (FUSED) {
-            const int my_slot = m_ok ? a.dv.row_slot[m] : -1;
-            const int my_rank = m_ok ? a.dv.row_rank[m] : 0;
-            const float my_scale = m_ok ? a.dv.row_scale[m] : 0.f;
-            if (__ballot(my_slot >= 0 && my_rank > 0)) {      // uniform over the wave
-                uint16_t* sV = ring + wave * (kPieceRows * kVStageStride);
-                stage_window_v(sV, sl.vpart, a.n_kc, m_first + mb * 32, a.dv);
-                auto vfrag = [&](int k, bool on, float) -> bf16x8 {
-                    u32x4 v = {0u, 0u, 0u, 0u};
-                    if (on) v = *reinterpret_cast<const u32x4*>(sV + i * kVStageStride + k);
-                    return as_bf16x8(v);
-                };
-                expand_window_pipelined<NB>(acc[mb], my_slot, my_rank, my_scale, n_first, N, a.dv, sl.b_off, vfrag);
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next window is staged
-            }
-        }
-
-        if (m_ok) {
-            if (FUSED) {
-                uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
+        if (m >= T) continue;
+        const int nblk_slice = (N + 31) / 32;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb) {
+            const int bn = (n_first + nb * 32) / 32;          // block inside the slice
+            if (bn < nblk_slice) {
+                float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)((m - a.m_begin) / 32)) * a.nblk + sl.blk0 + bn) * 1024;
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = n_first + nb * 32 + g * 8 + h * 4;
-                        if (n < N) {
-                            bf16x4 o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[mb][nb][g * 4 + e];
-                            *reinterpret_cast<u32x2*>(orow + n) = __builtin_bit_cast(u32x2, o);
-                        }
-                    }
-            } else {
-                // fp32 partial tiles are kept block by block in accumulator order: block (m / 32, n / 32)
-                // of split s is 1024 consecutive floats, lane (i, h) owning floats 256 g + 8 i + 4 h .. + 3,
-                // so every store (and the matching load in the reduce kernel) covers 1 KB contiguously
-                const int nblk_slice = (N + 31) / 32;
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int bn = (n_first + nb * 32) / 32;          // block inside the slice
-                    if (bn < nblk_slice) {
-                        float* blk = a.part + (((size_t)split * (a.Mpad / 32) + (size_t)((m - a.m_begin) / 32)) * a.nblk + sl.blk0 + bn) * 1024;
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
-                                       acc[mb][nb][g * 4 + 3]};
-                            // read once by another kernel: keep the tiles from lingering dirty in L2
-                            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4));
-                        }
-                    }
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 o = {acc[mb][nb][g * 4 + 0], acc[mb][nb][g * 4 + 1], acc[mb][nb][g * 4 + 2],
+                               acc[mb][nb][g * 4 + 3]};
+                    // read once by another kernel: keep the tiles from lingering dirty in L2
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(blk + g * 256 + i * 8 + h * 4));
                 }
             }
         }

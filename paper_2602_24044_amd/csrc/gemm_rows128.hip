@@ -209,7 +209,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     }
 
     // ---------------- epilogue ----------------
-    static_assert(!FUSED || NS * STAGE_B >= NWV * (PRE ? MB : 1) * kPieceRows * kVStageStride * 2, "ring too small for v staging");
+    static_assert(!FUSED || NS * STAGE_B >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
     static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
     if constexpr (PRE)
