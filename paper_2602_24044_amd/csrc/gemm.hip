@@ -61,17 +61,12 @@ __device__ inline void wait_copies_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// PW > 0 adds PW producer waves that do nothing but issue the tile copies; the WGM x WGN compute waves
-// then never sit behind a copy instruction that the memory pipeline has not accepted yet.  PW = -1 (fused
-// path only) lets every wave copy, as on the split path: right for small batches, where the copy rate and
-// not the MFMA issue bounds the loop.
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PWA = 0>
-__global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
+// ALLCOPY (fused path only): every wave copies, as on the split path: right for small batches, where the copy
+// rate and not the MFMA issue bounds the loop.
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, bool ALLCOPY = false>
+__global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, ShrinkArgs sa)
 {
-    constexpr int PW = PWA > 0 ? PWA : 0;
-    constexpr int NCW = WGM * WGN;                          // compute waves
-    constexpr int NWV = NCW + PW;                           // all waves
-    constexpr int NT = NWV * kWave;
+    constexpr int NWV = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
     constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
     constexpr int STAGE = (BM + BN) * kTK;                  // elements per stage
@@ -79,7 +74,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
     // copy instruction by a full memory pipeline cannot issue its MFMAs; with two waves per SIMD the other
     // one keeps the matrix core busy meanwhile (measured: a few percent on the compute-bound shapes, none
     // on the split path, where every wave copies).
-    constexpr int CW = PW > 0 ? PW : ((FUSED && NWV > 4 && PWA == 0) ? 4 : NWV);
+    constexpr int CW = (FUSED && NWV > 4 && !ALLCOPY) ? 4 : NWV;
     constexpr int XQ = BM / 16 / CW, WQ = BN / 16 / CW;     // copy instructions per copying wave and tile
     constexpr int QPT = XQ + WQ;
     static_assert(BM % (16 * CW) == 0 && BN % (16 * CW) == 0, "tile/waves");
@@ -92,8 +87,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, h = lane >> 5;
-    const bool producer = PW > 0 && wave >= NCW;
-    const int cwave = PW > 0 ? wave - NCW : wave;           // index among the copying waves
+    const int cwave = wave;                                 // index among the copying waves
     const int wm = wave % WGM, wn = (wave / WGM) % WGN;
     const int T = a.m_end, K = a.K;                         // rows past m_end are computed, never stored
 
@@ -177,7 +171,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
     const uint32_t cp_w = ring_addr + BM * kTK * 2 + cwave * WQ * 1024;
     const int rd_lane[2] = {i * kTK + ((0 * 2 + h) ^ sw) * 8, i * kTK + ((1 * 2 + h) ^ sw) * 8};
 
-    const bool copier = PW > 0 ? producer : wave < CW;
+    const bool copier = wave < CW;
     auto copy_one = [&](int stage, int q, uint32_t k0) {      // q: compile-time constant at every call site
         if (!copier) return;
         const uint32_t so = (uint32_t)stage * (STAGE * 2);
@@ -264,47 +258,7 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
         }
     };
 
-    if constexpr (PW > 0) {
-        // Specialised waves.  Tile t lives in stage t % NS; barrier b (b = 0 .. nk) publishes tile b and
-        // frees the stage of tile b - 2 ... the producers wait for their own copies of tile b, join the
-        // barrier, then refill the stage of tile b - 1 with tile b + NS - 2.
-        if (producer) {
-            static_for<NS - 1>([&](auto d) {
-                if (d.value < nk) {
-                    static_for<QPT>([&](auto q) { copy_one(d.value, q.value, (uint32_t)d.value * kTK); });
-                }
-            });
-            if (nk > 0) {
-                int young = nk - 1;
-                if (young > NS - 2) young = NS - 2;
-                wait_barrier(young);                                  // barrier 0: tile 0 is complete
-            }
-            int fre = NS - 1;                                          // stage of tile j - 1
-            for (int j = 0; j < nk; ++j) {
-                int young = nk - 2 - j;
-                if (young < 0) young = 0;
-                if (young > NS - 3) young = NS - 3;
-                wait_barrier(young);                                  // barrier j + 1: tile j + 1 is complete
-                if (j + NS - 1 < nk) {
-                    const uint32_t k0 = (uint32_t)(j + NS - 1) * kTK;
-                    static_for<QPT>([&](auto q) { copy_one(fre, q.value, k0); });
-                }
-                fre = (fre + 1 == NS) ? 0 : fre + 1;
-            }
-        } else {
-            if (nk > 0) {
-                wait_copies_then_barrier<0>();                        // barrier 0
-                static_for<NR>([&](auto r) { read_one(I0{}, 0, 0, r.value); });
-            }
-            int cur = 0, nxt = 1 % NS;
-            for (int j = 0; j < nk; ++j) {
-                // compute waves issue no copies: iteration<false> with nothing of their own to wait for
-                iteration(std::false_type{}, nk, cur, nxt, 0, 0);
-                cur = nxt;
-                nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
-            }
-        }
-    } else {
+    {
         // Prologue: tiles 0 .. NS - 3 in full and the first half of tile NS - 2 (its second half follows in
         // K step 0 of iteration 0, exactly as in the steady state).
         const bool steady = nk >= NS;              // at least one steady-state iteration exists
@@ -359,22 +313,21 @@ __global__ __launch_bounds__((WGM * WGN + (PWA > 0 ? PWA : 0)) * kWave) void gem
 
     // ---------------- epilogue ----------------
     // every copy has landed and been read once all waves have left the main loop: the ring is free
-    static_assert(!FUSED || NS * STAGE * 2 >= NCW * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
+    static_assert(!FUSED || NS * STAGE * 2 >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
     static_assert(FUSED || NS * STAGE * 2 >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
-    if (!producer)
-        finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, ring);
+    finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, ring);
     if (!FUSED && sa.on) {
         __syncthreads();
         shrink_block_items<NWV>(sa, blockIdx.x, gridDim.x, spf.n_items, reinterpret_cast<float*>(ring), spf);
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, int PW = 0>
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, bool ALLCOPY = false>
 hipError_t launch_one(const GemmArgs& a, const ShrinkArgs& sa, hipStream_t stream)
 {
-    constexpr int NT = (WGM * WGN + (PW > 0 ? PW : 0)) * kWave;
-    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS, PW>;
+    constexpr int NT = WGM * WGN * kWave;
+    auto kfn = gemm_kernel<BM, BN, WGM, WGN, FUSED, NS, ALLCOPY>;
     const int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(NT), 0, stream, a, sa);
     return hipGetLastError();
@@ -415,7 +368,7 @@ hipError_t launch_gemm_fused(const GemmArgs& a0, int variant, hipStream_t stream
         case 5:
             tiles(256, 128);
             *name = "gemm_fused_256x128_w8_allcopy";
-            return launch_one<256, 128, 4, 2, true, 5, -1>(a, none, stream);
+            return launch_one<256, 128, 4, 2, true, 5, true>(a, none, stream);
         default:
             tiles(256, 256);
             *name = "gemm_fused_256x256_w8";
@@ -452,10 +405,6 @@ hipError_t launch_gemm_splitk(const GemmArgs& a0, const ShrinkArgs& sa, int vari
             tiles(128, 128);
             *name = "gemm_splitk_shrink_128x128_w4_s8";
             return launch_one<128, 128, 2, 2, false, 8>(a, sa, stream);
-        case 5:
-            tiles(256, 128);
-            *name = "gemm_splitk_shrink_256x128_w8p4";
-            return launch_one<256, 128, 4, 2, false, 5, 4>(a, sa, stream);
         default:
             tiles(256, 128);
             *name = "gemm_splitk_shrink_256x128_w8";
