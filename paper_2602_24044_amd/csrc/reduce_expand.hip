@@ -35,7 +35,18 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     const bool m_ok = m < m_end;
     const int n_first = (group * 4 - sl.blk0) * 32 + wave * 32;       // column inside the slice
 
-    // partial sums first: the loads are independent of the LDS staging below
+    // The kernel is a chain of memory round trips; everything whose address is known at the start is requested
+    // at the start, oldest first what the next dependent load needs: this lane's row (slot, rank, token), the
+    // rank and scale of the row this thread stages, then the partial tiles.
+    const int my_slot[1] = {m_ok ? a.dv.row_slot[m] : -1};
+    const int my_rank[1] = {m_ok ? a.dv.row_rank[m] : 0};
+    const int my_tok = m_ok ? a.dv.perm[m] : 0;
+    const int st_row = tid >> 3, st_seg = tid & 7;
+    const int st_m = a.m_begin + win * kPieceRows + st_row;
+    const bool st_on = st_m < m_end && st_seg * 8 < a.dv.max_rank;
+    const int st_rank = st_on ? a.dv.row_rank[st_m] : 0;
+    const float st_scale = st_on ? a.dv.row_scale[st_m] : 0.f;
+
     f32x16 acc[1];
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
@@ -44,67 +55,73 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     // coalesced; four splits (16 independent 16-byte loads per lane) are kept in flight
     const int nblk = a.nblk;
     const int bn = group * 4 + wave;                                  // block in the packed partial matrix
-    if (n_first < N) {
-        for (int s0 = 0; s0 < a.split_k; s0 += 4) {
-            f32x4 p[4][4];
+    const bool cols_on = n_first < N;
+    f32x4 p[4][4];
+    auto load_splits = [&](int s0) {
 #pragma unroll
-            for (int ds = 0; ds < 4; ++ds) {
-                const int s = (s0 + ds < a.split_k) ? s0 + ds : s0;
-                const float* blk = a.part + (((size_t)s * (a.Mpad / 32) + (size_t)win) * nblk + bn) * 1024;
+        for (int ds = 0; ds < 4; ++ds) {
+            const int sp = (s0 + ds < a.split_k) ? s0 + ds : s0;
+            const float* blk = a.part + (((size_t)sp * (a.Mpad / 32) + (size_t)win) * nblk + bn) * 1024;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) p[ds][g] = *reinterpret_cast<const f32x4*>(blk + g * 256 + i * 8 + h * 4);
+            for (int g = 0; g < 4; ++g) p[ds][g] = *reinterpret_cast<const f32x4*>(blk + g * 256 + i * 8 + h * 4);
+        }
+    };
+    auto add_splits = [&](int s0) {
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds) {
+            if (s0 + ds < a.split_k) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[0][g * 4 + e] += p[ds][g][e];
             }
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds) {
-                if (s0 + ds < a.split_k) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[0][g * 4 + e] += p[ds][g][e];
-                }
-            }
+        }
+    };
+    if (cols_on) load_splits(0);
+
+    // the window's shrink results, thread -> (row, 8 ranks): requested behind the first partial tiles (their
+    // address needs only the row's rank, which was requested before those)
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    const bool st_live = st_on && st_seg * 8 < st_rank;
+    if (st_live) {
+#pragma unroll 4
+        for (int c = 0; c < a.n_kc; ++c) {
+            const float* vp = sl.vpart + ((size_t)c * T + st_m) * a.dv.max_rank + st_seg * 8;
+            lo += *reinterpret_cast<const f32x4*>(vp);
+            hi += *reinterpret_cast<const f32x4*>(vp + 4);
         }
     }
 
-    // stage the window's scaled shrink results: thread -> (row, 8 ranks)
-    {
-        const int row = tid >> 3, seg = tid & 7;
-        const int mr = a.m_begin + win * kPieceRows + row;
-        u32x4 packed = {0u, 0u, 0u, 0u};
-        if (mr < m_end && seg * 8 < a.dv.max_rank) {
-            // rank, scale and the partial results are fetched together; what lies past the row's rank
-            // is discarded by the select below, never used in arithmetic that is kept
-            const int r = a.dv.row_rank[mr];
-            const float sc = a.dv.row_scale[mr];
-            f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-            for (int c = 0; c < a.n_kc; ++c) {
-                const float* vp = sl.vpart + ((size_t)c * T + mr) * a.dv.max_rank + seg * 8;
-                lo += *reinterpret_cast<const f32x4*>(vp);
-                hi += *reinterpret_cast<const f32x4*>(vp + 4);
-            }
-            if (seg * 8 < r) {
-                bf16x8 vb;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    vb[e] = (__bf16)(lo[e] * sc);
-                    vb[4 + e] = (__bf16)(hi[e] * sc);
-                }
-                packed = __builtin_bit_cast(u32x4, vb);
-            }
+    if (cols_on) {
+        add_splits(0);
+        for (int s0 = 4; s0 < a.split_k; s0 += 4) {
+            load_splits(s0);
+            add_splits(s0);
         }
-        *reinterpret_cast<u32x4*>(sV + row * kVStride + seg * 8) = packed;
+    }
+
+    // stage the scaled shrink results as bf16
+    {
+        u32x4 packed = {0u, 0u, 0u, 0u};
+        if (st_live) {
+            bf16x8 vb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vb[e] = (__bf16)(lo[e] * st_scale);
+                vb[4 + e] = (__bf16)(hi[e] * st_scale);
+            }
+            packed = __builtin_bit_cast(u32x4, vb);
+        }
+        *reinterpret_cast<u32x4*>(sV + st_row * kVStride + st_seg * 8) = packed;
     }
     __syncthreads();
 
-    const int my_slot[1] = {m_ok ? a.dv.row_slot[m] : -1};
-    const int my_rank[1] = {m_ok ? a.dv.row_rank[m] : 0};
     f32x16 accw[1][1] = {{acc[0]}};
     expand_windows<1, 1, 6>(accw, my_slot, my_rank, n_first, N, a.dv, sl.b_off, sV);
     acc[0] = accw[0][0];
 
     if (m_ok) {
-        uint16_t* orow = sl.out + (size_t)a.dv.perm[m] * N;
+        uint16_t* orow = sl.out + (size_t)my_tok * N;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int n = n_first + g * 8 + h * 4;
