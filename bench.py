@@ -139,7 +139,7 @@ def main():
                     help="run plain device copy kernels of known size and exit (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; the path shards by adapter with no exchange, "
+        print("bench.py: the library runs on one GPU; the path shards by adapter with no exchange, "
               "so --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
