@@ -35,7 +35,9 @@ def _bucket_only_workload(T, n_slots, seed, mode, frac_none=0.1, zipf=False):
 @pytest.mark.parametrize("mode", [wl.BUCKET_SORTED, wl.BUCKET_RUNS])
 @pytest.mark.parametrize("T,n_slots,seed", [(1, 1, 0), (63, 3, 1), (64, 4, 2), (65, 33, 3), (256, 32, 4), (512, 384, 5),
                                             (1023, 100, 6), (1024, 17, 7), (1025, 1000, 8), (2432, 128, 9),
-                                            (26000, 64, 10), (5000, 4095, 11)])
+                                            (26000, 64, 10), (5000, 4095, 11),
+                                            # around the limit up to which the kernel keeps its intermediates on chip
+                                            (4095, 300, 12), (4096, 4095, 13), (4097, 37, 14)])
 def test_segment_map_bit_exact(mode, T, n_slots, seed):
     w = _bucket_only_workload(T, n_slots, seed, mode, zipf=(seed % 2 == 0))
     announce(f"bucket T={T} n_slots={n_slots} mode={mode} seed={seed}")
