@@ -632,8 +632,9 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         // small batches walk K in 64-wide tiles (whole cache lines per row segment).  Narrow launches (k, v
         // alone) fill the chip better with square 128 x 128 tiles, and so does a 4096-wide projection over a
         // short K at up to 256 tokens (half the K splits, half the partial tiles)
+        // and up to 128 tokens a 256-row tile would copy and multiply rows that do not exist
         if (split_variant == 0)
-            split_variant = (n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
+            split_variant = (T <= 128 || n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
         const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
         const long tiles = tiles_of(bm, bn);
         // The 64-wide-K kernels give a quarter of the CUs workgroups that only shrink, from the start (a shrink
@@ -777,7 +778,8 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         if (auto_variant) {
             fv = pick_fused_variant(T, n_max, tiles_of);
             // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
-            if (T <= kSplitMaxTokens) fv = fv == 4 ? 8 : (fv == 3 ? 9 : 10);
+            // (128-row tiles up to 128 tokens)
+            if (T <= kSplitMaxTokens) fv = T <= 128 ? 9 : (fv == 4 ? 8 : (fv == 3 ? 9 : 10));
         }
         // A last round of 256 x 256 tiles that fills less than half the chip costs as much as a full one.  When
         // the rows behind the full rounds are few enough for the split-K path, the fused launch stops at the
