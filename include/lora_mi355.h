@@ -198,6 +198,30 @@ enum {
     LORA_TUNE_FUSED_VARIANT = 0, /* tile shape / wave layout of the fused GEMM */
     LORA_TUNE_SPLIT_VARIANT = 1  /* tile shape / wave layout of the split-K GEMM */
 };
+/* Values of LORA_TUNE_FUSED_VARIANT: tile (rows x columns x K tile), wavefronts per workgroup. */
+enum {
+    LORA_FUSED_AUTO = 0,
+    LORA_FUSED_256x256x32_W4 = 1,
+    LORA_FUSED_256x256x32_W4_3STAGES = 2,
+    LORA_FUSED_128x128x32_W4 = 3,
+    LORA_FUSED_256x128x32_W8 = 4,
+    LORA_FUSED_256x128x32_W8_ALLCOPY = 5, /* every wavefront issues tile copies */
+    LORA_FUSED_256x128x64_W8 = 8,         /* 64-wide K tiles: whole 128-byte lines per row segment */
+    LORA_FUSED_128x128x64_W4 = 9,
+    LORA_FUSED_256x256x64_W8 = 10,
+    LORA_FUSED_256x256x32_W8 = 12         /* what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
+};
+/* Values of LORA_TUNE_SPLIT_VARIANT. */
+enum {
+    LORA_SPLIT_AUTO = 0,
+    LORA_SPLIT_256x128x32_W4 = 1,
+    LORA_SPLIT_256x64x32_W4 = 2,
+    LORA_SPLIT_128x128x32_W4 = 3,
+    LORA_SPLIT_128x128x32_W4_8STAGES = 4,
+    LORA_SPLIT_256x128x64_W8 = 6,
+    LORA_SPLIT_128x128x64_W4 = 7,
+    LORA_SPLIT_256x128x32_W8 = 8
+};
 lora_status lora_set_tuning(lora_ctx *ctx, int32_t key, int32_t value);
 
 /* Kernel launches made by the most recent lora_layer_forward on this context: fills up to `cap`

@@ -813,7 +813,9 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
             const char* name = nullptr;
             GemmArgs a = ga;
             a.m_end = m_split;
-            const hipError_t le = fv >= 8 ? launch_gemm_rows128_fused(a, fv - 8, s, &name) : launch_gemm_fused(a, fv, s, &name);
+            // 8 .. 10: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
+            const hipError_t le = (fv >= 8 && fv <= 10) ? launch_gemm_rows128_fused(a, fv - 8, s, &name)
+                                                        : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
         }

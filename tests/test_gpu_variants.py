@@ -9,11 +9,8 @@ from paper_2602_24044_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-# fused GEMM: 0 automatic, 1 - 5 the 32-wide-K tiles, 8 - 10 the 64-wide-K (whole cache line) tiles
-FUSED_VARIANTS = [1, 2, 3, 4, 5, 8, 9, 10]
-# split-K GEMM: 0 automatic, 1 - 4 and 8 the 32-wide-K tiles, 6 and 7 the 64-wide-K tiles
-SPLIT_VARIANTS = [1, 2, 3, 4, 6, 7, 8]
-
+FUSED_VARIANTS = sorted(B.FUSED_VARIANTS.values())
+SPLIT_VARIANTS = sorted(B.SPLIT_VARIANTS.values())
 
 @pytest.mark.parametrize("variant", FUSED_VARIANTS)
 def test_fused_variant_decode_and_prefill(variant):
