@@ -645,9 +645,25 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7) &&
                      pieces_bound * std::max(1, K / 2048) <= 512;
         const long target = dyn_shrink ? 192 : 256;
-        // enough K splits to give every CU a workgroup, but no more than 8: each split costs a pass of
-        // fp32 partial tiles through memory
-        S = c->cfg.split_k > 0 ? c->cfg.split_k : (int)std::max<long>(1, std::min<long>(8, (target + tiles / 2) / tiles));
+        // K splits, at most 8, by a cost model in microseconds: a workgroup walking all of K moves (bm + bn) K
+        // bf16 through its CU at about 48 GB/s, a launch takes ceil(tiles S / target) rounds of 1 / S of that
+        // (one workgroup per CU: a grid just above the CU count costs a whole extra round), and every split
+        // writes and reads back a set of fp32 partial tiles at about 5 TB/s.
+        if (c->cfg.split_k > 0) {
+            S = c->cfg.split_k;
+        } else {
+            const double t_full = (double)(bm + bn) * K * 2.0 / 48e3;
+            const double t_part = (double)Mpad * (double)n_pad_total * 8.0 / 5e6;
+            double best = 0.0;
+            for (int cand = 1; cand <= 8; ++cand) {
+                const double rounds = (double)((tiles * cand + target - 1) / target);
+                const double cost = t_full * rounds / cand + t_part * cand;
+                if (cand == 1 || cost < best) {
+                    best = cost;
+                    S = cand;
+                }
+            }
+        }
         S = std::min(S, std::max(1, (K / kBK) / 2));
         const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
         S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
