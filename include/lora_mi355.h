@@ -138,7 +138,7 @@ lora_status lora_create(const lora_config *cfg, lora_ctx **out);
 /* Waits for the context's own events, releases host resources.  The slab stays the caller's. */
 lora_status lora_destroy(lora_ctx *ctx);
 
-/* Makes n adapters resident (paper Sec. 2.2 / Sec. 5.2.2: adapters are loaded from CPU memory
+/* Makes n adapters resident (paper Sec. 2.2 / Sec. 5.1.3: adapters are loaded from CPU memory
  * into the GPU's adapter region; load time grows with adapter size, unloading is free).
  * in_use / n_in_use (host): adapter ids of the batch about to run; they are marked used now and
  * are never chosen as victims.  The whole call is planned on the host first: on any error

@@ -1,7 +1,7 @@
 """Latency model of one multi-adapter layer-step, fitted on measurements of this library.
 
 The paper models the latency of a serving step as the product of a term linear in the batch size B and a term
-linear in the number A of distinct adapters in the batch (Sec. 6, Eq. 1):
+linear in the number A of distinct adapters in the batch (Sec. 5.2, Eq. 1):
 
     Lat_model(B, A) = (K4 * B + K5) * (K6 * A + K7)
 

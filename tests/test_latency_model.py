@@ -1,4 +1,4 @@
-"""CPU tests of the Eq. 1 fit (paper Sec. 6): Lat(B, A) = (K4 B + K5)(K6 A + K7) with K7 fixed to 1."""
+"""CPU tests of the Eq. 1 fit (paper Sec. 5.2): Lat(B, A) = (K4 B + K5)(K6 A + K7) with K7 fixed to 1."""
 import numpy as np
 import pytest
 
