@@ -57,9 +57,9 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         P = ctypes.c_void_p
         lib.lora_oracle_project.restype = ctypes.c_int
-        lib.lora_oracle_project.argtypes = [ctypes.c_int32] * 3 + [P, P, P, ctypes.c_int32, P, P, P, P, P]
+        lib.lora_oracle_project.argtypes = [ctypes.c_int32] * 3 + [P, P, P, ctypes.c_int32, P, P, P, P, P, P]
         lib.lora_oracle_project_at.restype = ctypes.c_int
-        lib.lora_oracle_project_at.argtypes = ([ctypes.c_int32] * 3 + [P, P, P, ctypes.c_int32, P, P, P, P]
+        lib.lora_oracle_project_at.argtypes = ([ctypes.c_int32] * 3 + [P, P, P, ctypes.c_int32, P, P, P, P, P]
                                                + [ctypes.c_int64, P, P, P])
         lib.lora_oracle_threads.restype = ctypes.c_int
         _lib = lib
@@ -93,8 +93,17 @@ def _adapter_tables(adapters: Dict[int, Tuple[int, float, Optional[np.ndarray], 
     return n, rank, scale, A_ptr, B_ptr, keep
 
 
-def project(x: np.ndarray, W: np.ndarray, ids: np.ndarray, adapters) -> np.ndarray:
-    """y_ref [T, d_out] float64 for bf16-bit inputs x [T,d_in], W [d_out,d_in]."""
+def _bias_arg(bias, d_out: int):
+    if bias is None:
+        return None, None
+    bias = np.ascontiguousarray(bias, dtype=np.uint16)
+    assert bias.shape == (d_out,), (bias.shape, d_out)
+    return bias, bias.ctypes.data
+
+
+def project(x: np.ndarray, W: np.ndarray, ids: np.ndarray, adapters, bias=None) -> np.ndarray:
+    """y_ref [T, d_out] float64 for bf16-bit inputs x [T,d_in], W [d_out,d_in]; bias: bf16 bits [d_out] of the
+    backbone layer's bias, or None."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
     W = np.ascontiguousarray(W, dtype=np.uint16)
     ids = np.ascontiguousarray(ids, dtype=np.int32)
@@ -103,17 +112,18 @@ def project(x: np.ndarray, W: np.ndarray, ids: np.ndarray, adapters) -> np.ndarr
     assert W.shape[1] == d_in and ids.shape == (T,)
     n, rank, scale, A_ptr, B_ptr, keep = _adapter_tables(adapters, d_in, d_out)
     y = np.empty((T, d_out), dtype=np.float64)
+    bias, bias_p = _bias_arg(bias, d_out)
     rc = _load().lora_oracle_project(T, d_in, d_out, x.ctypes.data, W.ctypes.data, ids.ctypes.data, n,
                                      rank.ctypes.data, scale.ctypes.data,
                                      ctypes.cast(A_ptr, ctypes.c_void_p), ctypes.cast(B_ptr, ctypes.c_void_p),
-                                     y.ctypes.data)
+                                     bias_p, y.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle: token names an unknown adapter (rc={rc})")
     del keep
     return y
 
 
-def project_at(x, W, ids, adapters, ts: np.ndarray, ns: np.ndarray) -> np.ndarray:
+def project_at(x, W, ids, adapters, ts: np.ndarray, ns: np.ndarray, bias=None) -> np.ndarray:
     """y_ref at the sampled (token, column) pairs only, each evaluated on its own."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
     W = np.ascontiguousarray(W, dtype=np.uint16)
@@ -124,10 +134,11 @@ def project_at(x, W, ids, adapters, ts: np.ndarray, ns: np.ndarray) -> np.ndarra
     d_out = W.shape[0]
     n, rank, scale, A_ptr, B_ptr, keep = _adapter_tables(adapters, d_in, d_out)
     y = np.empty(ts.shape[0], dtype=np.float64)
+    bias, bias_p = _bias_arg(bias, d_out)
     rc = _load().lora_oracle_project_at(T, d_in, d_out, x.ctypes.data, W.ctypes.data, ids.ctypes.data, n,
                                         rank.ctypes.data, scale.ctypes.data,
                                         ctypes.cast(A_ptr, ctypes.c_void_p), ctypes.cast(B_ptr, ctypes.c_void_p),
-                                        ts.shape[0], ts.ctypes.data, ns.ctypes.data, y.ctypes.data)
+                                        bias_p, ts.shape[0], ts.ctypes.data, ns.ctypes.data, y.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle: bad sample or unknown adapter (rc={rc})")
     del keep

@@ -10,7 +10,10 @@
  *
  *     y[t,n] = sum_k x[t,k] W[n,k]  +  s_i * sum_j ( sum_k x[t,k] A_i[j,k] ) B_i[n,j]
  *
- * and y[t,n] = sum_k x[t,k] W[n,k] when id[t] < 0 or rank_i == 0.
+ * and y[t,n] = sum_k x[t,k] W[n,k] when id[t] < 0 or rank_i == 0.  Where the backbone layer has a
+ * bias b (the q, k, v projections of the Qwen2.5 family, one of the two model families of the
+ * paper's evaluation, Sec. 8.1), the backbone layer's output is x W^T + b and the adapter's
+ * activations are added to that: b[n] is added to every y[t,n], with or without an adapter.
  *
  * Inputs are bf16 bit patterns (uint16), widened exactly to double; all arithmetic is
  * IEEE double, plain nested loops in index order, no blocking, no intermediate or final
@@ -19,7 +22,9 @@
  *
  * Pins (tests, CPU only): all-backbone batches against a float64 library matmul, the
  * merged-weight identity y = x (W + s B A)^T, bitwise base-only results for B = 0 /
- * rank 0 / s = 0 / id = -1, hand-computed small-integer cases, one-hot inputs.
+ * rank 0 / s = 0 / id = -1, hand-computed small-integer cases, one-hot inputs; for the bias:
+ * x = 0 returns b in every row, a hand-computed integer case, and the difference to the
+ * bias-free result on mixed batches.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -43,7 +48,8 @@ static inline double widen_bf16(uint16_t b)
 int lora_oracle_project(int32_t T, int32_t d_in, int32_t d_out,
                         const uint16_t *x, const uint16_t *W, const int32_t *ids,
                         int32_t n_adapters, const int32_t *rank, const double *scale,
-                        const uint16_t *const *A, const uint16_t *const *B, double *y)
+                        const uint16_t *const *A, const uint16_t *const *B,
+                        const uint16_t *bias /* [d_out] or NULL */, double *y)
 {
     for (int32_t t = 0; t < T; ++t) {
         int32_t i = ids[t];
@@ -74,6 +80,7 @@ int lora_oracle_project(int32_t T, int32_t d_in, int32_t d_out,
                 double base = 0.0;
                 for (int32_t k = 0; k < d_in; ++k)
                     base += widen_bf16(xt[k]) * widen_bf16(Wn[k]);
+                if (bias) base += widen_bf16(bias[n]);
                 if (r > 0) {
                     const uint16_t *Bn = B[i] + (size_t)n * r;
                     double d = 0.0;
@@ -95,7 +102,7 @@ int lora_oracle_project_at(int32_t T, int32_t d_in, int32_t d_out,
                            const uint16_t *x, const uint16_t *W, const int32_t *ids,
                            int32_t n_adapters, const int32_t *rank, const double *scale,
                            const uint16_t *const *A, const uint16_t *const *B,
-                           int64_t n_samples, const int32_t *ts, const int32_t *ns, double *y)
+                           const uint16_t *bias /* [d_out] or NULL */, int64_t n_samples, const int32_t *ts, const int32_t *ns, double *y)
 {
     for (int64_t q = 0; q < n_samples; ++q) {
         if (ts[q] < 0 || ts[q] >= T || ns[q] < 0 || ns[q] >= d_out) return -2;
@@ -113,6 +120,7 @@ int lora_oracle_project_at(int32_t T, int32_t d_in, int32_t d_out,
         double base = 0.0;
         for (int32_t k = 0; k < d_in; ++k)
             base += widen_bf16(xt[k]) * widen_bf16(Wn[k]);
+        if (bias) base += widen_bf16(bias[n]);
         if (r > 0) {
             const uint16_t *Bn = B[i] + (size_t)n * r;
             double d = 0.0;

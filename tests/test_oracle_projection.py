@@ -42,6 +42,56 @@ def test_hand_computed_fixture():
     assert np.array_equal(oracle.project_at(x, W, ids, adapters, ts, ns), np.array(fx["y"]).reshape(-1))
 
 
+def _tiny_fixture():
+    fx = parse_fixture(os.path.join(GOLDEN, "tiny_projection.txt"))
+    adapters = {}
+    for i in (0, 1):
+        r = fx[f"a{i}_rank"][0][0]
+        adapters[i] = (r, fx[f"a{i}_scale"][0][0], _bits(fx[f"a{i}_A"]).reshape(r, -1),
+                       _bits(fx[f"a{i}_B"]).reshape(-1, r))
+    return _bits(fx["x"]), _bits(fx["W"]), np.array(fx["ids"][0], dtype=np.int32), adapters
+
+
+def test_hand_computed_fixture_with_bias():
+    # the backbone layer's output includes its bias; worked by hand in tests/golden/tiny_projection_bias.txt
+    x, W, ids, adapters = _tiny_fixture()
+    fb = parse_fixture(os.path.join(GOLDEN, "tiny_projection_bias.txt"))
+    b = _bits(fb["bias"][0])
+    y = oracle.project(x, W, ids, adapters, bias=b)
+    assert np.array_equal(y, np.array(fb["y"], dtype=np.float64))
+    ts = np.array([0, 0, 1, 1, 2, 2], dtype=np.int32)
+    ns = np.array([0, 1, 0, 1, 0, 1], dtype=np.int32)
+    assert np.array_equal(oracle.project_at(x, W, ids, adapters, ts, ns, bias=b), np.array(fb["y"]).reshape(-1))
+
+
+def test_bias_properties():
+    # T != d_out and a bias that differs in every column: a bias indexed by token, scaled by the adapter, or
+    # added only to rows with (or without) an adapter fails one of these
+    w = _small_workload(seed=31, T=7, d_in=32, d_out=24, ranks=(8, 0, 16))
+    ad = oracle.adapters_of(w, 0)
+    b = _bits(np.arange(24, dtype=np.float32) * 0.25 - 2.0)
+    bd = wl.bf16_bits_to_f64(b)
+    # x = 0: every row is the bias itself
+    y0 = oracle.project(np.zeros_like(w.x[0]), w.W[0], w.token_ids, ad, bias=b)
+    assert np.array_equal(y0, np.tile(bd, (w.T, 1)))
+    # mixed batch: the bias shifts every row by b, whatever its adapter
+    y = oracle.project(w.x[0], w.W[0], w.token_ids, ad)
+    yb = oracle.project(w.x[0], w.W[0], w.token_ids, ad, bias=b)
+    assert len(set(w.token_ids.tolist())) > 1
+    assert np.max(np.abs((yb - y) - bd[None, :])) <= 1e-12 * np.max(np.abs(y))
+    # backbone only: library matmul plus bias
+    ids = np.full(w.T, -1, dtype=np.int32)
+    ref = wl.bf16_bits_to_f64(w.x[0]) @ wl.bf16_bits_to_f64(w.W[0]).T + bd[None, :]
+    assert np.max(np.abs(oracle.project(w.x[0], w.W[0], ids, ad, bias=b) - ref)) <= 1e-12 * np.max(np.abs(ref))
+    # a zero bias is no bias, bitwise
+    assert np.array_equal(oracle.project(w.x[0], w.W[0], w.token_ids, ad, bias=np.zeros(24, dtype=np.uint16)), y)
+    # sampled evaluation agrees
+    ts = np.array([0, 3, 6, 2], dtype=np.int32)
+    ns = np.array([23, 0, 11, 5], dtype=np.int32)
+    ys = oracle.project_at(w.x[0], w.W[0], w.token_ids, ad, ts, ns, bias=b)
+    assert np.max(np.abs(ys - yb[ts, ns])) <= 1e-13 * np.max(np.abs(yb))
+
+
 def test_backbone_only_equals_library_matmul():
     w = _small_workload(T=17, d_in=96, d_out=72)
     ids = np.full(w.T, -1, dtype=np.int32)
