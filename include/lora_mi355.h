@@ -183,6 +183,16 @@ lora_status lora_layer_forward_group(lora_ctx* ctx, int32_t n, const int32_t* pr
                                      const void* const* d_W, const lora_segments* seg, void* const* d_out,
                                      void* stream);
 
+/* Bias of a backbone projection (paper Sec. 2.2: the adapter's activations are added to the backbone layer's
+ * output, which for a layer with a bias is x W^T + b; Sec. 8.1 evaluates on the Qwen2.5 family, whose q, k, v
+ * projections have one).  d_bias: device bf16 [d_out_proj], 16-byte aligned, owned by the caller, read by every
+ * later lora_layer_forward / lora_layer_forward_group of that projection until it is replaced: it must stay
+ * valid and unchanged while such calls may still run.  NULL removes the bias (the state after lora_create).
+ * The result becomes bf16(x W^T + b + s (x A^T) B^T): b is added in fp32 before the one rounding.  Host state
+ * only: nothing is enqueued and calls already enqueued are not affected.
+ * Errors: INVALID_ARG (proj out of range, misaligned pointer). */
+lora_status lora_set_bias(lora_ctx *ctx, int32_t proj, const void *d_bias);
+
 /* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
  * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set, else LORA_OK; *flags (may be NULL)
  * receives the raw word. */

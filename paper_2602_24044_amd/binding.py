@@ -64,7 +64,7 @@ EXPORTS = [
     "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error", "lora_set_tuning",
+    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias",
 ]
 LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
@@ -133,6 +133,8 @@ _lib.lora_profile_reset.restype = ctypes.c_int
 _lib.lora_profile_reset.argtypes = [_P]
 _lib.lora_status_string.restype = ctypes.c_char_p
 _lib.lora_status_string.argtypes = [ctypes.c_int]
+_lib.lora_set_bias.restype = ctypes.c_int
+_lib.lora_set_bias.argtypes = [_P, ctypes.c_int32, _P]
 _lib.lora_set_tuning.restype = ctypes.c_int
 _lib.lora_set_tuning.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
 _lib.lora_last_hip_error.restype = ctypes.c_char_p
@@ -255,6 +257,13 @@ def lora_slot_of(ctx: int, adapter_id: int) -> int:
 
 def lora_slot_adapter(ctx: int, slot: int) -> int:
     return int(_lib.lora_slot_adapter(_P(ctx), int(slot)))
+
+
+def lora_set_bias(ctx: int, proj: int, d_bias: int) -> None:
+    """d_bias: device address of bf16 [d_out] (0 removes the bias); the memory stays the caller's."""
+    st = _lib.lora_set_bias(_P(ctx), int(proj), _P(int(d_bias) or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_set_bias")
 
 
 def lora_set_tuning(ctx: int, key: int, value: int) -> None:

@@ -146,12 +146,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, Shrin
     }
 
     f32x16 acc[MB][NB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    init_accumulators<MB, NB, FUSED>(acc, sl, n0 + wn * WTN);
 
     // ---- software-pipelined main loop ----
     // Tile j lives in stage j % NS.  State at the top of iteration j: tile j has landed for every wave,

@@ -30,6 +30,36 @@ constexpr int epilogue_bytes_per_wave()
     return v > o ? v : o;
 }
 
+// Accumulators at the start of a tile: zero, or on the fused path the bias of the backbone layer where the
+// projection has one (the q, k, v projections of the Qwen2.5 family): the products are then accumulated onto it
+// in fp32 and it costs the epilogue neither loads nor registers.  The split path adds the bias once, in the
+// reduce kernel.
+template <int MB, int NB, bool FUSED>
+__device__ __forceinline__ void init_accumulators(f32x16 (&acc)[MB][NB], const Slice& sl, int n_first)
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    if (!FUSED || sl.bias == nullptr) return;                     // uniform over the launch
+    const int h = (threadIdx.x & (kWave - 1)) >> 5;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n_first + nb * 32 + g * 8 + h * 4;      // N is a multiple of 8: all four or none
+            if (n < sl.N) {
+                const bf16x4 b = __builtin_bit_cast(bf16x4, *reinterpret_cast<const u32x2*>(sl.bias + n));
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[mb][nb][g * 4 + e] = (float)b[e];
+            }
+        }
+}
+
 // Rounds WB windows of accumulators to bf16 and stores them to out rows perm[m], through LDS (sT: this wave's
 // piece, WB * 32 rows of NB * 64 bytes).  Chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & (CH - 1)):
 // the 8-byte writes of a half wave then collide two ways at most and the 16-byte reads are contiguous.

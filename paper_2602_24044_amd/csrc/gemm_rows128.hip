@@ -146,12 +146,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     auto copy_tile = [&](int t, int stage) { copy_part(t, stage, 0, QPT); };
 
     f32x16 acc[MB][NB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    init_accumulators<MB, NB, FUSED>(acc, sl, n0 + wn * WTN);
 
     // byte offset of this lane's fragment of K step kk inside a 32-row block: row i, chunk 2 kk + h
     const int sw = (i >> 1) & 7;

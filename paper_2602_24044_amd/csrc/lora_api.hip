@@ -174,6 +174,7 @@ struct lora_ctx {
     bool have_fwd = false;
 
     int32_t tune[8] = {0};
+    const uint16_t* bias[kMaxProj] = {nullptr};   // device, caller-owned (lora_set_bias)
 
     // current segment map
     uint64_t epoch = 0;
@@ -712,6 +713,7 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         sl.vpart = vpart + vslice * k;
         sl.a_off = c->L.a_off[p];
         sl.b_off = c->L.b_off[p];
+        sl.bias = c->bias[p];
         sl.N = c->proj[p].d_out;
         sl.tile0 = 0;
         sl.blk0 = blk;
@@ -872,6 +874,14 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
     if (flags) *flags = word;
     return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
+}
+
+lora_status lora_set_bias(lora_ctx* c, int32_t proj, const void* d_bias)
+{
+    if (!c || proj < 0 || proj >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_bias) & 15) return LORA_ERR_INVALID_ARG;
+    c->bias[proj] = static_cast<const uint16_t*>(d_bias);
+    return LORA_OK;
 }
 
 lora_status lora_set_tuning(lora_ctx* c, int32_t key, int32_t value)

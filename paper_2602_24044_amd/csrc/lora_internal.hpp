@@ -97,6 +97,7 @@ struct Slice {
     int32_t tile0;       // first N tile of the slice (set by the GEMM launcher for its tile width)
     int32_t blk0;        // first 32-column block of the slice in the packed partial matrix (multiple of 4)
     int32_t pad_;
+    const uint16_t* bias;// [N] bf16 bias of the backbone layer, or null
 };
 struct GroupArgs {
     int32_t n;

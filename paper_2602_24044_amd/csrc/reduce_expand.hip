@@ -1,5 +1,5 @@
 // Split-K reduction fused with the LoRA expand and the output rounding:
-//   out[perm[m], n] = bf16( sum_s part[s][m][n] + scale * sum_j v[m][j] B_slot(m)[n][j] )
+//   out[perm[m], n] = bf16( sum_s part[s][m][n] + bias[n] + scale * sum_j v[m][j] B_slot(m)[n][j] )
 // (paper Sec. 2.2: the second low-rank matrix maps the adapter's activations back to the layer's
 // output, where they are added to the backbone result).
 //
@@ -78,6 +78,16 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         }
     };
     if (cols_on) load_splits(0);
+    // bias of the backbone layer (null: none), this lane's 16 columns
+    bf16x4 bias[4];
+    const bool bias_on = sl.bias != nullptr;
+    if (bias_on) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n_first + g * 8 + h * 4;
+            bias[g] = __builtin_bit_cast(bf16x4, n < N ? *reinterpret_cast<const u32x2*>(sl.bias + n) : u32x2{0u, 0u});
+        }
+    }
 
     // the window's shrink results, thread -> (row, 8 ranks): requested behind the first partial tiles (their
     // address needs only the row's rank, which was requested before those)
@@ -98,6 +108,13 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
             load_splits(s0);
             add_splits(s0);
         }
+    }
+
+    if (bias_on) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[0][g * 4 + e] += (float)bias[g][e];
     }
 
     // stage the scaled shrink results as bf16

@@ -50,6 +50,7 @@ class Session:
         self.x: List[torch.Tensor] = []
         self.out: List[torch.Tensor] = []
         self.ids: Optional[torch.Tensor] = None
+        self.bias: List[Optional[torch.Tensor]] = []
         if upload_inputs:
             self.upload_inputs()
 
@@ -60,6 +61,10 @@ class Session:
         self.x = [_bf16_tensor(m, self.device) for m in w.x]
         self.out = [torch.empty((w.T, d_out), dtype=torch.bfloat16, device=self.device) for (_, d_out) in w.proj]
         self.ids = torch.from_numpy(w.token_ids).to(self.device)
+        self.bias = [None if w.bias_of(p) is None else _bf16_tensor(w.bias_of(p), self.device)
+                     for p in range(len(w.proj))]
+        for p, b in enumerate(self.bias):
+            B.lora_set_bias(self.ctx, p, 0 if b is None else b.data_ptr())
 
     def pin_adapter(self, aid: int) -> dict:
         if aid not in self.pinned:

@@ -91,6 +91,10 @@ class Workload:
     resident: List[int] = field(default_factory=list)   # adapter ids preloaded before the step
     missing: List[int] = field(default_factory=list)    # adapter ids the step must load first
     request_lens: Optional[np.ndarray] = None
+    bias: List[Optional[np.ndarray]] = field(default_factory=list)   # per projection: uint16 [d_out] or None
+
+    def bias_of(self, p: int) -> Optional[np.ndarray]:
+        return self.bias[p] if p < len(self.bias) else None
 
     @property
     def T(self) -> int:
@@ -271,7 +275,13 @@ def qwen_decode(shrink: int = 1, n_tokens: int = 256, mode: int = BUCKET_SORTED)
     ids = zipf_ids(rng, n_tokens, list(range(32)), 1.0)
     if mode != BUCKET_SORTED:
         ids = np.sort(ids)[::-1].copy()          # runs of equal adapters, as contiguous prefill requests would be
-    return custom(f"qwen7b_decode_s{shrink}", seed, proj, names, 32, 32, mode, ids, ranks)
+    w = custom(f"qwen7b_decode_s{shrink}", seed, proj, names, 32, 32, mode, ids, ranks)
+    # the q, k, v projections of this model family have a bias; drawn from a generator of its own, of the
+    # size of the projections' outputs so that dropping it is far outside the parity tolerance
+    brng = np.random.default_rng(2000 + seed)
+    w.bias = [to_bf16_bits(brng.standard_normal(d_out).astype(np.float32)) if nm in ("q", "k", "v") else None
+              for nm, (_, d_out) in zip(names, proj)]
+    return w
 
 
 def by_index(i: int, **kw) -> Workload:

@@ -63,7 +63,7 @@ def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=
         for p in range(len(w.proj)):
             out = sess.out[p] if packed else sess.forward(p)
             torch.cuda.synchronize()
-            y_ref = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p))
+            y_ref = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p), bias=w.bias_of(p))
             e = rel_err(bf16_tensor_to_bits(out), y_ref)
             launches = group_launches[p] if packed else B.lora_last_launches(sess.ctx)
             announce(f"  proj {p} {w.proj[p]} launches={launches} rel_err={e:.3e}")

@@ -163,3 +163,16 @@ def test_group_argument_errors():
         assert status([0, 1]) == B.LORA_ERR_INVALID_ARG               # no segment map yet
     finally:
         B.lora_destroy(ctx)
+
+
+def test_bias_argument_errors():
+    ctx = _host_ctx(proj=((64, 64), (64, 128)))
+    try:
+        B.lora_set_bias(ctx, 1, 0)                       # removing a bias that is not set is fine
+        B.lora_set_bias(ctx, 0, 4096)                    # host state only: the address is not touched here
+        for proj, addr in ((-1, 4096), (2, 4096), (0, 4096 + 8)):
+            with pytest.raises(B.LoraError) as e:
+                B.lora_set_bias(ctx, proj, addr)
+            assert e.value.status == B.LORA_ERR_INVALID_ARG
+    finally:
+        B.lora_destroy(ctx)

@@ -47,7 +47,7 @@ def _run_full(w, n_samples=N_SAMPLES, packed=True):
             # always include the first and last token / column (tile edges)
             ts[:4] = [0, 0, w.T - 1, w.T - 1]
             ns[:4] = [0, d_out - 1, 0, d_out - 1]
-            y_ref = oracle.project_at(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p), ts, ns)
+            y_ref = oracle.project_at(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p), ts, ns, bias=w.bias_of(p))
             got = wl.bf16_bits_to_f64(got_all[ts, ns])
             # scale of the projection: the largest sampled reference magnitude (a lower bound of max|y_ref|)
             err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))

@@ -62,6 +62,44 @@ def test_qwen_shapes_prefill_runs_reduced():
     run_and_check(w, path=B.LORA_PATH_AUTO, packed=True)
 
 
+@pytest.mark.parametrize("path", PATHS)
+def test_bias_is_added_and_can_be_removed(path):
+    # the q, k, v projections of the Qwen2.5 family have a bias: added before the rounding, for rows with and
+    # without an adapter; removing it restores the bias-free result
+    w = wl.qwen_decode(shrink=4, n_tokens=300)
+    w.token_ids[::5] = -1
+    announce(f"bias on/off {w.name} T={w.T} path={path}")
+    s = Session(w, path=path)
+    try:
+        s.load(w.resident)
+        s.bucket()
+        g = [w.proj_names.index(nm) for nm in ("q", "k", "v")]
+        assert all(w.bias_of(p) is not None for p in g)
+        for packed in (True, False):
+            if packed:
+                s.forward_group(g)
+            else:
+                for p in g:
+                    s.forward(p)
+            torch.cuda.synchronize()
+            for p in g:
+                ad = oracle.adapters_of(w, p)
+                with_b = oracle.project(w.x[p], w.W[p], w.token_ids, ad, bias=w.bias_of(p))
+                without = oracle.project(w.x[p], w.W[p], w.token_ids, ad)
+                got = bf16_tensor_to_bits(s.out[p])
+                assert rel_err(got, with_b) <= TOL
+                assert rel_err(got, without) > 10 * TOL          # the bias is far outside the tolerance
+        for p in g:
+            B.lora_set_bias(s.ctx, p, 0)
+        s.forward_group(g)
+        torch.cuda.synchronize()
+        for p in g:
+            without = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p))
+            assert rel_err(bf16_tensor_to_bits(s.out[p]), without) <= TOL
+    finally:
+        s.close()
+
+
 @pytest.mark.parametrize("mode", [wl.BUCKET_SORTED, wl.BUCKET_RUNS])
 def test_poorly_filled_last_round_takes_the_split_path(mode):
     # 18 x 16 tiles of 256 x 256: one full round of 256 and 32 more.  The fused launch stops after 16 row tiles and
