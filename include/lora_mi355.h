@@ -93,11 +93,14 @@ typedef struct {
     int32_t path;           /* LORA_PATH_* */
     int32_t split_k;        /* 0 = automatic; otherwise the K split of the SPLITK path (1..16) */
     uint32_t flags;         /* LORA_CREATE_* */
+    int32_t n_layers;       /* decoder layers that share the slot table, 1 .. 256 (0 is read as 1): a slot then
+                               holds one adapter's matrices for every layer, see lora_model_forward_group */
 } lora_config;
 
 /* One adapter to make resident.  A[p] / B[p]: pinned host, row-major bf16, A[p] is
  * [rank, d_in_p], B[p] is [d_out_p, rank]; they must stay valid and unchanged until the copy
- * stream has passed the call.  rank must be 0 or a multiple of 8 (<= max_rank); rank 0 needs no
+ * stream has passed the call.  With n_layers > 1 the arrays hold n_layers * n_proj pointers,
+ * layer-major: A[layer * n_proj + p].  rank must be 0 or a multiple of 8 (<= max_rank); rank 0 needs no
  * A/B.  slot: in, >= 0 = explicit slot, -1 = the library picks (an empty slot, else the least
  * recently used one); out = slot used.  copied: out, 1 if weights were copied, 0 if the adapter
  * was already resident (touch only). */
@@ -127,7 +130,7 @@ typedef struct {
 } lora_segments;
 
 /* Device bytes the context needs for `cfg` (slot region + scratch); 0 if cfg is invalid.
- * Slot region = n_slots * max_rank * sum_p (d_in_p + d_out_p) * 2 bytes: every slot has the
+ * Slot region = n_slots * n_layers * max_rank * sum_p (d_in_p + d_out_p) * 2 bytes: every slot has the
  * uniform S_max footprint, but kernels only ever read an adapter's own rank rows. */
 size_t lora_slab_bytes(const lora_config *cfg);
 
@@ -183,6 +186,18 @@ lora_status lora_layer_forward_group(lora_ctx* ctx, int32_t n, const int32_t* pr
                                      const void* const* d_W, const lora_segments* seg, void* const* d_out,
                                      void* stream);
 
+/* Whole-model form of lora_layer_forward_group (paper Sec. 2.2: an adapter adds its matrices to the targeted
+ * layers of every decoder layer, and the adapter slots hold whole adapters; Sec. 5.1.3: loading time grows with
+ * adapter size).  The context was created with n_layers > 1; `layer` (0 .. n_layers - 1) selects which layer's
+ * part of every slot the call reads; everything else as lora_layer_forward_group, which is this call with
+ * layer 0.  The segment map of one lora_bucket serves every layer of the step.  lora_slots_load enqueues an
+ * adapter's copies layer after layer and the forward of a layer waits only for the copies of its own
+ * projections, so a step that runs behind a load starts on the first layers while later ones still travel.
+ * Errors: as lora_layer_forward_group, INVALID_ARG also for a layer out of range. */
+lora_status lora_model_forward_group(lora_ctx *ctx, int32_t layer, int32_t n, const int32_t *projs,
+                                     const void *const *d_x, const void *const *d_W, const lora_segments *seg,
+                                     void *const *d_out, void *stream);
+
 /* Bias of a backbone projection (paper Sec. 2.2: the adapter's activations are added to the backbone layer's
  * output, which for a layer with a bias is x W^T + b; Sec. 8.1 evaluates on the Qwen2.5 family, whose q, k, v
  * projections have one).  d_bias: device bf16 [d_out_proj], 16-byte aligned, owned by the caller, read by every
@@ -190,8 +205,9 @@ lora_status lora_layer_forward_group(lora_ctx* ctx, int32_t n, const int32_t* pr
  * valid and unchanged while such calls may still run.  NULL removes the bias (the state after lora_create).
  * The result becomes bf16(x W^T + b + s (x A^T) B^T): b is added in fp32 before the one rounding.  Host state
  * only: nothing is enqueued and calls already enqueued are not affected.
- * Errors: INVALID_ARG (proj out of range, misaligned pointer). */
-lora_status lora_set_bias(lora_ctx *ctx, int32_t proj, const void *d_bias);
+ * layer: 0 unless the context has n_layers > 1.
+ * Errors: INVALID_ARG (layer or proj out of range, misaligned pointer). */
+lora_status lora_set_bias(lora_ctx *ctx, int32_t layer, int32_t proj, const void *d_bias);
 
 /* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
  * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set, else LORA_OK; *flags (may be NULL)

@@ -64,7 +64,7 @@ EXPORTS = [
     "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias",
+    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group",
 ]
 LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
@@ -84,7 +84,8 @@ class lora_config(ctypes.Structure):
     _fields_ = [("n_slots", ctypes.c_int32), ("max_rank", ctypes.c_int32), ("n_proj", ctypes.c_int32),
                 ("proj", ctypes.POINTER(lora_proj_shape)), ("max_tokens", ctypes.c_int32),
                 ("max_adapter_id", ctypes.c_int32), ("slab", ctypes.c_void_p), ("slab_bytes", ctypes.c_size_t),
-                ("path", ctypes.c_int32), ("split_k", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("path", ctypes.c_int32), ("split_k", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("n_layers", ctypes.c_int32)]
 
 
 class lora_adapter_desc(ctypes.Structure):
@@ -116,6 +117,10 @@ _lib.lora_layer_forward.argtypes = [_P, ctypes.c_int32, _P, _P, ctypes.POINTER(l
 _lib.lora_layer_forward_group.restype = ctypes.c_int
 _lib.lora_layer_forward_group.argtypes = [_P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_P),
                                           ctypes.POINTER(_P), ctypes.POINTER(lora_segments), ctypes.POINTER(_P), _P]
+_lib.lora_model_forward_group.restype = ctypes.c_int
+_lib.lora_model_forward_group.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                                          ctypes.POINTER(_P), ctypes.POINTER(_P), ctypes.POINTER(lora_segments),
+                                          ctypes.POINTER(_P), _P]
 _lib.lora_poll_device_flags.restype = ctypes.c_int
 _lib.lora_poll_device_flags.argtypes = [_P, ctypes.POINTER(ctypes.c_uint32), _P]
 _lib.lora_slot_of.restype = ctypes.c_int32
@@ -134,7 +139,7 @@ _lib.lora_profile_reset.argtypes = [_P]
 _lib.lora_status_string.restype = ctypes.c_char_p
 _lib.lora_status_string.argtypes = [ctypes.c_int]
 _lib.lora_set_bias.restype = ctypes.c_int
-_lib.lora_set_bias.argtypes = [_P, ctypes.c_int32, _P]
+_lib.lora_set_bias.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, _P]
 _lib.lora_set_tuning.restype = ctypes.c_int
 _lib.lora_set_tuning.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
 _lib.lora_last_hip_error.restype = ctypes.c_char_p
@@ -158,10 +163,11 @@ def lora_last_hip_error() -> str:
 
 def make_config(proj: Sequence[Tuple[int, int]], n_slots: int, max_rank: int, max_tokens: int,
                 max_adapter_id: int, slab_ptr: int = 0, slab_bytes: int = 0, path: int = LORA_PATH_AUTO,
-                split_k: int = 0, flags: int = 0):
+                split_k: int = 0, flags: int = 0, n_layers: int = 1):
     arr = (lora_proj_shape * len(proj))(*[lora_proj_shape(int(a), int(b)) for a, b in proj])
     cfg = lora_config(int(n_slots), int(max_rank), len(proj), arr, int(max_tokens), int(max_adapter_id),
-                      ctypes.c_void_p(slab_ptr or None), int(slab_bytes), int(path), int(split_k), int(flags))
+                      ctypes.c_void_p(slab_ptr or None), int(slab_bytes), int(path), int(split_k), int(flags),
+                      int(n_layers))
     cfg._keep = arr
     return cfg
 
@@ -242,6 +248,18 @@ def lora_layer_forward_group(ctx: int, projs: Sequence[int], d_x: Sequence[int],
         raise LoraError(st, "lora_layer_forward_group")
 
 
+def lora_model_forward_group(ctx: int, layer: int, projs: Sequence[int], d_x: Sequence[int], d_W: Sequence[int],
+                             seg: lora_segments, d_out: Sequence[int], stream: int = 0) -> None:
+    n = len(projs)
+    pa = (ctypes.c_int32 * n)(*[int(p) for p in projs])
+    xa = (_P * n)(*[_P(v or None) for v in d_x])
+    wa = (_P * n)(*[_P(v or None) for v in d_W])
+    oa = (_P * n)(*[_P(v or None) for v in d_out])
+    st = _lib.lora_model_forward_group(_P(ctx), int(layer), n, pa, xa, wa, ctypes.byref(seg), oa, _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_model_forward_group")
+
+
 def lora_poll_device_flags(ctx: int, stream: int = 0) -> Tuple[int, int]:
     """Returns (status, raw flag word); status is LORA_OK or LORA_ERR_NOT_RESIDENT."""
     w = ctypes.c_uint32(0)
@@ -259,9 +277,9 @@ def lora_slot_adapter(ctx: int, slot: int) -> int:
     return int(_lib.lora_slot_adapter(_P(ctx), int(slot)))
 
 
-def lora_set_bias(ctx: int, proj: int, d_bias: int) -> None:
+def lora_set_bias(ctx: int, proj: int, d_bias: int, layer: int = 0) -> None:
     """d_bias: device address of bf16 [d_out] (0 removes the bias); the memory stays the caller's."""
-    st = _lib.lora_set_bias(_P(ctx), int(proj), _P(int(d_bias) or None))
+    st = _lib.lora_set_bias(_P(ctx), int(layer), int(proj), _P(int(d_bias) or None))
     if st != LORA_OK:
         raise LoraError(st, "lora_set_bias")
 

@@ -29,8 +29,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t slot_stride_elems = 0;          // bf16 elements per slot
-    size_t a_off[kMaxProj] = {0};          // element offsets inside a slot
-    size_t b_off[kMaxProj] = {0};
+    std::vector<size_t> a_off, b_off;      // [n_layers * n_proj] element offsets inside a slot (layer-major)
     size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
     size_t off_row_rank = 0, off_row_scale = 0;
     size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
@@ -82,6 +81,7 @@ bool valid_config(const lora_config* c)
     if (c->n_slots < 1 || c->n_slots > kMaxSlots) return false;
     if (c->max_rank < 8 || c->max_rank > kMaxRank || c->max_rank % 8) return false;
     if (c->n_proj < 1 || c->n_proj > kMaxProj) return false;
+    if (c->n_layers < 0 || c->n_layers > kMaxLayers) return false;
     if (c->max_tokens < 1 || c->max_adapter_id < 0) return false;
     if (c->path < LORA_PATH_AUTO || c->path > LORA_PATH_SPLITK) return false;
     if (c->split_k < 0 || c->split_k > 16) return false;
@@ -100,13 +100,19 @@ Layout make_layout(const lora_config* c)
     Layout L;
     size_t e = 0;
     int k_max = 0;
-    for (int p = 0; p < c->n_proj; ++p) {
-        L.a_off[p] = e;
-        e += (size_t)c->max_rank * c->proj[p].d_in;
-        L.b_off[p] = e;
-        e += (size_t)c->max_rank * c->proj[p].d_out;
-        k_max = std::max(k_max, c->proj[p].d_in);
-    }
+    const int n_layers = std::max(1, c->n_layers);
+    L.a_off.resize((size_t)n_layers * c->n_proj);
+    L.b_off.resize((size_t)n_layers * c->n_proj);
+    // a slot holds one adapter of the whole model: layer after layer, per layer the A and B of every projection
+    for (int l = 0; l < n_layers; ++l)
+        for (int p = 0; p < c->n_proj; ++p) {
+            const size_t f = (size_t)l * c->n_proj + p;
+            L.a_off[f] = e;
+            e += (size_t)c->max_rank * c->proj[p].d_in;
+            L.b_off[f] = e;
+            e += (size_t)c->max_rank * c->proj[p].d_out;
+            k_max = std::max(k_max, c->proj[p].d_in);
+        }
     L.slot_stride_elems = align_up(e * 2, kAlign) / 2;
     const size_t Tm = (size_t)c->max_tokens;
     size_t o = 0;
@@ -166,15 +172,16 @@ struct lora_ctx {
 
     // stream ordering
     hipEvent_t ev_meta = nullptr, ev_fwd = nullptr;
-    hipEvent_t ev_proj[kMaxProj] = {nullptr};
+    std::vector<hipEvent_t> ev_proj;        // [n_layers * n_proj]: copies of that layer's projection enqueued
     bool meta_pending = false;
-    bool proj_pending[kMaxProj] = {false};
+    std::vector<char> proj_pending;         // [n_layers * n_proj]
+    int n_layers = 1;
     hipStream_t copy_stream = nullptr;      // stream of the latest load
     hipStream_t last_fwd_stream = nullptr;
     bool have_fwd = false;
 
     int32_t tune[8] = {0};
-    const uint16_t* bias[kMaxProj] = {nullptr};   // device, caller-owned (lora_set_bias)
+    std::vector<const uint16_t*> bias;      // [n_layers * n_proj] device, caller-owned (lora_set_bias)
 
     // current segment map
     uint64_t epoch = 0;
@@ -293,6 +300,11 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
     c->cfg.proj = c->proj.data();
     c->L = make_layout(&c->cfg);
     c->host_only = (cfg->flags & LORA_CREATE_HOST_ONLY) != 0;
+    c->n_layers = std::max(1, cfg->n_layers);
+    const size_t n_flat = (size_t)c->n_layers * cfg->n_proj;
+    c->ev_proj.assign(n_flat, nullptr);
+    c->proj_pending.assign(n_flat, 0);
+    c->bias.assign(n_flat, nullptr);
     c->slot_adapter.assign(cfg->n_slots, -1);
     c->slot_rank_h.assign(cfg->n_slots, 0);
     c->slot_scale_h.assign(cfg->n_slots, 0.f);
@@ -311,8 +323,8 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
         c->base = static_cast<char*>(cfg->slab);
         bool ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming)) &&
                   !HIP_FAIL(hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming));
-        for (int p = 0; ok && p < cfg->n_proj; ++p)
-            ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_proj[p], hipEventDisableTiming));
+        for (size_t f = 0; ok && f < n_flat; ++f)
+            ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_proj[f], hipEventDisableTiming));
         ok = ok && !HIP_FAIL(launch_fill_i32(c->d_slot_rank(), 0, cfg->n_slots, nullptr));
         ok = ok && !HIP_FAIL(launch_fill_i32(reinterpret_cast<int32_t*>(c->d_slot_scale()), 0, cfg->n_slots, nullptr));
         ok = ok && !HIP_FAIL(launch_fill_i32(c->d_id2slot(), -1, (size_t)cfg->max_adapter_id + 1, nullptr));
@@ -336,8 +348,8 @@ lora_status lora_destroy(lora_ctx* c)
         (void)hipDeviceSynchronize();
         if (c->ev_meta) (void)hipEventDestroy(c->ev_meta);
         if (c->ev_fwd) (void)hipEventDestroy(c->ev_fwd);
-        for (int p = 0; p < kMaxProj; ++p)
-            if (c->ev_proj[p]) (void)hipEventDestroy(c->ev_proj[p]);
+        for (hipEvent_t e : c->ev_proj)
+            if (e) (void)hipEventDestroy(e);
         for (auto& s : c->prof_pool) {
             (void)hipEventDestroy(s.beg);
             (void)hipEventDestroy(s.end);
@@ -378,8 +390,8 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
         if (d.slot < -1 || d.slot >= n_slots) return LORA_ERR_SLOT_RANGE;
         if (d.rank > 0 && !c->host_only) {
             if (!d.A || !d.B) return LORA_ERR_INVALID_ARG;
-            for (int p = 0; p < n_proj; ++p)
-                if (!d.A[p] || !d.B[p]) return LORA_ERR_INVALID_ARG;
+            for (int f = 0; f < n_proj * c->n_layers; ++f)
+                if (!d.A[f] || !d.B[f]) return LORA_ERR_INVALID_ARG;
         }
     }
 
@@ -483,11 +495,13 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     }
     if (HIP_FAIL(hipEventRecord(c->ev_meta, cs))) return LORA_ERR_HIP;
     c->meta_pending = true;
-    // The matrices of one projection travel in one launch of a kernel that reads the pinned host memory itself
+    // Layer after layer, so that a forward pass running behind the copies can start on the first layers while
+    // the later ones still travel.  The matrices of one projection travel in one launch of a kernel that reads the pinned host memory itself
     // (a hipMemcpyAsync per matrix costs the host and the copy engine about as much as the matrix's transfer);
     // a source that is not device-visible pinned host memory goes through hipMemcpyAsync.
     char* slots = c->base + c->L.off_slots;
-    for (int p = 0; p < n_proj; ++p) {
+    for (int f = 0; f < n_proj * c->n_layers; ++f) {
+        const int p = f % n_proj;
         const size_t d_in = c->proj[p].d_in, d_out = c->proj[p].d_out;
         CopyBatch batch;
         batch.n = 0;
@@ -511,12 +525,12 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             if (!out_copied[i] || descs[i].rank <= 0) continue;
             const size_t r = descs[i].rank;
             char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
-            if (!enqueue(slot_base + c->L.a_off[p] * 2, descs[i].A[p], r * d_in * 2)) return LORA_ERR_HIP;
-            if (!enqueue(slot_base + c->L.b_off[p] * 2, descs[i].B[p], d_out * r * 2)) return LORA_ERR_HIP;
+            if (!enqueue(slot_base + c->L.a_off[f] * 2, descs[i].A[f], r * d_in * 2)) return LORA_ERR_HIP;
+            if (!enqueue(slot_base + c->L.b_off[f] * 2, descs[i].B[f], d_out * r * 2)) return LORA_ERR_HIP;
         }
         if (!flush()) return LORA_ERR_HIP;
-        if (HIP_FAIL(hipEventRecord(c->ev_proj[p], cs))) return LORA_ERR_HIP;
-        c->proj_pending[p] = true;
+        if (HIP_FAIL(hipEventRecord(c->ev_proj[f], cs))) return LORA_ERR_HIP;
+        c->proj_pending[f] = 1;
     }
     c->copy_stream = cs;
     return LORA_OK;
@@ -575,11 +589,13 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     return LORA_OK;
 }
 
-lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,
-                                     const void* const* d_W, const lora_segments* seg, void* const* d_out,
-                                     void* stream_v)
+lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, const int32_t* projs,
+                                     const void* const* d_x, const void* const* d_W, const lora_segments* seg,
+                                     void* const* d_out, void* stream_v)
 {
     if (!c || !seg || !projs || n < 1 || n > kMaxGroup) return LORA_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->n_layers) return LORA_ERR_INVALID_ARG;
+    const int flat0 = layer * c->cfg.n_proj;                 // this layer's projections in the per-layer tables
     for (int k = 0; k < n; ++k) {
         if (projs[k] < 0 || projs[k] >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
         for (int j = 0; j < k; ++j)
@@ -600,9 +616,9 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
     }
     hipStream_t s = static_cast<hipStream_t>(stream_v);
     for (int k = 0; k < n; ++k) {
-        const int p = projs[k];
-        if (c->proj_pending[p] && s != c->copy_stream) {
-            if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[p], 0))) return LORA_ERR_HIP;
+        const int f = flat0 + projs[k];
+        if (c->proj_pending[f] && s != c->copy_stream) {
+            if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[f], 0))) return LORA_ERR_HIP;
         }
     }
     const int K = c->proj[projs[0]].d_in;
@@ -711,9 +727,9 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
         sl.W = static_cast<const uint16_t*>(d_W[k]);
         sl.out = static_cast<uint16_t*>(d_out[k]);
         sl.vpart = vpart + vslice * k;
-        sl.a_off = c->L.a_off[p];
-        sl.b_off = c->L.b_off[p];
-        sl.bias = c->bias[p];
+        sl.a_off = c->L.a_off[flat0 + p];
+        sl.b_off = c->L.b_off[flat0 + p];
+        sl.bias = c->bias[flat0 + p];
         sl.N = c->proj[p].d_out;
         sl.tile0 = 0;
         sl.blk0 = blk;
@@ -857,10 +873,17 @@ lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* proj
     return LORA_OK;
 }
 
+lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,
+                                     const void* const* d_W, const lora_segments* seg, void* const* d_out,
+                                     void* stream_v)
+{
+    return lora_model_forward_group(c, 0, n, projs, d_x, d_W, seg, d_out, stream_v);
+}
+
 lora_status lora_layer_forward(lora_ctx* c, int32_t p, const void* d_x, const void* d_W, const lora_segments* seg,
                                void* d_out, void* stream_v)
 {
-    return lora_layer_forward_group(c, 1, &p, &d_x, &d_W, seg, &d_out, stream_v);
+    return lora_model_forward_group(c, 0, 1, &p, &d_x, &d_W, seg, &d_out, stream_v);
 }
 
 lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
@@ -876,11 +899,11 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
 }
 
-lora_status lora_set_bias(lora_ctx* c, int32_t proj, const void* d_bias)
+lora_status lora_set_bias(lora_ctx* c, int32_t layer, int32_t proj, const void* d_bias)
 {
-    if (!c || proj < 0 || proj >= c->cfg.n_proj) return LORA_ERR_INVALID_ARG;
+    if (!c || proj < 0 || proj >= c->cfg.n_proj || layer < 0 || layer >= c->n_layers) return LORA_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(d_bias) & 15) return LORA_ERR_INVALID_ARG;
-    c->bias[proj] = static_cast<const uint16_t*>(d_bias);
+    c->bias[(size_t)layer * c->cfg.n_proj + proj] = static_cast<const uint16_t*>(d_bias);
     return LORA_OK;
 }
 

@@ -12,6 +12,7 @@ constexpr int kPieceRows = 32;       // grouped rows are cut into pieces that ne
 constexpr int kBK = 64;              // K extent of one LDS tile (bf16 elements)
 constexpr int kMaxSlots = 4095;
 constexpr int kMaxProj = 16;
+constexpr int kMaxLayers = 256;
 constexpr int kMaxRank = 64;
 constexpr int kMetaBatch = 16;       // slot-metadata updates carried by one kernel launch
 constexpr int kSplitMaxTokens = 1024;// largest T served by the split-K path

@@ -25,6 +25,26 @@ def bf16_tensor_to_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def packed_groups(w: Workload) -> List[List[int]]:
+    """Projections a decoder layer computes from one input side by side: q|k|v and gate|up."""
+    names = list(w.proj_names)
+    groups, used = [], set()
+    for fam in (("q", "k", "v"), ("gate", "up")):
+        g = [names.index(nm) for nm in fam if nm in names]
+        if len(g) > 1 and len({w.proj[p][0] for p in g}) == 1:
+            groups.append(g)
+            used.update(g)
+    out = []
+    for p in range(len(names)):
+        if p in used:
+            g = next(g for g in groups if p in g)
+            if g[0] == p:
+                out.append(g)
+        else:
+            out.append([p])
+    return out
+
+
 class Session:
     def __init__(self, w: Workload, path: int = B.LORA_PATH_AUTO, split_k: int = 0, device: str = "cuda:0",
                  max_tokens: Optional[int] = None, upload_inputs: bool = True):
@@ -119,23 +139,7 @@ class Session:
         return [self.out[p] for p in ps]
 
     def packed_groups(self) -> List[List[int]]:
-        """Projections a decoder layer computes from one input side by side: q|k|v and gate|up."""
-        names = list(self.w.proj_names)
-        groups, used = [], set()
-        for fam in (("q", "k", "v"), ("gate", "up")):
-            g = [names.index(nm) for nm in fam if nm in names]
-            if len(g) > 1 and len({self.w.proj[p][0] for p in g}) == 1:
-                groups.append(g)
-                used.update(g)
-        out = []
-        for p in range(len(names)):
-            if p in used:
-                g = next(g for g in groups if p in g)
-                if g[0] == p:
-                    out.append(g)
-            else:
-                out.append([p])
-        return out
+        return packed_groups(self.w)
 
     def step(self, packed: bool = True) -> None:
         """One pass of the whole path: segment map + every projection (q|k|v and gate|up as packed calls)."""
@@ -166,6 +170,99 @@ class Session:
 
     def id2slot(self) -> np.ndarray:
         return np.array([B.lora_slot_of(self.ctx, i) for i in range(self.w.max_adapter_id + 1)], dtype=np.int32)
+
+    def close(self):
+        if self.ctx:
+            B.lora_destroy(self.ctx)
+            self.ctx = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class ModelSession:
+    """Whole-model harness: `layers` are the per-layer workloads of one step (workloads.model_layers), served by
+    one context with n_layers layers: one slot table, one segment map per step, a slot holds an adapter's matrices
+    of every layer.  Owns tensors and forwards to the C ABI; no arithmetic of the method happens here."""
+
+    def __init__(self, layers: Sequence[Workload], path: int = B.LORA_PATH_AUTO, split_k: int = 0,
+                 device: str = "cuda:0", n_slots: Optional[int] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
+        self.layers = list(layers)
+        w = self.w = self.layers[0]
+        for lw in self.layers:
+            assert lw.proj == w.proj and np.array_equal(lw.token_ids, w.token_ids)
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        cfg = B.make_config(w.proj, n_slots or w.n_slots, w.max_rank, max(w.T, 1), w.max_adapter_id, path=path,
+                            split_k=split_k, n_layers=len(self.layers))
+        nbytes = B.lora_slab_bytes(cfg)
+        if nbytes == 0:
+            raise B.LoraError(B.LORA_ERR_SHAPE, "lora_slab_bytes")
+        self.slab_bytes = nbytes
+        self.slab = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        cfg.slab = self.slab.data_ptr()
+        cfg.slab_bytes = nbytes
+        self.cfg = cfg
+        self.ctx = B.lora_create(cfg)
+        self.W = [[_bf16_tensor(m, self.device) for m in lw.W] for lw in self.layers]
+        self.x = [[_bf16_tensor(m, self.device) for m in lw.x] for lw in self.layers]
+        self.out = [[torch.empty((w.T, d_out), dtype=torch.bfloat16, device=self.device) for (_, d_out) in w.proj]
+                    for _ in self.layers]
+        self.bias = [[None if lw.bias_of(p) is None else _bf16_tensor(lw.bias_of(p), self.device)
+                      for p in range(len(w.proj))] for lw in self.layers]
+        for l, row in enumerate(self.bias):
+            for p, b in enumerate(row):
+                if b is not None:
+                    B.lora_set_bias(self.ctx, p, b.data_ptr(), layer=l)
+        self.ids = torch.from_numpy(w.token_ids).to(self.device)
+        self.groups = packed_groups(w)
+        self.pinned: Dict[int, dict] = {}
+        self.seg: Optional[B.lora_segments] = None
+
+    def pin_adapter(self, aid: int) -> dict:
+        if aid not in self.pinned:
+            a0 = self.w.adapters[aid]
+            ent = {"adapter_id": aid, "rank": a0.rank, "scale": a0.scale, "slot": -1}
+            if a0.rank > 0:
+                # layer-major: every projection of layer 0, then of layer 1, ...
+                ent["A_t"] = [_bf16_tensor(m, pin=True) for lw in self.layers for m in lw.adapters[aid].A]
+                ent["B_t"] = [_bf16_tensor(m, pin=True) for lw in self.layers for m in lw.adapters[aid].B]
+                ent["A_ptrs"] = [t.data_ptr() for t in ent["A_t"]]
+                ent["B_ptrs"] = [t.data_ptr() for t in ent["B_t"]]
+            self.pinned[aid] = ent
+        return self.pinned[aid]
+
+    def load(self, adapter_ids: Sequence[int], in_use: Sequence[int] = (), stream: Optional[torch.cuda.Stream] = None,
+             chunk: int = 64):
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        ids, res = list(adapter_ids), []
+        for i in range(0, len(ids), chunk):
+            res += B.lora_slots_load(self.ctx, [dict(self.pin_adapter(a)) for a in ids[i:i + chunk]], in_use, s)
+        return res
+
+    def bucket(self, stream: Optional[torch.cuda.Stream] = None) -> B.lora_segments:
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        self.seg = B.lora_bucket(self.ctx, self.ids.data_ptr() if self.ids.numel() else 0, int(self.ids.numel()),
+                                 self.w.mode, s)
+        return self.seg
+
+    def forward_layer(self, l: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        for g in self.groups:
+            B.lora_model_forward_group(self.ctx, l, g, [self.x[l][p].data_ptr() for p in g],
+                                       [self.W[l][p].data_ptr() for p in g], self.seg,
+                                       [self.out[l][p].data_ptr() for p in g], s)
+
+    def step(self, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """One step of the whole model: one segment map, then every layer's projections."""
+        self.bucket(stream)
+        for l in range(len(self.layers)):
+            self.forward_layer(l, stream)
 
     def close(self):
         if self.ctx:

@@ -284,6 +284,25 @@ def qwen_decode(shrink: int = 1, n_tokens: int = 256, mode: int = BUCKET_SORTED)
     return w
 
 
+def model_layers(base: Workload, n_layers: int) -> List[Workload]:
+    """The step of `base` seen by n_layers decoder layers of one model: the same tokens, adapter ids, ranks, scales,
+    resident / missing sets and bias pattern in every layer; each layer draws its own W, x, adapter matrices
+    (and bias values) from a seed of its own.  Layer 0 is `base` itself."""
+    layers = [base]
+    ranks = {aid: a.rank for aid, a in base.adapters.items()}
+    scales = {aid: a.scale for aid, a in base.adapters.items()}
+    for l in range(1, n_layers):
+        w = custom(f"{base.name}_layer{l}", base.seed + 7919 * l, base.proj, base.proj_names, base.n_slots,
+                   base.max_rank, base.mode, base.token_ids, ranks, base.resident, base.missing, scales,
+                   base.request_lens)
+        if base.bias:
+            brng = np.random.default_rng(2000 + base.seed + 7919 * l)
+            w.bias = [None if b is None else to_bf16_bits(brng.standard_normal(b.shape[0]).astype(np.float32))
+                      for b in base.bias]
+        layers.append(w)
+    return layers
+
+
 def by_index(i: int, **kw) -> Workload:
     return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}[i](**kw)
 

@@ -176,3 +176,31 @@ def test_bias_argument_errors():
             assert e.value.status == B.LORA_ERR_INVALID_ARG
     finally:
         B.lora_destroy(ctx)
+
+
+def test_layers_in_the_config():
+    proj = ((4096, 4096), (4096, 1024))
+    per_layer = 32 * 32 * sum(a + b for a, b in proj) * 2           # one layer's share of the slot region
+    one = B.lora_slab_bytes(B.make_config(proj, 32, 32, 256, 31, n_layers=1))
+    assert B.lora_slab_bytes(B.make_config(proj, 32, 32, 256, 31, n_layers=0)) == one     # 0 is read as 1
+    four = B.lora_slab_bytes(B.make_config(proj, 32, 32, 256, 31, n_layers=4))
+    assert abs((four - one) - 3 * per_layer) <= 4096                  # scratch does not grow with the layers
+    assert B.lora_slab_bytes(B.make_config(proj, 32, 32, 256, 31, n_layers=257)) == 0
+    assert B.lora_slab_bytes(B.make_config(proj, 32, 32, 256, 31, n_layers=-1)) == 0
+    # layer arguments of the calls that take one
+    cfg = B.make_config(((64, 64),), 3, 32, 16, 63, flags=B.LORA_CREATE_HOST_ONLY, n_layers=2)
+    ctx = B.lora_create(cfg)
+    try:
+        B.lora_set_bias(ctx, 0, 4096, layer=1)
+        for layer in (-1, 2):
+            with pytest.raises(B.LoraError) as e:
+                B.lora_set_bias(ctx, 0, 4096, layer=layer)
+            assert e.value.status == B.LORA_ERR_INVALID_ARG
+            with pytest.raises(B.LoraError) as e:
+                B.lora_model_forward_group(ctx, layer, [0], [16], [16], B.lora_segments(), [16])
+            assert e.value.status == B.LORA_ERR_INVALID_ARG
+        # the slot table is one for all layers: a load names the adapter once
+        assert B.lora_slots_load(ctx, [dict(adapter_id=5, rank=8, scale=1.0)]) == [(0, True)]
+        assert B.lora_slot_of(ctx, 5) == 0
+    finally:
+        B.lora_destroy(ctx)
