@@ -100,7 +100,10 @@ typedef struct {
 /* One adapter to make resident.  A[p] / B[p]: pinned host, row-major bf16, A[p] is
  * [rank, d_in_p], B[p] is [d_out_p, rank]; they must stay valid and unchanged until the copy
  * stream has passed the call.  With n_layers > 1 the arrays hold n_layers * n_proj pointers,
- * layer-major: A[layer * n_proj + p].  rank must be 0 or a multiple of 8 (<= max_rank); rank 0 needs no
+ * layer-major: A[layer * n_proj + p].  Inside its slot an adapter is stored packed at its own
+ * rank in the order A[0], B[0], A[1], B[1], ...: matrices that follow each other in that order
+ * in host memory too (an adapter kept as one buffer) travel as one copy per projection, or per
+ * layer when n_layers > 1.  rank must be 0 or a multiple of 8 (<= max_rank); rank 0 needs no
  * A/B.  slot: in, >= 0 = explicit slot, -1 = the library picks (an empty slot, else the least
  * recently used one); out = slot used.  copied: out, 1 if weights were copied, 0 if the adapter
  * was already resident (touch only). */
@@ -145,13 +148,17 @@ lora_status lora_destroy(lora_ctx *ctx);
  * into the GPU's adapter region; load time grows with adapter size, unloading is free).
  * in_use / n_in_use (host): adapter ids of the batch about to run; they are marked used now and
  * are never chosen as victims.  The whole call is planned on the host first: on any error
- * nothing is enqueued and the table is unchanged.  On success the copies (one kernel launch per
- * projection, reading the page-locked host buffers directly; a source that is not page-locked,
- * device-visible host memory is copied with hipMemcpyAsync instead), the slot metadata update
- * and the id->slot map update are enqueued on copy_stream; later
- * lora_bucket / lora_layer_forward calls on other streams wait for them through events, and
- * the copies themselves wait for forward work already enqueued (a slot is never overwritten
- * while an earlier step may still read it).
+ * nothing is enqueued and the table is unchanged.  On success the slot metadata update, the
+ * id->slot map update and the copies are enqueued on copy_stream, the copies projection after
+ * projection (layer after layer when n_layers > 1) with one event each.  Runs travel in launches
+ * of a kernel that reads the page-locked host buffers directly, or, when n_layers > 1 and every
+ * run of the call is at least 1 MiB, through the copy engine, which keeps its rate while forward
+ * kernels occupy the compute units (LORA_TUNE_COPY_ENGINE overrides the choice; a source that is not
+ * page-locked, device-visible host memory is always copied with hipMemcpyAsync).  Later
+ * lora_bucket / lora_layer_forward calls on other streams wait through those events, each
+ * forward only for the copies of its own projection (layer), and the copies themselves wait
+ * for forward work already enqueued (a slot is never overwritten while an earlier step may
+ * still read it).
  * Errors: INVALID_ARG, ID_RANGE, SLOT_RANGE, RANK_EXCEEDS_SMAX, SHAPE (rank not a multiple of
  * 8), SLOTS_EXHAUSTED, HIP. */
 lora_status lora_slots_load(lora_ctx *ctx, int32_t n, lora_adapter_desc *descs,
@@ -222,7 +229,14 @@ int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter i
  * unknown values fall back to it.  Every variant computes the same result to the same tolerance. */
 enum {
     LORA_TUNE_FUSED_VARIANT = 0, /* tile shape / wave layout of the fused GEMM */
-    LORA_TUNE_SPLIT_VARIANT = 1  /* tile shape / wave layout of the split-K GEMM */
+    LORA_TUNE_SPLIT_VARIANT = 1, /* tile shape / wave layout of the split-K GEMM */
+    LORA_TUNE_COPY_ENGINE = 2    /* what carries an adapter's matrices into its slot (lora_slots_load) */
+};
+/* Values of LORA_TUNE_COPY_ENGINE. */
+enum {
+    LORA_COPY_AUTO = 0,   /* the copy engine for whole-layer runs of at least 1 MiB (n_layers > 1), else the kernel */
+    LORA_COPY_KERNEL = 1, /* a kernel that reads the pinned host memory, a batch of runs per launch */
+    LORA_COPY_ENGINE = 2  /* hipMemcpyAsync per run */
 };
 /* Values of LORA_TUNE_FUSED_VARIANT: tile (rows x columns x K tile), wavefronts per workgroup. */
 enum {

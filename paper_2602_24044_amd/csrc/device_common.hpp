@@ -147,7 +147,7 @@ __device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_piec
 
     const bool x_ok = i < nrows;
     const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
-    const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + sl.a_off;
+    const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + (size_t)r * sl.a_unit;
     const bool a0_ok = i < r, a1_ok = (32 + i) < r;
     const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
     const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
@@ -271,7 +271,7 @@ __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 // ---------------------------------------------------------------------------------------------------
 template <int MB, int NB, int D>
 __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB], int n_first,
-                                      int N, const DeviceView& dv, size_t b_off, const uint16_t* sV)
+                                      int N, const DeviceView& dv, size_t b_unit, const uint16_t* sV)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
@@ -304,7 +304,7 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int n = n_first + nb * 32 + i;
-            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + b_off + (size_t)n * q.r;
+            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + ((size_t)q.r * b_unit + (size_t)n * q.r);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const int k = ks * 16 + h * 8;

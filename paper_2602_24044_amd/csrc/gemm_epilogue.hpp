@@ -144,7 +144,7 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
 #pragma unroll
             for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_off, sV);
+        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_unit, sV);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     store_windows<MB, NB>(acc, a, sl, m_first, n_first, mine);
@@ -197,7 +197,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
                     ps[w] = slot[p * WB + w];
                     pr[w] = rank[p * WB + w];
                 }
-                expand_windows<WB, NB, (MB > 2 ? 2 : 3)>(pair, ps, pr, n_first, N, a.dv, sl.b_off, sV);
+                expand_windows<WB, NB, (MB > 2 ? 2 : 3)>(pair, ps, pr, n_first, N, a.dv, sl.b_unit, sV);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the piece is reused
             }
             store_windows<WB, NB>(pair, a, sl, m_first + p * WB * 32, n_first, mine);

@@ -4,6 +4,7 @@
 #include "lora_internal.hpp"
 
 #include <algorithm>
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <string>
@@ -25,11 +26,17 @@ inline bool hip_fail(hipError_t e, const char* what)
 #define HIP_FAIL(call) hip_fail((call), #call)
 
 constexpr size_t kAlign = 256;
+constexpr size_t kEngineRunBytes = 1u << 20;   // shortest run for which a copy call per run pays
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t slot_stride_elems = 0;          // bf16 elements per slot
-    std::vector<size_t> a_off, b_off;      // [n_layers * n_proj] element offsets inside a slot (layer-major)
+    // An adapter sits in its slot packed at its own rank r: layer after layer, per layer the A [r, d_in] and
+    // B [d_out, r] of every projection back to back.  a_unit / b_unit [n_layers * n_proj]: elements in front of
+    // that matrix per unit of rank (its offset inside the slot is r times that), so one adapter is one run of
+    // r * unit_total elements at the start of its slot, whatever its rank.
+    std::vector<size_t> a_unit, b_unit;
+    size_t unit_total = 0;
     size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
     size_t off_row_rank = 0, off_row_scale = 0;
     size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
@@ -101,19 +108,19 @@ Layout make_layout(const lora_config* c)
     size_t e = 0;
     int k_max = 0;
     const int n_layers = std::max(1, c->n_layers);
-    L.a_off.resize((size_t)n_layers * c->n_proj);
-    L.b_off.resize((size_t)n_layers * c->n_proj);
-    // a slot holds one adapter of the whole model: layer after layer, per layer the A and B of every projection
+    L.a_unit.resize((size_t)n_layers * c->n_proj);
+    L.b_unit.resize((size_t)n_layers * c->n_proj);
     for (int l = 0; l < n_layers; ++l)
         for (int p = 0; p < c->n_proj; ++p) {
             const size_t f = (size_t)l * c->n_proj + p;
-            L.a_off[f] = e;
-            e += (size_t)c->max_rank * c->proj[p].d_in;
-            L.b_off[f] = e;
-            e += (size_t)c->max_rank * c->proj[p].d_out;
+            L.a_unit[f] = e;
+            e += (size_t)c->proj[p].d_in;
+            L.b_unit[f] = e;
+            e += (size_t)c->proj[p].d_out;
             k_max = std::max(k_max, c->proj[p].d_in);
         }
-    L.slot_stride_elems = align_up(e * 2, kAlign) / 2;
+    L.unit_total = e;
+    L.slot_stride_elems = align_up(e * (size_t)c->max_rank * 2, kAlign) / 2;
     const size_t Tm = (size_t)c->max_tokens;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, kAlign); return at; };
@@ -172,10 +179,12 @@ struct lora_ctx {
 
     // stream ordering
     hipEvent_t ev_meta = nullptr, ev_fwd = nullptr;
-    std::vector<hipEvent_t> ev_proj;        // [n_layers * n_proj]: copies of that layer's projection enqueued
+    // copies are enqueued in units (a projection; a whole layer when there are several layers), one event each
+    std::vector<hipEvent_t> ev_unit;
     bool meta_pending = false;
-    std::vector<char> proj_pending;         // [n_layers * n_proj]
+    std::vector<char> unit_pending;
     int n_layers = 1;
+    int unit_of(int layer, int proj) const { return n_layers > 1 ? layer : proj; }
     hipStream_t copy_stream = nullptr;      // stream of the latest load
     hipStream_t last_fwd_stream = nullptr;
     bool have_fwd = false;
@@ -302,8 +311,9 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
     c->host_only = (cfg->flags & LORA_CREATE_HOST_ONLY) != 0;
     c->n_layers = std::max(1, cfg->n_layers);
     const size_t n_flat = (size_t)c->n_layers * cfg->n_proj;
-    c->ev_proj.assign(n_flat, nullptr);
-    c->proj_pending.assign(n_flat, 0);
+    const size_t n_units = c->n_layers > 1 ? (size_t)c->n_layers : (size_t)cfg->n_proj;
+    c->ev_unit.assign(n_units, nullptr);
+    c->unit_pending.assign(n_units, 0);
     c->bias.assign(n_flat, nullptr);
     c->slot_adapter.assign(cfg->n_slots, -1);
     c->slot_rank_h.assign(cfg->n_slots, 0);
@@ -323,8 +333,8 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
         c->base = static_cast<char*>(cfg->slab);
         bool ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming)) &&
                   !HIP_FAIL(hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming));
-        for (size_t f = 0; ok && f < n_flat; ++f)
-            ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_proj[f], hipEventDisableTiming));
+        for (size_t u = 0; ok && u < n_units; ++u)
+            ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_unit[u], hipEventDisableTiming));
         ok = ok && !HIP_FAIL(launch_fill_i32(c->d_slot_rank(), 0, cfg->n_slots, nullptr));
         ok = ok && !HIP_FAIL(launch_fill_i32(reinterpret_cast<int32_t*>(c->d_slot_scale()), 0, cfg->n_slots, nullptr));
         ok = ok && !HIP_FAIL(launch_fill_i32(c->d_id2slot(), -1, (size_t)cfg->max_adapter_id + 1, nullptr));
@@ -348,7 +358,7 @@ lora_status lora_destroy(lora_ctx* c)
         (void)hipDeviceSynchronize();
         if (c->ev_meta) (void)hipEventDestroy(c->ev_meta);
         if (c->ev_fwd) (void)hipEventDestroy(c->ev_fwd);
-        for (hipEvent_t e : c->ev_proj)
+        for (hipEvent_t e : c->ev_unit)
             if (e) (void)hipEventDestroy(e);
         for (auto& s : c->prof_pool) {
             (void)hipEventDestroy(s.beg);
@@ -495,14 +505,55 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     }
     if (HIP_FAIL(hipEventRecord(c->ev_meta, cs))) return LORA_ERR_HIP;
     c->meta_pending = true;
-    // Layer after layer, so that a forward pass running behind the copies can start on the first layers while
-    // the later ones still travel.  The matrices of one projection travel in one launch of a kernel that reads the pinned host memory itself
-    // (a hipMemcpyAsync per matrix costs the host and the copy engine about as much as the matrix's transfer);
-    // a source that is not device-visible pinned host memory goes through hipMemcpyAsync.
+    // The copies go out in units, in order: a unit is one projection, or one whole layer when the context holds
+    // several layers (a forward pass running behind the copies can then start on the first layers while later
+    // ones still travel); one event per unit.  Inside a slot an adapter's matrices follow each other without
+    // gaps, so matrices that also follow each other in host memory travel as one run.
+    // Two carriers.  A kernel that reads the pinned host memory itself, a batch of runs per launch: the faster
+    // one on an idle GPU and for short runs (a copy call per run costs the host and the engine about 10 us), but
+    // its workgroups find no free compute unit while forward kernels run.  The copy engine (hipMemcpyAsync per
+    // run): needs no compute unit, so a load in the shadow of a running step keeps its rate.  Unless told
+    // otherwise the engine carries the loads of a context with several layers whose runs all reach
+    // kEngineRunBytes (whole layers of an adapter kept as one host buffer), the kernel everything else; a source
+    // that is not device-visible pinned host memory always goes through hipMemcpyAsync.
     char* slots = c->base + c->L.off_slots;
-    for (int f = 0; f < n_proj * c->n_layers; ++f) {
-        const int p = f % n_proj;
-        const size_t d_in = c->proj[p].d_in, d_out = c->proj[p].d_out;
+    const bool by_layer = c->n_layers > 1;
+    const int n_units = by_layer ? c->n_layers : n_proj;
+    struct Run { const char* src; char* dst; size_t bytes; };
+    std::vector<std::vector<Run>> unit_runs(n_units);
+    size_t shortest = SIZE_MAX;
+    for (int u = 0; u < n_units; ++u) {
+        const int f_begin = by_layer ? u * n_proj : u, f_end = by_layer ? (u + 1) * n_proj : u + 1;
+        std::vector<Run>& runs = unit_runs[u];
+        for (int i = 0; i < n; ++i) {
+            if (!out_copied[i] || descs[i].rank <= 0) continue;
+            const size_t r = descs[i].rank;
+            char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
+            const size_t first = runs.size();
+            auto add = [&](const void* src, size_t dst_elems, size_t bytes) {
+                const char* sp = static_cast<const char*>(src);
+                char* dp = slot_base + dst_elems * 2;
+                if (runs.size() > first) {
+                    Run& last = runs.back();
+                    if (sp == last.src + last.bytes && dp == last.dst + last.bytes && last.bytes + bytes <= 0xffffffffu) {
+                        last.bytes += bytes;
+                        return;
+                    }
+                }
+                runs.push_back(Run{sp, dp, bytes});
+            };
+            for (int f = f_begin; f < f_end; ++f) {
+                const int p = f % n_proj;
+                add(descs[i].A[f], r * c->L.a_unit[f], r * (size_t)c->proj[p].d_in * 2);
+                add(descs[i].B[f], r * c->L.b_unit[f], r * (size_t)c->proj[p].d_out * 2);
+            }
+        }
+        for (const Run& r : runs) shortest = std::min(shortest, r.bytes);
+    }
+    const int tuned = c->tune[LORA_TUNE_COPY_ENGINE];
+    const bool engine = tuned == LORA_COPY_ENGINE ||
+                        (tuned != LORA_COPY_KERNEL && by_layer && shortest >= kEngineRunBytes);
+    for (int u = 0; u < n_units; ++u) {
         CopyBatch batch;
         batch.n = 0;
         auto flush = [&]() -> bool {
@@ -510,27 +561,22 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             batch.n = 0;
             return true;
         };
-        auto enqueue = [&](void* dst, const void* src, size_t bytes) -> bool {
-            const void* dev_src = device_view_of_pinned(src);
-            if (!dev_src || bytes % 16 || bytes > 0xffffffffu || (reinterpret_cast<uintptr_t>(src) & 15))
-                return !HIP_FAIL(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, cs));
-            if (batch.n == kCopyBatch && !flush()) return false;
+        for (const Run& r : unit_runs[u]) {
+            const void* dev_src = engine ? nullptr : device_view_of_pinned(r.src);
+            const bool kernel_ok = dev_src && r.bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(r.src) & 15) == 0;
+            if (!kernel_ok) {
+                if (HIP_FAIL(hipMemcpyAsync(r.dst, r.src, r.bytes, hipMemcpyHostToDevice, cs))) return LORA_ERR_HIP;
+                continue;
+            }
+            if (batch.n == kCopyBatch && !flush()) return LORA_ERR_HIP;
             batch.src[batch.n] = dev_src;
-            batch.dst[batch.n] = dst;
-            batch.bytes[batch.n] = (uint32_t)bytes;
+            batch.dst[batch.n] = r.dst;
+            batch.bytes[batch.n] = (uint32_t)r.bytes;
             ++batch.n;
-            return true;
-        };
-        for (int i = 0; i < n; ++i) {
-            if (!out_copied[i] || descs[i].rank <= 0) continue;
-            const size_t r = descs[i].rank;
-            char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
-            if (!enqueue(slot_base + c->L.a_off[f] * 2, descs[i].A[f], r * d_in * 2)) return LORA_ERR_HIP;
-            if (!enqueue(slot_base + c->L.b_off[f] * 2, descs[i].B[f], d_out * r * 2)) return LORA_ERR_HIP;
         }
         if (!flush()) return LORA_ERR_HIP;
-        if (HIP_FAIL(hipEventRecord(c->ev_proj[f], cs))) return LORA_ERR_HIP;
-        c->proj_pending[f] = 1;
+        if (HIP_FAIL(hipEventRecord(c->ev_unit[u], cs))) return LORA_ERR_HIP;
+        c->unit_pending[u] = 1;
     }
     c->copy_stream = cs;
     return LORA_OK;
@@ -616,9 +662,9 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
     }
     hipStream_t s = static_cast<hipStream_t>(stream_v);
     for (int k = 0; k < n; ++k) {
-        const int f = flat0 + projs[k];
-        if (c->proj_pending[f] && s != c->copy_stream) {
-            if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_proj[f], 0))) return LORA_ERR_HIP;
+        const int u = c->unit_of(layer, projs[k]);
+        if (c->unit_pending[u] && s != c->copy_stream && (k == 0 || u != c->unit_of(layer, projs[k - 1]))) {
+            if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_unit[u], 0))) return LORA_ERR_HIP;
         }
     }
     const int K = c->proj[projs[0]].d_in;
@@ -727,8 +773,8 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
         sl.W = static_cast<const uint16_t*>(d_W[k]);
         sl.out = static_cast<uint16_t*>(d_out[k]);
         sl.vpart = vpart + vslice * k;
-        sl.a_off = c->L.a_off[flat0 + p];
-        sl.b_off = c->L.b_off[flat0 + p];
+        sl.a_unit = c->L.a_unit[flat0 + p];
+        sl.b_unit = c->L.b_unit[flat0 + p];
         sl.bias = c->bias[flat0 + p];
         sl.N = c->proj[p].d_out;
         sl.tile0 = 0;

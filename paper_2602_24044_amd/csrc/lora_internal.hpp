@@ -92,8 +92,8 @@ struct Slice {
     const uint16_t* W;   // [N, K] bf16
     uint16_t* out;       // [T, N] bf16
     float* vpart;        // [n_kc][T][max_rank] fp32: this slice's shrink results
-    size_t a_off;        // element offsets of this projection's A and B inside a slot
-    size_t b_off;
+    size_t a_unit;       // elements in front of this projection's A and B inside a slot, per unit of the rank of
+    size_t b_unit;       // the adapter in it (the adapter is stored packed at its own rank)
     int32_t N;
     int32_t tile0;       // first N tile of the slice (set by the GEMM launcher for its tile width)
     int32_t blk0;        // first 32-column block of the slice in the packed partial matrix (multiple of 4)
@@ -108,7 +108,7 @@ struct GroupArgs {
 
 struct ShrinkArgs {
     DeviceView dv;
-    GroupArgs g;         // x, a_off and vpart of every slice
+    GroupArgs g;         // x, a_unit and vpart of every slice
     int32_t K;
     int32_t n_kc;        // K chunks (one partial result each)
     int32_t kc_len;      // K extent of a chunk (multiple of 64); the waves of a workgroup share a chunk

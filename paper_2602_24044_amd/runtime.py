@@ -21,6 +21,26 @@ def _bf16_tensor(bits: np.ndarray, device=None, pin: bool = False) -> torch.Tens
     return t.view(torch.bfloat16)
 
 
+def pin_matrices(A: Sequence[np.ndarray], B: Sequence[np.ndarray], packed: bool) -> dict:
+    """Page-locked host copies of an adapter's matrices (bf16 bits), A[k] / B[k] in the order the library takes them.
+    packed: one buffer holding A[0], B[0], A[1], B[1], ... back to back (the order inside a slot: the load then
+    moves whole runs); otherwise one buffer per matrix."""
+    if not packed:
+        A_t = [_bf16_tensor(m, pin=True) for m in A]
+        B_t = [_bf16_tensor(m, pin=True) for m in B]
+        return {"keep": A_t + B_t, "A_ptrs": [t.data_ptr() for t in A_t], "B_ptrs": [t.data_ptr() for t in B_t]}
+    n_el = sum(a.size + b.size for a, b in zip(A, B))
+    buf = torch.empty(n_el, dtype=torch.int16, pin_memory=True)
+    view = buf.numpy()
+    A_ptrs, B_ptrs, off = [], [], 0
+    for a, b in zip(A, B):
+        for m, ptrs in ((a, A_ptrs), (b, B_ptrs)):
+            view[off:off + m.size] = np.ascontiguousarray(m).view(np.int16).reshape(-1)
+            ptrs.append(buf.data_ptr() + 2 * off)
+            off += m.size
+    return {"keep": [buf], "A_ptrs": A_ptrs, "B_ptrs": B_ptrs}
+
+
 def bf16_tensor_to_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
@@ -47,10 +67,11 @@ def packed_groups(w: Workload) -> List[List[int]]:
 
 class Session:
     def __init__(self, w: Workload, path: int = B.LORA_PATH_AUTO, split_k: int = 0, device: str = "cuda:0",
-                 max_tokens: Optional[int] = None, upload_inputs: bool = True):
+                 max_tokens: Optional[int] = None, upload_inputs: bool = True, packed_host: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
         self.w = w
+        self.packed_host = packed_host
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.max_tokens = int(max_tokens or max(w.T, 1))
@@ -91,10 +112,7 @@ class Session:
             a = self.w.adapters[aid]
             ent = {"adapter_id": aid, "rank": a.rank, "scale": a.scale, "slot": -1}
             if a.rank > 0:
-                ent["A_t"] = [_bf16_tensor(m, pin=True) for m in a.A]
-                ent["B_t"] = [_bf16_tensor(m, pin=True) for m in a.B]
-                ent["A_ptrs"] = [t.data_ptr() for t in ent["A_t"]]
-                ent["B_ptrs"] = [t.data_ptr() for t in ent["B_t"]]
+                ent.update(pin_matrices(a.A, a.B, self.packed_host))
             self.pinned[aid] = ent
         return self.pinned[aid]
 
@@ -189,10 +207,11 @@ class ModelSession:
     of every layer.  Owns tensors and forwards to the C ABI; no arithmetic of the method happens here."""
 
     def __init__(self, layers: Sequence[Workload], path: int = B.LORA_PATH_AUTO, split_k: int = 0,
-                 device: str = "cuda:0", n_slots: Optional[int] = None):
+                 device: str = "cuda:0", n_slots: Optional[int] = None, packed_host: bool = True):
         if not torch.cuda.is_available():
             raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
         self.layers = list(layers)
+        self.packed_host = packed_host
         w = self.w = self.layers[0]
         for lw in self.layers:
             assert lw.proj == w.proj and np.array_equal(lw.token_ids, w.token_ids)
@@ -230,10 +249,8 @@ class ModelSession:
             ent = {"adapter_id": aid, "rank": a0.rank, "scale": a0.scale, "slot": -1}
             if a0.rank > 0:
                 # layer-major: every projection of layer 0, then of layer 1, ...
-                ent["A_t"] = [_bf16_tensor(m, pin=True) for lw in self.layers for m in lw.adapters[aid].A]
-                ent["B_t"] = [_bf16_tensor(m, pin=True) for lw in self.layers for m in lw.adapters[aid].B]
-                ent["A_ptrs"] = [t.data_ptr() for t in ent["A_t"]]
-                ent["B_ptrs"] = [t.data_ptr() for t in ent["B_t"]]
+                ent.update(pin_matrices([m for lw in self.layers for m in lw.adapters[aid].A],
+                                        [m for lw in self.layers for m in lw.adapters[aid].B], self.packed_host))
             self.pinned[aid] = ent
         return self.pinned[aid]
 

@@ -26,12 +26,19 @@ def _check_all(ms, outs=None, ids=None):
     return worst
 
 
-@pytest.mark.parametrize("path", [B.LORA_PATH_AUTO, B.LORA_PATH_FUSED, B.LORA_PATH_SPLITK])
-def test_every_layer_reads_its_own_part_of_the_slots(path):
+@pytest.mark.parametrize("path,engine,packed_host", [
+    (B.LORA_PATH_AUTO, B.LORA_COPY_AUTO, True), (B.LORA_PATH_FUSED, B.LORA_COPY_KERNEL, True),
+    (B.LORA_PATH_SPLITK, B.LORA_COPY_ENGINE, True), (B.LORA_PATH_AUTO, B.LORA_COPY_AUTO, False),
+    (B.LORA_PATH_AUTO, B.LORA_COPY_ENGINE, False)])
+def test_every_layer_reads_its_own_part_of_the_slots(path, engine, packed_host):
+    # an adapter kept as one host buffer travels as one run per layer, one kept matrix by matrix as many; by the
+    # copy engine, by the copy kernel, or by whichever the run lengths select
     layers = wl.model_layers(wl.qwen_decode(shrink=8, n_tokens=150), 3)      # with the q, k, v bias of that family
-    announce(f"model step {layers[0].name} layers={len(layers)} T={layers[0].T} path={path}")
-    ms = ModelSession(layers, path=path)
+    announce(f"model step {layers[0].name} layers={len(layers)} T={layers[0].T} path={path} engine={engine} "
+             f"packed_host={packed_host}")
+    ms = ModelSession(layers, path=path, packed_host=packed_host)
     try:
+        B.lora_set_tuning(ms.ctx, B.LORA_TUNE_COPY_ENGINE, engine)
         ms.load(layers[0].resident)
         ms.step()
         torch.cuda.synchronize()

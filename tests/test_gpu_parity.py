@@ -62,6 +62,29 @@ def test_qwen_shapes_prefill_runs_reduced():
     run_and_check(w, path=B.LORA_PATH_AUTO, packed=True)
 
 
+@pytest.mark.parametrize("engine", [B.LORA_COPY_AUTO, B.LORA_COPY_KERNEL, B.LORA_COPY_ENGINE])
+@pytest.mark.parametrize("packed_host", [False, True])
+def test_adapter_copies_by_engine_kernel_and_host_layout(engine, packed_host):
+    # mixed ranks below S_max: the adapters sit packed at their own rank in their slots; loads with evictions
+    w = wl.config5(shrink=8, prefill_len=300, n_decode=100, population=40, n_slots=32, n_missing=6)
+    announce(f"copies {w.name} engine={engine} packed_host={packed_host}")
+    s = Session(w, packed_host=packed_host)
+    try:
+        B.lora_set_tuning(s.ctx, B.LORA_TUNE_COPY_ENGINE, engine)
+        s.load(w.resident)
+        s.load(w.missing, in_use=w.distinct_adapters())
+        s.bucket()
+        assert check_segments(s, w) == 0
+        for g in s.packed_groups():
+            s.forward_group(g) if len(g) > 1 else s.forward(g[0])
+        torch.cuda.synchronize()
+        for p in range(len(w.proj)):
+            y_ref = oracle.project(w.x[p], w.W[p], w.token_ids, oracle.adapters_of(w, p))
+            assert rel_err(bf16_tensor_to_bits(s.out[p]), y_ref) <= TOL
+    finally:
+        s.close()
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_bias_is_added_and_can_be_removed(path):
     # the q, k, v projections of the Qwen2.5 family have a bias: added before the rounding, for rows with and

@@ -54,3 +54,12 @@ def test_additive_fit_recovers_exact_constants():
     assert r["c_B"] == pytest.approx(0.3) and r["c_0"] == pytest.approx(150.0)
     assert r["c_A"] == pytest.approx(0.5) and r["c_step"] == pytest.approx(20.0)
     assert r["max_rel_err"] < 1e-9
+
+
+def test_slot_region_bytes():
+    # one rank unit of a two-layer model with projections (64 -> 128) and (128 -> 64): 2 layers x 384 elements x 2 bytes
+    from paper_2602_24044_amd.model_step import slot_region_bytes
+    r = slot_region_bytes([(64, 128), (128, 64)], 2, [8, 16, 32, 8], 32, 3)
+    assert r["per_rank_unit"] == 2 * 2 * 384
+    assert r["uniform"] == 3 * 32 * 1536                 # A_max slots of the largest rank
+    assert r["packed"] == (8 + 16 + 32) * 1536           # the first A_max adapters at their own ranks
