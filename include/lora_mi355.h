@@ -50,7 +50,8 @@ typedef enum {
     LORA_ERR_SLOTS_EXHAUSTED = 6,  /* every slot is held by an adapter of the current batch */
     LORA_ERR_NOT_RESIDENT = 7,     /* reported by lora_poll_device_flags: a token named a non-resident adapter */
     LORA_ERR_HIP = 8,              /* a HIP runtime call failed (no device, bad stream, ...) */
-    LORA_ERR_ID_RANGE = 9          /* adapter id outside [0, max_adapter_id] */
+    LORA_ERR_ID_RANGE = 9,         /* adapter id outside [0, max_adapter_id] */
+    LORA_ERR_STARVATION = 10       /* lora_place_adapters: no starvation-free allocation on the GPUs given */
 } lora_status;
 
 /* Segment-map modes (lora_bucket). */
@@ -276,6 +277,30 @@ int32_t lora_last_launches(const lora_ctx *ctx, const char **names, int32_t cap)
 lora_status lora_profile_enable(lora_ctx *ctx, int32_t on);
 int32_t lora_profile_collect(lora_ctx *ctx, const char **names, double *total_ms, int64_t *counts, int32_t cap);
 lora_status lora_profile_reset(lora_ctx *ctx);
+
+/* Adapter placement over GPUs (paper Sec. 7, the greedy caching algorithm with its feasibility test).  Host
+ * code, no device access.  Input: for each of n_adapters its size (rank, > 0) and Poisson arrival rate
+ * (>= 0), and the number of GPUs.  The two predictors are the caller's: given the sizes and rates of all
+ * adapters that would share one GPU (n of them, in the order they were taken from the queue) and a configuration
+ * a_max, predict_throughput returns the expected throughput (any unit, only compared) and predict_starvation
+ * nonzero if requests would starve; `user` is handed through.  Adapters are taken in priority order (largest
+ * size first; inside one size by arrival rate alternating high and low; ties by index) and included in the open
+ * GPU provisionally; whenever that GPU's adapter count reaches one of 8 16 32 64 96 128 160 192 256 320 384 the
+ * provisional set is tested: the GPU's a_max becomes the better of its current value and the next value of that
+ * list (the next value outright while it has none), and if starvation is predicted for it the provisional set
+ * goes back to the queue and the GPU takes no more adapters.  What is still provisional at the end is tested
+ * once more.  Output: gpu_of[a] in [0, n_gpus) for every adapter, a_max_of[g] for every GPU (0: GPU unused).
+ * Errors: INVALID_ARG; STARVATION when an adapter finds no GPU left or the last test fails (outputs are then
+ * unspecified). */
+typedef double (*lora_throughput_fn)(void *user, int32_t n, const int32_t *sizes, const double *rates, int32_t a_max);
+typedef int32_t (*lora_starvation_fn)(void *user, int32_t n, const int32_t *sizes, const double *rates, int32_t a_max);
+lora_status lora_place_adapters(int32_t n_adapters, const int32_t *size, const double *rate, int32_t n_gpus,
+                                lora_throughput_fn predict_throughput, lora_starvation_fn predict_starvation,
+                                void *user, int32_t *gpu_of, int32_t *a_max_of);
+
+/* The priority order alone (paper Sec. 7, PrioritySorting): order_out[k] = index of the k-th adapter to place.
+ * Errors: INVALID_ARG. */
+lora_status lora_priority_sorting(int32_t n_adapters, const int32_t *size, const double *rate, int32_t *order_out);
 
 const char *lora_status_string(lora_status s);
 

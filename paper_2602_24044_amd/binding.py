@@ -51,6 +51,7 @@ LORA_ERR_SLOTS_EXHAUSTED = 6
 LORA_ERR_NOT_RESIDENT = 7
 LORA_ERR_HIP = 8
 LORA_ERR_ID_RANGE = 9
+LORA_ERR_STARVATION = 10
 LORA_BUCKET_SORTED = 0
 LORA_BUCKET_RUNS = 1
 LORA_PATH_AUTO = 0
@@ -64,7 +65,7 @@ EXPORTS = [
     "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group",
+    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
 ]
 LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
@@ -260,6 +261,49 @@ def lora_model_forward_group(ctx: int, layer: int, projs: Sequence[int], d_x: Se
     st = _lib.lora_model_forward_group(_P(ctx), int(layer), n, pa, xa, wa, ctypes.byref(seg), oa, _P(stream or None))
     if st != LORA_OK:
         raise LoraError(st, "lora_model_forward_group")
+
+
+THROUGHPUT_FN = ctypes.CFUNCTYPE(ctypes.c_double, _P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_double), ctypes.c_int32)
+STARVATION_FN = ctypes.CFUNCTYPE(ctypes.c_int32, _P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_double), ctypes.c_int32)
+_lib.lora_place_adapters.restype = ctypes.c_int
+_lib.lora_place_adapters.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
+                                     ctypes.c_int32, THROUGHPUT_FN, STARVATION_FN, _P,
+                                     ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+_lib.lora_priority_sorting.restype = ctypes.c_int
+_lib.lora_priority_sorting.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_int32)]
+
+
+def lora_priority_sorting(size: Sequence[int], rate: Sequence[float]) -> List[int]:
+    n = len(size)
+    sz = (ctypes.c_int32 * max(n, 1))(*[int(v) for v in size])
+    rt = (ctypes.c_double * max(n, 1))(*[float(v) for v in rate])
+    out = (ctypes.c_int32 * max(n, 1))()
+    st = _lib.lora_priority_sorting(n, sz, rt, out)
+    if st != LORA_OK:
+        raise LoraError(st, "lora_priority_sorting")
+    return [int(out[i]) for i in range(n)]
+
+
+def lora_place_adapters(size: Sequence[int], rate: Sequence[float], n_gpus: int, predict_throughput,
+                        predict_starvation) -> Tuple[List[int], List[int]]:
+    """predict_throughput(sizes, rates, a_max) -> float, predict_starvation(sizes, rates, a_max) -> bool, called
+    with the lists of one GPU's adapters.  Returns (gpu_of, a_max_of); raises LoraError (LORA_ERR_STARVATION)."""
+    n = len(size)
+    sz = (ctypes.c_int32 * max(n, 1))(*[int(v) for v in size])
+    rt = (ctypes.c_double * max(n, 1))(*[float(v) for v in rate])
+    gpu_of = (ctypes.c_int32 * max(n, 1))()
+    a_max_of = (ctypes.c_int32 * max(n_gpus, 1))()
+    thr = THROUGHPUT_FN(lambda user, k, s, r, p: float(predict_throughput([s[i] for i in range(k)],
+                                                                            [r[i] for i in range(k)], p)))
+    stv = STARVATION_FN(lambda user, k, s, r, p: int(bool(predict_starvation([s[i] for i in range(k)],
+                                                                              [r[i] for i in range(k)], p))))
+    st = _lib.lora_place_adapters(n, sz, rt, int(n_gpus), thr, stv, None, gpu_of, a_max_of)
+    if st != LORA_OK:
+        raise LoraError(st, "lora_place_adapters")
+    return [int(gpu_of[i]) for i in range(n)], [int(a_max_of[g]) for g in range(n_gpus)]
 
 
 def lora_poll_device_flags(ctx: int, stream: int = 0) -> Tuple[int, int]:

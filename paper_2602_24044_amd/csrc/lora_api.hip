@@ -280,6 +280,7 @@ const char* lora_status_string(lora_status s)
         case LORA_ERR_NOT_RESIDENT: return "token names a non-resident adapter";
         case LORA_ERR_HIP: return "HIP runtime error";
         case LORA_ERR_ID_RANGE: return "adapter id out of range";
+        case LORA_ERR_STARVATION: return "no starvation-free placement";
     }
     return "unknown status";
 }
