@@ -113,3 +113,32 @@ def test_argument_errors():
     with pytest.raises(B.LoraError) as e:                                      # an adapter and no GPU
         B.lora_place_adapters([8], [0.1], 0, *ok)
     assert e.value.status == B.LORA_ERR_STARVATION
+
+
+def test_placement_under_the_analytic_serving_model():
+    # the stand-in predictors built from the measured laws: sanity of the model and validity of what the greedy
+    # algorithm returns under it
+    from paper_2602_24044_amd.placement_model import ServingModel, place
+    m = ServingModel()
+    assert m.max_requests(32, 8) > m.max_requests(32, 384) > 0            # slots take memory from the KV cache
+    assert m.step_seconds(256, 32) > m.step_seconds(256, 1) > m.step_seconds(32, 1)
+    light, heavy = [0.1] * 16, [40.0] * 16
+    assert m.throughput([16] * 16, light, 16) == pytest.approx(m.incoming_token_rate(light))
+    assert not m.starvation([16] * 16, light, 16) and m.starvation([16] * 16, heavy, 16)
+    # fewer slots than adapters: loads cost step time once the GPU is the bottleneck
+    busy = [6.0] * 64
+    assert m.throughput([32] * 64, busy, 8) < m.throughput([32] * 64, busy, 64)
+    rng = np.random.default_rng(3)
+    n = 1500
+    size = [int(v) for v in rng.choice([8, 16, 32], size=n)]
+    rate = [float(v) for v in rng.choice([1.6, 0.8, 0.4, 0.1, 0.05, 0.025], size=n)]
+    gpu_of, a_max = place(size, rate, 32, m)
+    assert gpu_of == P.greedy(32, size, rate, m.throughput, m.starvation)[0]
+    used = max(gpu_of) + 1
+    assert 1 < used <= 32
+    for g in range(used):
+        mine = [a for a in range(n) if gpu_of[a] == g]
+        assert not m.starvation([size[a] for a in mine], [rate[a] for a in mine], a_max[g])
+    with pytest.raises(B.LoraError) as e:
+        place(size, rate, 1, m)
+    assert e.value.status == B.LORA_ERR_STARVATION
