@@ -84,3 +84,24 @@ def test_step_behind_a_load_on_another_stream():
         assert st == B.LORA_OK and word == 0
     finally:
         ms.close()
+
+
+def test_many_layers():
+    # 40 layers of small shapes: the last layers sit far into every slot; only the first, a middle and the last
+    # layer are compared (every layer is computed)
+    layers = wl.model_layers(wl.config2(shrink=16, n_tokens=96), 40)
+    announce(f"model step {layers[0].name} layers={len(layers)} T={layers[0].T}")
+    ms = ModelSession(layers)
+    try:
+        ms.load(layers[0].resident)
+        ms.step()
+        torch.cuda.synchronize()
+        for l in (0, 17, 39):
+            lw = layers[l]
+            for p in range(len(lw.proj)):
+                y_ref = oracle.project(lw.x[p], lw.W[p], lw.token_ids, oracle.adapters_of(lw, p))
+                assert rel_err(bf16_tensor_to_bits(ms.out[l][p]), y_ref) <= TOL, (l, p)
+        st, word = B.lora_poll_device_flags(ms.ctx)
+        assert st == B.LORA_OK and word == 0
+    finally:
+        ms.close()
