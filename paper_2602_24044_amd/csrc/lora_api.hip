@@ -261,6 +261,121 @@ struct LaunchScope {
     }
 };
 
+// What one forward call (a projection or a packed group over T tokens) launches: path, tile variant, K split and
+// the K chunks of the shrink.  Host arithmetic only.
+struct ForwardPlan {
+    int K = 0, Mpad = 0, n_max = 0;
+    long n_pad_total = 0;       // columns of all slices, each padded to a multiple of 128
+    bool split = false;         // split-K GEMM + reduce; otherwise shrink + fused GEMM
+    bool dyn_shrink = false;    // split path: a share of the workgroups only shrinks
+    int S = 1;                  // K split
+    int split_variant = 0;
+    int n_kc = 1, kc_len = 0;   // K chunks of the shrink and their length
+};
+
+lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t* projs, ForwardPlan& out)
+{
+    const int K = c->proj[projs[0]].d_in;
+    // the slices sit side by side along N, each padded to a multiple of 128 columns
+    long n_pad_total = 0;
+    int n_max = 0;
+    for (int k = 0; k < n; ++k) {
+        n_pad_total += (long)align_up((size_t)c->proj[projs[k]].d_out, 128);
+        n_max = std::max(n_max, c->proj[projs[k]].d_out);
+    }
+    auto tiles_of = [&](int bm, int bn) {
+        long t = 0;
+        for (int k = 0; k < n; ++k) t += (c->proj[projs[k]].d_out + bn - 1) / bn;
+        return t * ((T + bm - 1) / bm);
+    };
+
+    // ---- plan ----
+    const int Mpad = (T + 255) / 256 * 256;
+    bool split = false, dyn_shrink = false;
+    int S = 1;
+    int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
+    if (T <= kSplitMaxTokens) {
+        if (c->cfg.path == LORA_PATH_SPLITK) split = true;
+        else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < 128;
+    }
+    if (split) {
+        // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
+        // small batches walk K in 64-wide tiles (whole cache lines per row segment).  Narrow launches (k, v
+        // alone) fill the chip better with square 128 x 128 tiles, and so does a 4096-wide projection over a
+        // short K at up to 256 tokens (half the K splits, half the partial tiles)
+        // and up to 128 tokens a 256-row tile would copy and multiply rows that do not exist
+        if (split_variant == 0)
+            split_variant = (T <= 128 || n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
+        const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
+        const long tiles = tiles_of(bm, bn);
+        // The 64-wide-K kernels give a quarter of the CUs workgroups that only shrink, from the start (a shrink
+        // item is a chain of dependent loads: behind the tile it would be a tail that no other work hides).
+        // Only while those workgroups can finish the items meanwhile: a batch spread over hundreds of adapters
+        // has more shrink work than tile work, and every workgroup takes its share after its tile instead.
+        const long pieces_bound = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+        dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7) &&
+                     pieces_bound * std::max(1, K / 2048) <= 512;
+        const long target = dyn_shrink ? 192 : 256;
+        // K splits, at most 8, by a cost model in microseconds: a workgroup walking all of K moves (bm + bn) K
+        // bf16 through its CU at about 48 GB/s, a launch takes ceil(tiles S / target) rounds of 1 / S of that
+        // (one workgroup per CU: a grid just above the CU count costs a whole extra round), and every split
+        // writes and reads back a set of fp32 partial tiles at about 5 TB/s.
+        if (c->cfg.split_k > 0) {
+            S = c->cfg.split_k;
+        } else {
+            const double t_full = (double)(bm + bn) * K * 2.0 / 48e3;
+            const double t_part = (double)Mpad * (double)n_pad_total * 8.0 / 5e6;
+            double best = 0.0;
+            for (int cand = 1; cand <= 8; ++cand) {
+                const double rounds = (double)((tiles * cand + target - 1) / target);
+                const double cost = t_full * rounds / cand + t_part * cand;
+                if (cand == 1 || cost < best) {
+                    best = cost;
+                    S = cand;
+                }
+            }
+        }
+        S = std::min(S, std::max(1, (K / kBK) / 2));
+        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
+        S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
+        if ((size_t)S * Mpad * (size_t)n_pad_total > c->L.part_elems) return LORA_ERR_OOM;
+        // a single K range would only add the round trip of the partial tiles: the launch already fills
+        // the chip, take the fused path with the same tile
+        if (S == 1 && c->cfg.path == LORA_PATH_AUTO) split = false;
+        if (!split) dyn_shrink = false;
+    }
+    int n_kc = 1, kc_len = K;
+    if (T <= kSplitMaxTokens) {
+        n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
+        if (split && dyn_shrink) {
+            // chunks of 2048: one round of operand loads per wavefront and item
+            n_kc = std::max(1, std::min<int>(kMaxShrinkChunks, K / 2048));
+        } else if (split) {
+            // The shrink items (slice x piece x K chunk) are shared out over the workgroups of the split GEMM,
+            // each item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup
+            // one item (when there are more pieces than workgroups, fine chunks balance better and stay).
+            // The piece count is only known on the device; this is its upper bound.
+            const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
+            const long wgs = tiles_of(bm, bn) * S;
+            const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+            if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
+        }
+        kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
+        n_kc = (K + kc_len - 1) / kc_len;
+    }
+    out.K = K;
+    out.Mpad = Mpad;
+    out.n_max = n_max;
+    out.n_pad_total = n_pad_total;
+    out.split = split;
+    out.dyn_shrink = dyn_shrink;
+    out.S = S;
+    out.split_variant = split_variant;
+    out.n_kc = n_kc;
+    out.kc_len = kc_len;
+    return LORA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -668,94 +783,17 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
             if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_unit[u], 0))) return LORA_ERR_HIP;
         }
     }
-    const int K = c->proj[projs[0]].d_in;
-    // the slices sit side by side along N, each padded to a multiple of 128 columns
-    long n_pad_total = 0;
-    int n_max = 0;
-    for (int k = 0; k < n; ++k) {
-        n_pad_total += (long)align_up((size_t)c->proj[projs[k]].d_out, 128);
-        n_max = std::max(n_max, c->proj[projs[k]].d_out);
-    }
+    ForwardPlan plan;
+    if (const lora_status st = plan_forward(c, T, n, projs, plan); st != LORA_OK) return st;
+    const int K = plan.K, Mpad = plan.Mpad, n_max = plan.n_max, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
+    const long n_pad_total = plan.n_pad_total;
+    const bool split = plan.split, dyn_shrink = plan.dyn_shrink;
+    const int split_variant = plan.split_variant;
     auto tiles_of = [&](int bm, int bn) {
         long t = 0;
         for (int k = 0; k < n; ++k) t += (c->proj[projs[k]].d_out + bn - 1) / bn;
         return t * ((T + bm - 1) / bm);
     };
-
-    // ---- plan ----
-    const int Mpad = (T + 255) / 256 * 256;
-    bool split = false, dyn_shrink = false;
-    int S = 1;
-    int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
-    if (T <= kSplitMaxTokens) {
-        if (c->cfg.path == LORA_PATH_SPLITK) split = true;
-        else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < 128;
-    }
-    if (split) {
-        // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
-        // small batches walk K in 64-wide tiles (whole cache lines per row segment).  Narrow launches (k, v
-        // alone) fill the chip better with square 128 x 128 tiles, and so does a 4096-wide projection over a
-        // short K at up to 256 tokens (half the K splits, half the partial tiles)
-        // and up to 128 tokens a 256-row tile would copy and multiply rows that do not exist
-        if (split_variant == 0)
-            split_variant = (T <= 128 || n_pad_total <= 2048 || (n_pad_total <= 4096 && K <= 8192 && T <= 256)) ? 7 : 6;
-        const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
-        const long tiles = tiles_of(bm, bn);
-        // The 64-wide-K kernels give a quarter of the CUs workgroups that only shrink, from the start (a shrink
-        // item is a chain of dependent loads: behind the tile it would be a tail that no other work hides).
-        // Only while those workgroups can finish the items meanwhile: a batch spread over hundreds of adapters
-        // has more shrink work than tile work, and every workgroup takes its share after its tile instead.
-        const long pieces_bound = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
-        dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7) &&
-                     pieces_bound * std::max(1, K / 2048) <= 512;
-        const long target = dyn_shrink ? 192 : 256;
-        // K splits, at most 8, by a cost model in microseconds: a workgroup walking all of K moves (bm + bn) K
-        // bf16 through its CU at about 48 GB/s, a launch takes ceil(tiles S / target) rounds of 1 / S of that
-        // (one workgroup per CU: a grid just above the CU count costs a whole extra round), and every split
-        // writes and reads back a set of fp32 partial tiles at about 5 TB/s.
-        if (c->cfg.split_k > 0) {
-            S = c->cfg.split_k;
-        } else {
-            const double t_full = (double)(bm + bn) * K * 2.0 / 48e3;
-            const double t_part = (double)Mpad * (double)n_pad_total * 8.0 / 5e6;
-            double best = 0.0;
-            for (int cand = 1; cand <= 8; ++cand) {
-                const double rounds = (double)((tiles * cand + target - 1) / target);
-                const double cost = t_full * rounds / cand + t_part * cand;
-                if (cand == 1 || cost < best) {
-                    best = cost;
-                    S = cand;
-                }
-            }
-        }
-        S = std::min(S, std::max(1, (K / kBK) / 2));
-        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
-        S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
-        if ((size_t)S * Mpad * (size_t)n_pad_total > c->L.part_elems) return LORA_ERR_OOM;
-        // a single K range would only add the round trip of the partial tiles: the launch already fills
-        // the chip, take the fused path with the same tile
-        if (S == 1 && c->cfg.path == LORA_PATH_AUTO) split = false;
-        if (!split) dyn_shrink = false;
-    }
-    int n_kc = 1, kc_len = K;
-    if (T <= kSplitMaxTokens) {
-        n_kc = std::min<int>(kMaxShrinkChunks, (K + kShrinkKC - 1) / kShrinkKC);
-        if (split && dyn_shrink) {
-            // chunks of 2048: one round of operand loads per wavefront and item
-            n_kc = std::max(1, std::min<int>(kMaxShrinkChunks, K / 2048));
-        } else if (split) {
-            // The shrink items (slice x piece x K chunk) are shared out over the workgroups of the split GEMM,
-            // each item a dependent load -> MFMA -> reduce chain: no more chunks than give every workgroup
-            // one item (when there are more pieces than workgroups, fine chunks balance better and stay).
-            // The piece count is only known on the device; this is its upper bound.
-            const int bm = split_bm(split_variant), bn = split_variant == 2 ? 64 : 128;
-            const long wgs = tiles_of(bm, bn) * S;
-            const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
-            if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
-        }
-        kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
-        n_kc = (K + kc_len - 1) / kc_len;
-    }
     const size_t vslice = (size_t)n_kc * T * c->cfg.max_rank;
     if (vslice * n > c->L.vpart_elems) return LORA_ERR_OOM;
 
