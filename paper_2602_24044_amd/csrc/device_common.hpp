@@ -29,27 +29,28 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 // Operands come straight from global memory in MFMA layout.  Within a 64-wide K step lane (i, h)
 // reads 64 contiguous bytes of row i at k0 + 32 h; MFMA q of the step consumes bytes [16 q, 16 q + 16)
 // of both halves.  A and x use the same assignment, so the K order inside a step is permuted
-// identically on both sides.  Two K steps are kept in flight.
+// identically on both sides.  Several K steps are kept in flight (shrink_chunk).
 // ---------------------------------------------------------------------------------------------------
 struct ShrinkStep {
     u32x4 x[4], a0[4], a1[4];
 };
 
+// Every lane loads, also those whose row does not exist (their pointers are clamped to an existing row by the
+// caller and what they produce is never stored): a predicated load is a branch, and behind branches the compiler
+// can no longer count the loads in flight and waits for all of them before every step.
 template <bool R64>
-__device__ inline void shrink_fetch(ShrinkStep& s, const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1,
-                                    bool x_ok, bool a0_ok, bool a1_ok, int k0)
+__device__ __forceinline__ void shrink_fetch(ShrinkStep& s, const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1, int k0)
 {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        s.x[q] = x_ok ? load16(xrow + k0 + q * 8) : zero;
-        s.a0[q] = a0_ok ? load16(arow0 + k0 + q * 8) : zero;
-        if (R64) s.a1[q] = a1_ok ? load16(arow1 + k0 + q * 8) : zero;
+        s.x[q] = load16(xrow + k0 + q * 8);
+        s.a0[q] = load16(arow0 + k0 + q * 8);
+        if (R64) s.a1[q] = load16(arow1 + k0 + q * 8);
     }
 }
 
 template <bool R64>
-__device__ inline void shrink_mma(const ShrinkStep& s, f32x16& acc0, f32x16& acc1)
+__device__ __forceinline__ void shrink_mma(const ShrinkStep& s, f32x16& acc0, f32x16& acc1)
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -59,25 +60,39 @@ __device__ inline void shrink_mma(const ShrinkStep& s, f32x16& acc0, f32x16& acc
 }
 
 // K steps of one wavefront's share of an item, D of them in flight (each step is 8 or 12 independent 16-byte
-// loads per lane; an item is a chain of dependent memory latencies, so the depth sets its duration).
+// loads per lane; an item is a chain of dependent memory latencies, so the depth sets its duration).  The steady
+// state is free of branches, so that the wait before a step covers that step's loads only.
 template <bool R64>
-__device__ inline void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1, bool x_ok,
-                                    bool a0_ok, bool a1_ok, int k_begin, int k_end, f32x16& acc0, f32x16& acc1)
+__device__ __forceinline__ void shrink_chunk(const uint16_t* xrow, const uint16_t* arow0, const uint16_t* arow1, int k_begin,
+                                    int k_end, f32x16& acc0, f32x16& acc1)
 {
     constexpr int D = R64 ? 2 : 4;
     ShrinkStep st[D];
+    int k0 = k_begin;
+    if (k_end - k_begin >= 2 * D * kBK) {                    // uniform over the wave
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (k_begin + d * kBK < k_end) shrink_fetch<R64>(st[d], xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin + d * kBK);
-    for (int k0 = k_begin; k0 < k_end; k0 += D * kBK) {
+        for (int d = 0; d < D; ++d) shrink_fetch<R64>(st[d], xrow, arow0, arow1, k0 + d * kBK);
+        for (; k0 + 2 * D * kBK <= k_end; k0 += D * kBK) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (k0 + d * kBK < k_end) {                      // uniform over the wave
+            for (int d = 0; d < D; ++d) {
                 shrink_mma<R64>(st[d], acc0, acc1);
-                if (k0 + (D + d) * kBK < k_end)
-                    shrink_fetch<R64>(st[d], xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k0 + (D + d) * kBK);
+                shrink_fetch<R64>(st[d], xrow, arow0, arow1, k0 + (D + d) * kBK);
             }
         }
+        // the D steps still in flight
+#pragma unroll
+        for (int d = 0; d < D; ++d) shrink_mma<R64>(st[d], acc0, acc1);
+        k0 += D * kBK;
+    }
+    // what is left: fewer than 2 D steps, at most D at a time
+    while (k0 < k_end) {
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (k0 + d * kBK < k_end) shrink_fetch<R64>(st[d], xrow, arow0, arow1, k0 + d * kBK);
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (k0 + d * kBK < k_end) shrink_mma<R64>(st[d], acc0, acc1);
+        k0 += D * kBK;
     }
 }
 
@@ -145,7 +160,6 @@ __device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_piec
     int k_end = k_begin + per_wave * kBK;
     if (k_end > c_end) k_end = c_end;
 
-    const bool x_ok = i < nrows;
     const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
     const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + (size_t)r * sl.a_unit;
     const bool a0_ok = i < r, a1_ok = (32 + i) < r;
@@ -156,8 +170,8 @@ __device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_piec
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
     if (k_begin < k_end) {
-        if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
-        else shrink_chunk<true>(xrow, arow0, arow1, x_ok, a0_ok, a1_ok, k_begin, k_end, acc0, acc1);
+        if (r <= 32) shrink_chunk<false>(xrow, arow0, arow1, k_begin, k_end, acc0, acc1);
+        else shrink_chunk<true>(xrow, arow0, arow1, k_begin, k_end, acc0, acc1);
     }
 
     // accumulator: column = grouped row m_begin + i, register 4 g + e = rank index 8 g + 4 h + e
