@@ -268,6 +268,63 @@ __device__ inline u32x4 window_v_share(int q, const float* vpart, int n_kc, int 
     return packed;
 }
 
+// The four shares of each of WB consecutive windows.  One share after the other would be a chain of 4 * n_kc
+// dependent memory latencies per window (every chunk's partial is added before the next is requested); here the
+// row data of all windows is requested together, then per window and chunk the partials of its four shares in
+// one go: 1 + WB * n_kc latencies.  The partials are loaded by every lane (a predicated load is a branch that
+// keeps the compiler from overlapping the loads); lanes without a share read row 0 and drop the result.
+template <int WB>
+__device__ __forceinline__ void window_v_shares(u32x4 (&share)[WB][4], const float* vpart, int n_kc, int win0,
+                                                const DeviceView& dv)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int T = dv.T;
+    int r[WB][4];
+    float sc[WB][4];
+#pragma unroll
+    for (int w = 0; w < WB; ++w)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = lane + 64 * q;
+            const int mr = win0 + w * kPieceRows + (idx >> 3);
+            const bool on = mr < T && (idx & 7) * 8 < dv.max_rank;
+            r[w][q] = on ? dv.row_rank[mr] : 0;
+            sc[w][q] = on ? dv.row_scale[mr] : 0.f;
+        }
+    const size_t chunk = (size_t)T * dv.max_rank;
+#pragma unroll
+    for (int w = 0; w < WB; ++w) {
+        const float* vp[4];
+        f32x4 lo[4], hi[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = lane + 64 * q;
+            const int mr = win0 + w * kPieceRows + (idx >> 3), seg = idx & 7;
+            const bool live = seg * 8 < r[w][q];              // implies the row exists
+            vp[q] = vpart + (live ? (size_t)mr * dv.max_rank + seg * 8 : 0);
+            lo[q] = hi[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int c = 0; c < n_kc; ++c) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                lo[q] += *reinterpret_cast<const f32x4*>(vp[q] + c * chunk);
+                hi[q] += *reinterpret_cast<const f32x4*>(vp[q] + c * chunk + 4);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x8 vb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vb[e] = (__bf16)(lo[q][e] * sc[w][q]);
+                vb[4 + e] = (__bf16)(hi[q][e] * sc[w][q]);
+            }
+            const bool live = ((lane + 64 * q) & 7) * 8 < r[w][q];
+            share[w][q] = live ? __builtin_bit_cast(u32x4, vb) : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+}
+
 // Parks share q in the window's LDS image (sV: 32 rows of kVStageStride elements).
 __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 {

@@ -181,11 +181,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
             for (int w = 0; w < WB; ++w) any = any || __ballot(slot[p * WB + w] >= 0 && rank[p * WB + w] > 0) != 0;
             if (any) {                                            // uniform over the wave
                 u32x4 share[WB][4];
-#pragma unroll
-                for (int w = 0; w < WB; ++w)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        share[w][q] = window_v_share(q, sl.vpart, a.n_kc, m_first + (p * WB + w) * 32, a.dv);
+                window_v_shares<WB>(share, sl.vpart, a.n_kc, m_first + p * WB * 32, a.dv);
 #pragma unroll
                 for (int w = 0; w < WB; ++w)
 #pragma unroll
