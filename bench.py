@@ -116,7 +116,7 @@ def cpu_baseline(w, budget_s: float = 15.0):
         t0 = time.perf_counter()
         oracle.bucket(w.token_ids[sl], np.arange(w.max_adapter_id + 1, dtype=np.int32), w.mode)
         for p in range(len(w.proj)):
-            oracle.project(w.x[p][sl], w.W[p], w.token_ids[sl], oracle.adapters_of(w, p))
+            oracle.project(w.x[p][sl], w.W[p], w.token_ids[sl], oracle.adapters_of(w, p), bias=w.bias_of(p))
         t_used += time.perf_counter() - t0
         done += take
         n *= 2
@@ -129,7 +129,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 2 (8B decode, the headline), 3, 4 or 5")
+    ap.add_argument("--config", type=int, default=2, help="workload 2 (8B decode, the headline), 3, 4, 5, or 6 (config 2's recipe at Qwen2.5-7B shapes)")
     ap.add_argument("--copies", type=int, default=0,
                     help="distinct weight/slot copies rotated through (0 = 4 for configs 2 and 4, else 2)")
     ap.add_argument("--shrink", type=int, default=1, help="divide the model dimensions (debugging only)")
@@ -157,9 +157,10 @@ def main():
     names = {2: "8B-shape decode, 256 requests x 1 token, 32 adapters ranks {8,16,32}, Zipf(1.0) ids",
              3: "8B-shape prefill, 32 requests lognormal lengths, 64 adapters rank 16",
              4: "8B-shape many-adapter decode, 512 tokens uniform over 384 adapters ranks {8,16,32,64}",
-             5: "70B-shape mixed step, 2048-token prefill chunk + 384 decode tokens, 128 slots"}
+             5: "70B-shape mixed step, 2048-token prefill chunk + 384 decode tokens, 128 slots",
+             6: "Qwen2.5-7B-shape decode, 256 requests x 1 token, 32 adapters ranks {8,16,32}, Zipf(1.0) ids, q/k/v bias"}
 
-    copies = args.copies if args.copies > 0 else (4 if args.config in (2, 4) else 2)
+    copies = args.copies if args.copies > 0 else (4 if args.config in (2, 4, 6) else 2)
     # Config 5: every step loads the batch's cold adapters again (H2D copies inside the timed region).
     # Rank-0 placeholder adapters are put into their slots first (metadata only), so the next load of the
     # real adapters finds them non-resident and copies their weights from pinned host memory.

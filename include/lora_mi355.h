@@ -250,6 +250,7 @@ enum {
     LORA_FUSED_256x128x64_W8 = 8,         /* 64-wide K tiles: whole 128-byte lines per row segment */
     LORA_FUSED_128x128x64_W4 = 9,
     LORA_FUSED_256x256x64_W8 = 10,
+    LORA_FUSED_256x192x64_W8 = 11,
     LORA_FUSED_256x256x32_W8 = 12         /* what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
 };
 /* Values of LORA_TUNE_SPLIT_VARIANT. */

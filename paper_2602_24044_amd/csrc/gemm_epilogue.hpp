@@ -61,24 +61,34 @@ __device__ __forceinline__ void init_accumulators(f32x16 (&acc)[MB][NB], const S
 }
 
 // Rounds WB windows of accumulators to bf16 and stores them to out rows perm[m], through LDS (sT: this wave's
-// piece, WB * 32 rows of NB * 64 bytes).  Chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & (CH - 1)):
-// the 8-byte writes of a half wave then collide two ways at most and the 16-byte reads are contiguous.
+// piece, WB * 32 rows of NB * 64 bytes).  Chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & (CH - 1))
+// (CH a power of two; otherwise rotated by r >> 1): the 8-byte writes of a half wave then collide two ways at
+// most and the 16-byte reads are contiguous.  One read instruction covers 64 / CH whole rows (with 12 chunks per
+// row the last four lanes idle).
 template <int WB, int NB>
 __device__ __forceinline__ void store_windows(const f32x16 (&acc)[WB][NB], const GemmArgs& a, const Slice& sl, int m_first,
                                               int n_first, uint8_t* sT)
 {
     constexpr int CH = NB * 4, ROWB = NB * 64;     // 16-byte chunks and bytes per LDS row
+    constexpr bool P2 = (CH & (CH - 1)) == 0;
     constexpr int RPI = kWave / CH;                // rows one 16-byte-per-lane instruction covers
-    constexpr int ITER = WB * 32 / RPI;
+    constexpr int ROWS = WB * 32;
+    constexpr int ITER = (ROWS + RPI - 1) / RPI;
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
     const int T = a.m_end, N = sl.N;
+    // row: inside its 32-row window
+    auto place = [](int c, int row) { return P2 ? (c ^ ((row >> 1) & (CH - 1))) : (c + (row >> 1)) % CH; };
+    auto chunk_at = [](int pos, int row) { return P2 ? (pos ^ ((row >> 1) & (CH - 1))) : (pos + CH - (row >> 1) % CH) % CH; };
+    const int lrow = lane / CH, lpos = lane % CH;
+    const bool lane_on = lrow < RPI;
     // tokens of the rows this lane will store (fetched before the LDS round trip)
     int tok[ITER];
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int m = m_first + it * RPI + lane / CH;
-        tok[it] = m < T ? a.dv.perm[m] : -1;
+        const int row = it * RPI + lrow;
+        const int m = m_first + row;
+        tok[it] = (lane_on && row < ROWS && m < T) ? a.dv.perm[m] : -1;
     }
 #pragma unroll
     for (int w = 0; w < WB; ++w)
@@ -89,16 +99,18 @@ __device__ __forceinline__ void store_windows(const f32x16 (&acc)[WB][NB], const
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[w][nb][g * 4 + e];
-                const int pos = (nb * 4 + g) ^ ((i >> 1) & (CH - 1));
+                const int pos = place(nb * 4 + g, i);
                 *reinterpret_cast<u32x2*>(sT + (w * 32 + i) * ROWB + pos * 16 + h * 8) = __builtin_bit_cast(u32x2, o);
             }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int row = it * RPI + lane / CH, pos = lane % CH;
-        const int n = n_first + (pos ^ ((row >> 1) & (CH - 1))) * 8;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(sT + row * ROWB + pos * 16);
-        if (tok[it] >= 0 && n < N) *reinterpret_cast<u32x4*>(sl.out + (size_t)tok[it] * N + n) = v;
+        const int row = it * RPI + lrow;
+        if (tok[it] >= 0) {                                       // implies an existing row of this lane
+            const int n = n_first + chunk_at(lpos, row & 31) * 8;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(sT + row * ROWB + lpos * 16);
+            if (n < N) *reinterpret_cast<u32x4*>(sl.out + (size_t)tok[it] * N + n) = v;
+        }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");            // reads done before the piece is reused
 }
@@ -144,7 +156,7 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
 #pragma unroll
             for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        expand_windows<MB, NB, 4>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_unit, sV);
+        expand_windows<MB, NB, (NB > 2 ? 2 : 4)>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_unit, sV);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     store_windows<MB, NB>(acc, a, sl, m_first, n_first, mine);

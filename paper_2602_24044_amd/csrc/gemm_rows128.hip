@@ -248,6 +248,9 @@ hipError_t launch_gemm_rows128_fused(const GemmArgs& a, int variant, hipStream_t
         case 2:
             *name = "gemm_fused_256x256x64_w8";
             return launch_rows128<256, 256, 2, 4, true, 2>(a, none, stream);
+        case 3:
+            *name = "gemm_fused_256x192x64_w8";
+            return launch_rows128<256, 192, 4, 2, true, 2>(a, none, stream);
         default:
             *name = "gemm_fused_256x128x64_w8";
             return launch_rows128<256, 128, 4, 2, true, 3>(a, none, stream);

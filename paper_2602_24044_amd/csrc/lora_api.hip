@@ -899,6 +899,19 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
             // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
             // (128-row tiles up to 128 tokens)
             if (T <= kSplitMaxTokens) fv = T <= 128 ? 9 : (fv == 4 ? 8 : (fv == 3 ? 9 : 10));
+            // between 129 and 1024 tokens the launch is bound by what a workgroup moves through its CU: rounds
+            // of workgroups over the CUs times the rows (x and W) of a tile; near ties go to the larger tile
+            if (T > 128 && T <= kSplitMaxTokens) {
+                const struct { int v, bm, bn; } cand[] = {{10, 256, 256}, {11, 256, 192}, {8, 256, 128}, {9, 128, 128}};
+                double best = 0.0;
+                for (const auto& cd : cand) {
+                    const double cost = (double)((tiles_of(cd.bm, cd.bn) + 255) / 256) * (cd.bm + cd.bn);
+                    if (best == 0.0 || cost < best * 0.97) {
+                        best = cost;
+                        fv = cd.v;
+                    }
+                }
+            }
         }
         // A last round of 256 x 256 tiles that fills less than half the chip costs as much as a full one.  When
         // the rows behind the full rounds are few enough for the split-K path, the fused launch stops at the
@@ -932,8 +945,8 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
             const char* name = nullptr;
             GemmArgs a = ga;
             a.m_end = m_split;
-            // 8 .. 10: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
-            const hipError_t le = (fv >= 8 && fv <= 10) ? launch_gemm_rows128_fused(a, fv - 8, s, &name)
+            // 8 .. 11: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
+            const hipError_t le = (fv >= 8 && fv <= 11) ? launch_gemm_rows128_fused(a, fv - 8, s, &name)
                                                         : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);

@@ -304,7 +304,7 @@ def model_layers(base: Workload, n_layers: int) -> List[Workload]:
 
 
 def by_index(i: int, **kw) -> Workload:
-    return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}[i](**kw)
+    return {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: qwen_decode}[i](**kw)
 
 
 # --------------------------------------------------------------------------

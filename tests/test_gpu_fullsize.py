@@ -82,3 +82,30 @@ def test_config5_full():
 
 def test_qwen_7b_decode_full():
     _run_full(wl.qwen_decode(), n_samples=800)
+
+
+def test_whole_model_two_layers_full_size():
+    # two layers of 8B shapes in one context: the second layer sits 5 MB x rank into every slot; sampled outputs of
+    # both layers
+    from paper_2602_24044_amd.runtime import ModelSession
+    layers = wl.model_layers(wl.config2(), 2)
+    announce(f"model step {layers[0].name} layers=2 T={layers[0].T} (full size)")
+    ms = ModelSession(layers)
+    rng = np.random.default_rng(5)
+    try:
+        ms.load(layers[0].resident)
+        ms.step()
+        torch.cuda.synchronize()
+        for l, lw in enumerate(layers):
+            for p, (d_in, d_out) in enumerate(lw.proj):
+                ts = rng.integers(0, lw.T, size=200).astype(np.int32)
+                ns = rng.integers(0, d_out, size=200).astype(np.int32)
+                ts[:2], ns[:2] = [0, lw.T - 1], [0, d_out - 1]
+                y_ref = oracle.project_at(lw.x[p], lw.W[p], lw.token_ids, oracle.adapters_of(lw, p), ts, ns)
+                got = wl.bf16_bits_to_f64(bf16_tensor_to_bits(ms.out[l][p])[ts, ns])
+                err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
+                assert err <= TOL, (l, p, err)
+        st, word = B.lora_poll_device_flags(ms.ctx)
+        assert st == B.LORA_OK and word == 0
+    finally:
+        ms.close()
