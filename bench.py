@@ -23,9 +23,10 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def kernel_algorithmic_bytes(w, kernel: str, projections) -> float:
+def kernel_algorithmic_bytes(w, kernel: str, projections, shrink_inside: bool = False) -> float:
     """Bytes one layer-step's launches of `kernel` must move (over the projections that launch it): each
-    array counted once, in the kernel that has to touch it; split-K partials and re-reads are not counted."""
+    array counted once, in the kernel that has to touch it; split-K partials and re-reads are not counted.
+    shrink_inside: the fused GEMM launch also does the shrink (no separate shrink launch for these projections)."""
     used = w.distinct_adapters()
     rank_sum = sum(w.adapters[a].rank for a in used)
     T = w.T
@@ -37,6 +38,8 @@ def kernel_algorithmic_bytes(w, kernel: str, projections) -> float:
             tot += 2.0 * d_in * d_out + 2.0 * T * d_in + 2.0 * rank_sum * d_in
         elif kernel.startswith("gemm_fused"):
             tot += 2.0 * d_in * d_out + 2.0 * T * d_in + 2.0 * T * d_out + 2.0 * rank_sum * d_out
+            if shrink_inside:
+                tot += 2.0 * rank_sum * d_in
         elif kernel == "reduce_expand":
             tot += 2.0 * T * d_out + 2.0 * rank_sum * d_out
         elif kernel == "shrink":
@@ -223,6 +226,7 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
     # which projections launch the dominant kernel
     launched_by = []
+    shrink_inside = False
     s0 = sessions[0]
     s0.bucket()
     for g in s0.packed_groups():
@@ -232,9 +236,10 @@ def main():
             s0.forward(g[0])
         if dominant in B.lora_last_launches(s0.ctx):
             launched_by += g
+            shrink_inside = shrink_inside or "shrink" not in B.lora_last_launches(s0.ctx)
     torch.cuda.synchronize()
     dom_t = kernels[dominant]["us_per_step"] * 1e-6
-    dom_bytes = kernel_algorithmic_bytes(w, dominant, launched_by)
+    dom_bytes = kernel_algorithmic_bytes(w, dominant, launched_by, shrink_inside and dominant.startswith("gemm_fused"))
     dom_flops = kernel_flops(w, dominant, launched_by)
     achieved_gbs = dom_bytes / dom_t / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -68,7 +68,11 @@ enum {
 };
 
 /* Bits of the device flag word (lora_poll_device_flags). */
-enum { LORA_FLAG_NOT_RESIDENT = 1u };
+enum {
+    LORA_FLAG_NOT_RESIDENT = 1u,
+    LORA_FLAG_INTERNAL = 2u /* a bounded wait inside a kernel expired (never seen; a safety net): the results of
+                               the calls since the last poll are invalid, lora_poll_device_flags returns LORA_ERR_HIP */
+};
 
 /* lora_config.flags */
 enum {
@@ -218,7 +222,7 @@ lora_status lora_model_forward_group(lora_ctx *ctx, int32_t layer, int32_t n, co
 lora_status lora_set_bias(lora_ctx *ctx, int32_t layer, int32_t proj, const void *d_bias);
 
 /* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
- * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set, else LORA_OK; *flags (may be NULL)
+ * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set (LORA_ERR_HIP if LORA_FLAG_INTERNAL was), else LORA_OK; *flags (may be NULL)
  * receives the raw word. */
 lora_status lora_poll_device_flags(lora_ctx *ctx, uint32_t *flags, void *stream);
 
@@ -231,7 +235,14 @@ int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter i
 enum {
     LORA_TUNE_FUSED_VARIANT = 0, /* tile shape / wave layout of the fused GEMM */
     LORA_TUNE_SPLIT_VARIANT = 1, /* tile shape / wave layout of the split-K GEMM */
-    LORA_TUNE_COPY_ENGINE = 2    /* what carries an adapter's matrices into its slot (lora_slots_load) */
+    LORA_TUNE_COPY_ENGINE = 2,   /* what carries an adapter's matrices into its slot (lora_slots_load) */
+    LORA_TUNE_INLINE_SHRINK = 3  /* fused path up to 1024 tokens: shrink by the first workgroups of the GEMM launch */
+};
+/* Values of LORA_TUNE_INLINE_SHRINK. */
+enum {
+    LORA_INLINE_SHRINK_AUTO = 0, /* when the tiles leave CUs idle and those can finish the shrink in time */
+    LORA_INLINE_SHRINK_OFF = 1,  /* always a separate shrink launch */
+    LORA_INLINE_SHRINK_ON = 2    /* whenever at least 8 CUs have no tile */
 };
 /* Values of LORA_TUNE_COPY_ENGINE. */
 enum {

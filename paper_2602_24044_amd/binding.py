@@ -58,6 +58,7 @@ LORA_PATH_AUTO = 0
 LORA_PATH_FUSED = 1
 LORA_PATH_SPLITK = 2
 LORA_FLAG_NOT_RESIDENT = 1
+LORA_FLAG_INTERNAL = 2
 LORA_CREATE_HOST_ONLY = 1
 
 EXPORTS = [
@@ -71,6 +72,8 @@ LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
 LORA_TUNE_COPY_ENGINE = 2
 LORA_COPY_AUTO, LORA_COPY_KERNEL, LORA_COPY_ENGINE = 0, 1, 2
+LORA_TUNE_INLINE_SHRINK = 3
+LORA_INLINE_SHRINK_AUTO, LORA_INLINE_SHRINK_OFF, LORA_INLINE_SHRINK_ON = 0, 1, 2
 # values of LORA_TUNE_FUSED_VARIANT / LORA_TUNE_SPLIT_VARIANT (tile rows x columns x K tile, wavefronts)
 FUSED_VARIANTS = {"256x256x32_w4": 1, "256x256x32_w4_3stages": 2, "128x128x32_w4": 3, "256x128x32_w8": 4,
                   "256x128x32_w8_allcopy": 5, "256x128x64_w8": 8, "128x128x64_w4": 9, "256x256x64_w8": 10, "256x192x64_w8": 11,

@@ -69,6 +69,22 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         }
         return;
     }
+    // fused path: the workgroups at the front of the grid do the launch's shrink items and report
+    const int front = FUSED ? a.shrink_front : 0;
+    if (FUSED && front > 0 && (int)blockIdx.x < front) {
+        float* sRed = reinterpret_cast<float*>(ring);
+        const ShrinkPrefetch pa = shrink_prefetch(sa, blockIdx.x);
+        shrink_block_items<NWV>(sa, blockIdx.x, front, pa.n_items, sRed, pa);
+        // every wave's results have reached L2, then one thread makes them visible to the device and reports
+        // (a device-scope fence writes back / invalidates caches: one per workgroup, not one per wave)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            atomicAdd(a.sync, 1u);
+        }
+        return;
+    }
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -80,7 +96,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     // is the fastest index on the split path (every XCD keeps one x K-range in its L2)
     int split = 0, tile_m, tile_n;
     {
-        int b = blockIdx.x;
+        int b = (int)blockIdx.x - front;
         if (!FUSED) {
             split = b % a.split_k;
             b /= a.split_k;
@@ -163,7 +179,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     // fused path: the epilogue's per-row data travels while the first tiles do
     constexpr bool PRE = FUSED && MB <= 2;
     TilePrefetch<PRE ? MB : 1> pre;
-    if constexpr (PRE) prefetch_windows(pre, a, sl, m0 + wm * WTM);
+    if constexpr (PRE) {
+        if (front == 0) prefetch_windows(pre, a, sl, m0 + wm * WTM);      // else: not there yet
+    }
 
     int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
     for (int j = 0; j < nk; ++j) {
@@ -207,6 +225,30 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     static_assert(!FUSED || NS * STAGE_B >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
     static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
+    if (FUSED && front > 0) {
+        // The shrink results come from the workgroups at the front of this launch.  They hold the lowest
+        // indices, so they were dispatched before this workgroup and never wait for anything: the wait ends.
+        // It is bounded all the same; if it expires the call's result is invalid and flagged.
+        if (threadIdx.x == 0) {
+            int spins = 0;
+            while (__hip_atomic_load(a.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)front) {
+                if (++spins > kShrinkWaitSpins) {
+                    atomicOr(a.flags, kFlagInternal);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(32);
+            }
+            // past the wait: the last tile workgroup to get here sets the counters back for the next launch
+            const uint32_t tiles = gridDim.x - (uint32_t)front;
+            if (atomicAdd(a.sync + 1, 1u) == tiles - 1) {
+                __hip_atomic_store(a.sync, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.sync + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // what the shrink workgroups wrote is read from here on
+        }
+        __syncthreads();
+        if constexpr (PRE) prefetch_windows(pre, a, sl, m0 + wm * WTM);
+    }
     if constexpr (PRE)
         finish_tile_prefetched<MB, NB>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, wave, reinterpret_cast<uint16_t*>(ring), pre);
     else
@@ -230,6 +272,7 @@ hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
     const int extra = FUSED ? 0 : a.main_grid;            // on entry: workgroups that only do shrink items
     a.main_grid = grid;
     grid += extra;
+    if (FUSED) grid += a.shrink_front;                    // those come first
     hipLaunchKernelGGL((gemm_rows128_kernel<BM, BN, WGM, WGN, FUSED, NS>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream,
                        a, sa);
     return hipGetLastError();
@@ -237,10 +280,10 @@ hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_gemm_rows128_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name)
+hipError_t launch_gemm_rows128_fused(const GemmArgs& a, const ShrinkArgs& none, int variant, hipStream_t stream,
+                                     const char** name)
 {
-    ShrinkArgs none{};
-    none.on = 0;
+    // `none`: the shrink work of the launch when a.shrink_front > 0, otherwise unused
     switch (variant) {
         case 1:
             *name = "gemm_fused_128x128x64_w4";

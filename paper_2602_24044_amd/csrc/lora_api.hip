@@ -885,13 +885,6 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
 
     if (!split) {
         // ---- shrink, then base GEMM with the expand in its epilogue ----
-        if (sa.on) {
-            const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
-            const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc * n;
-            const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
-            LaunchScope ls(c, s, "shrink");
-            if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
-        }
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
         const bool auto_variant = fv == 0;
         if (auto_variant) {
@@ -940,13 +933,44 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
                 }
             }
         }
+        // Small batches leave CUs without a tile (224 tiles of 256 x 128 for a Llama-8B gate|up, 198 of 256 x 192
+        // for Qwen2.5-7B).  When those CUs can finish the shrink well inside the time the tiles stream, they do
+        // it as the first workgroups of the GEMM launch and the separate shrink launch goes.
+        int front = 0;
+        if (sa.on && fv >= 8 && fv <= 11 && T <= kSplitMaxTokens && m_split == T &&
+            c->tune[LORA_TUNE_INLINE_SHRINK] != LORA_INLINE_SHRINK_OFF) {
+            const int bm = fv == 9 ? 128 : 256, bn = fv == 10 ? 256 : (fv == 11 ? 192 : 128);
+            const long idle = 256 - tiles_of(bm, bn);
+            const int chunks = std::max(1, std::min<int>(kMaxShrinkChunks, K / 2048));   // one round of loads per item
+            const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
+            const double t_main = (double)(bm + bn) * K * 2.0 / 48e3;                   // us, see plan_forward
+            if (idle >= 8 && chunks <= n_kc &&      // the scratch for the shrink results is sized for n_kc chunks
+                (c->tune[LORA_TUNE_INLINE_SHRINK] == LORA_INLINE_SHRINK_ON ||
+                 (double)(pieces * chunks) * 4.0 / (double)std::min<long>(idle, 64) <= 0.6 * t_main)) {
+                front = (int)std::min<long>(idle, 64);
+                sa.n_kc = chunks;
+                sa.kc_len = ((K + chunks - 1) / chunks + kBK - 1) / kBK * kBK;
+                sa.n_kc = (K + sa.kc_len - 1) / sa.kc_len;
+                ga.n_kc = sa.n_kc;
+            }
+        }
+        if (sa.on && front == 0) {
+            const long seg_bound = seg->mode == LORA_BUCKET_SORTED ? std::min<long>(T, (long)c->cfg.n_slots + 1) : T;
+            const long items = (seg_bound + (T + kPieceRows - 1) / kPieceRows) * n_kc * n;
+            const int grid = (int)std::max<long>(1, std::min<long>(items, 4096));
+            LaunchScope ls(c, s, "shrink");
+            if (HIP_FAIL(launch_shrink(sa, grid, s))) return LORA_ERR_HIP;
+        }
         {
             LaunchScope ls(c, s, "gemm_fused");
             const char* name = nullptr;
             GemmArgs a = ga;
             a.m_end = m_split;
+            a.shrink_front = front;
+            a.sync = c->dev<uint32_t>(c->L.off_header) + 8;
+            a.flags = c->d_flags();
             // 8 .. 11: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
-            const hipError_t le = (fv >= 8 && fv <= 11) ? launch_gemm_rows128_fused(a, fv - 8, s, &name)
+            const hipError_t le = (fv >= 8 && fv <= 11) ? launch_gemm_rows128_fused(a, sa, fv - 8, s, &name)
                                                         : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
@@ -994,6 +1018,13 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     if (HIP_FAIL(launch_fill_i32(reinterpret_cast<int32_t*>(c->d_flags()), 0, 1, s))) return LORA_ERR_HIP;
     if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
     if (flags) *flags = word;
+    if (word & LORA_FLAG_INTERNAL) {
+        // a bounded wait inside a kernel expired: the counters it used may be left half-way
+        if (HIP_FAIL(launch_fill_i32(c->dev<int32_t>(c->L.off_header) + 8, 0, 2, s))) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
+        g_last_hip_error = "a kernel's bounded wait for the launch's shrink workgroups expired";
+        return LORA_ERR_HIP;
+    }
     return (word & LORA_FLAG_NOT_RESIDENT) ? LORA_ERR_NOT_RESIDENT : LORA_OK;
 }
 

@@ -18,6 +18,8 @@ constexpr int kMetaBatch = 16;       // slot-metadata updates carried by one ker
 constexpr int kSplitMaxTokens = 1024;// largest T served by the split-K path
 constexpr int kShrinkKC = 1024;      // K extent of one shrink work item on the split-K path
 constexpr int kMaxShrinkChunks = 64;
+constexpr uint32_t kFlagInternal = 2u;     // LORA_FLAG_INTERNAL: a bounded wait inside a kernel expired
+constexpr int kShrinkWaitSpins = 400000;  // bounded wait of the tile workgroups for the launch's shrink workgroups (~1 us each)
 
 // Device-side view of a context: everything the kernels need, passed by value.
 struct DeviceView {
@@ -131,6 +133,14 @@ struct GemmArgs {
     // takes the items blockIdx, blockIdx + grid, ... after its tile)
     int32_t main_grid;
     int32_t shrink_q;
+    // fused path of the 64-wide-K kernels: the first shrink_front workgroups of the grid do the launch's shrink
+    // items (the tiles leave that many CUs idle) and the tile workgroups wait for them before their epilogue.
+    // sync[0]: shrink workgroups that have finished, sync[1]: tile workgroups past the wait; the last of those
+    // sets both back to zero.  The wait is bounded: when it expires, LORA_FLAG_INTERNAL is set in *flags.
+    int32_t shrink_front;
+    int32_t pad_;
+    uint32_t* sync;
+    uint32_t* flags;
 };
 
 struct ReduceArgs {
@@ -154,7 +164,7 @@ hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);
 hipError_t launch_gemm_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
 hipError_t launch_gemm_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 // K walked in 64-wide tiles (whole 128-byte lines per row segment): the small-batch kernels
-hipError_t launch_gemm_rows128_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
+hipError_t launch_gemm_rows128_fused(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 hipError_t launch_reduce_expand(const ReduceArgs& a, int grid, hipStream_t stream);
 

@@ -32,3 +32,14 @@ def test_whole_line_split_variants_short_k_ranges(variant):
     tuning = {B.LORA_TUNE_SPLIT_VARIANT: variant}
     run_and_check(wl.config1(), path=B.LORA_PATH_SPLITK, split_k=16, tuning=tuning)
     run_and_check(wl.config1(), path=B.LORA_PATH_SPLITK, split_k=2, tuning=tuning)
+
+
+@pytest.mark.parametrize("mode", [B.LORA_INLINE_SHRINK_OFF, B.LORA_INLINE_SHRINK_ON])
+@pytest.mark.parametrize("variant", [8, 9, 10, 11])
+def test_shrink_inside_the_fused_launch(mode, variant):
+    # fused path up to 1024 tokens: the shrink by the first workgroups of the GEMM launch, or as a launch of its own;
+    # two steps in a row (the launch leaves its counters at zero for the next one)
+    tuning = {B.LORA_TUNE_INLINE_SHRINK: mode, B.LORA_TUNE_FUSED_VARIANT: variant}
+    run_and_check(wl.config2(shrink=8, n_tokens=300), path=B.LORA_PATH_FUSED, tuning=tuning, packed=True)
+    run_and_check(wl.config4(shrink=8), path=B.LORA_PATH_FUSED, tuning=tuning, packed=True)
+    run_and_check(wl.qwen_decode(shrink=4, n_tokens=200), path=B.LORA_PATH_FUSED, tuning=tuning)
