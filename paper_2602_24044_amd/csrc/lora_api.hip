@@ -327,8 +327,12 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
             const double t_part = (double)Mpad * (double)n_pad_total * 8.0 / 5e6;
             double best = 0.0;
             for (int cand = 1; cand <= 8; ++cand) {
-                const double rounds = (double)((tiles * cand + target - 1) / target);
-                const double cost = t_full * rounds / cand + t_part * cand;
+                // a single K range takes the fused path instead (below): every CU can hold a tile and there are
+                // no partial tiles at all
+                const bool fused_instead = cand == 1 && c->cfg.path == LORA_PATH_AUTO;
+                const long per_round = fused_instead ? 256 : target;
+                const double rounds = (double)((tiles * cand + per_round - 1) / per_round);
+                const double cost = t_full * rounds / cand + (fused_instead ? 0.0 : t_part * cand);
                 if (cand == 1 || cost < best) {
                     best = cost;
                     S = cand;
