@@ -408,3 +408,25 @@ def test_group_with_one_shared_input_tensor():
             assert rel_err(bf16_tensor_to_bits(s.out[p]), y_ref) <= TOL
     finally:
         s.close()
+
+
+def test_launches_do_not_depend_on_the_context_size():
+    # a context sized for more tokens has more scratch; the same step must take the same kernels (a cost model that
+    # priced a single K range like a split once sent gate|up down the split path as soon as scratch allowed two)
+    w = wl.config2(shrink=2, n_tokens=256)
+    seen = []
+    for max_tokens in (None, 4096):
+        s = Session(w, max_tokens=max_tokens)
+        try:
+            s.load(w.resident)
+            s.bucket()
+            per_group = []
+            for g in s.packed_groups():
+                s.forward_group(g) if len(g) > 1 else s.forward(g[0])
+                per_group.append(tuple(B.lora_last_launches(s.ctx)))
+            torch.cuda.synchronize()
+            seen.append(per_group)
+        finally:
+            s.close()
+    announce(f"launches per call: {seen[0]}")
+    assert seen[0] == seen[1]
