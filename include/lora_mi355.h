@@ -51,7 +51,8 @@ typedef enum {
     LORA_ERR_NOT_RESIDENT = 7,     /* reported by lora_poll_device_flags: a token named a non-resident adapter */
     LORA_ERR_HIP = 8,              /* a HIP runtime call failed (no device, bad stream, ...) */
     LORA_ERR_ID_RANGE = 9,         /* adapter id outside [0, max_adapter_id] */
-    LORA_ERR_STARVATION = 10       /* lora_place_adapters: no starvation-free allocation on the GPUs given */
+    LORA_ERR_STARVATION = 10,      /* lora_place_adapters: no starvation-free allocation on the GPUs given */
+    LORA_ERR_SCRATCH_LIMIT = 11    /* lora_layer_forward_static: the call needs more scratch than the static buffer holds */
 } lora_status;
 
 /* Segment-map modes (lora_bucket). */
@@ -187,6 +188,22 @@ lora_status lora_bucket(lora_ctx *ctx, const int32_t *d_token_adapter, int32_t T
  * Errors: INVALID_ARG (proj out of range, stale seg, null or misaligned pointers), HIP. */
 lora_status lora_layer_forward(lora_ctx *ctx, int32_t proj, const void *d_x, const void *d_W,
                                const lora_segments *seg, void *d_out, void *stream);
+
+/* lora_layer_forward for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and
+ * same kernels as lora_layer_forward, but the scratch of the call (split-K partial tiles, shrink results) lives in
+ * a buffer of lora_static_scratch_bytes() = 40 MiB that is part of the library image, one copy per GPU, held
+ * until the process ends, instead of the context's slab.  The call allocates nothing and frees nothing.  A call
+ * whose shrink results do not fit (more than 2 Mi values: tokens x max_rank x K chunks) or whose partial tiles do
+ * not fit even unsplit (more than 8 Mi values: tokens rounded up to 256 x d_out rounded up to 128) fails with
+ * LORA_ERR_SCRATCH_LIMIT before anything is enqueued; between those limits the K split shrinks to what fits, so
+ * the rounding order, not the tolerance, may differ from lora_layer_forward.  Nothing in the buffer has to start
+ * at zero: every value a call reads it has written itself.  All calls on one GPU, from every context, share the
+ * one buffer: two such calls that overlap in time on a GPU race; order them on one stream or by events.
+ * Errors: as lora_layer_forward, plus SCRATCH_LIMIT. */
+lora_status lora_layer_forward_static(lora_ctx *ctx, int32_t proj, const void *d_x, const void *d_W,
+                                      const lora_segments *seg, void *d_out, void *stream);
+size_t lora_static_scratch_bytes(void);
 
 /* Packed projections (paper Sec. 2.2 applied to projections that are computed from one layer input side by
  * side, such as q|k|v and gate|up): the same result as n calls of lora_layer_forward for projs[0..n-1] in

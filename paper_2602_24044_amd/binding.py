@@ -52,6 +52,7 @@ LORA_ERR_NOT_RESIDENT = 7
 LORA_ERR_HIP = 8
 LORA_ERR_ID_RANGE = 9
 LORA_ERR_STARVATION = 10
+LORA_ERR_SCRATCH_LIMIT = 11
 LORA_BUCKET_SORTED = 0
 LORA_BUCKET_RUNS = 1
 LORA_PATH_AUTO = 0
@@ -66,7 +67,7 @@ EXPORTS = [
     "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
+    "lora_last_hip_error", "lora_layer_forward_static", "lora_static_scratch_bytes", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
 ]
 LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
@@ -120,6 +121,10 @@ _lib.lora_bucket.restype = ctypes.c_int
 _lib.lora_bucket.argtypes = [_P, _P, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(lora_segments), _P]
 _lib.lora_layer_forward.restype = ctypes.c_int
 _lib.lora_layer_forward.argtypes = [_P, ctypes.c_int32, _P, _P, ctypes.POINTER(lora_segments), _P, _P]
+_lib.lora_layer_forward_static.restype = ctypes.c_int
+_lib.lora_layer_forward_static.argtypes = [_P, ctypes.c_int32, _P, _P, ctypes.POINTER(lora_segments), _P, _P]
+_lib.lora_static_scratch_bytes.restype = ctypes.c_size_t
+_lib.lora_static_scratch_bytes.argtypes = []
 _lib.lora_layer_forward_group.restype = ctypes.c_int
 _lib.lora_layer_forward_group.argtypes = [_P, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(_P),
                                           ctypes.POINTER(_P), ctypes.POINTER(lora_segments), ctypes.POINTER(_P), _P]
@@ -240,6 +245,18 @@ def lora_layer_forward(ctx: int, proj: int, d_x: int, d_W: int, seg: lora_segmen
                                  _P(d_out or None), _P(stream or None))
     if st != LORA_OK:
         raise LoraError(st, "lora_layer_forward")
+
+
+def lora_layer_forward_static(ctx: int, proj: int, d_x: int, d_W: int, seg: lora_segments, d_out: int,
+                              stream: int = 0) -> None:
+    st = _lib.lora_layer_forward_static(_P(ctx), int(proj), _P(d_x or None), _P(d_W or None), ctypes.byref(seg),
+                                        _P(d_out or None), _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_layer_forward_static")
+
+
+def lora_static_scratch_bytes() -> int:
+    return int(_lib.lora_static_scratch_bytes())
 
 
 def lora_layer_forward_group(ctx: int, projs: Sequence[int], d_x: Sequence[int], d_W: Sequence[int],

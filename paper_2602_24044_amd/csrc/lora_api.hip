@@ -6,11 +6,20 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 using namespace lora;
+
+// Scratch of lora_layer_forward_static, for callers that may not allocate and hand in no workspace: split-K
+// partial tiles first, the shrink results behind them.  Every GPU the library runs on holds its own copy of the
+// array until the process ends.  In host code this name is only a handle for hipGetSymbolAddress: the kernels
+// get the address that call returns (static_scratch_of), never the name itself.
+constexpr size_t kStaticPartBytes = 32u << 20;
+constexpr size_t kStaticVpartBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticPartBytes + kStaticVpartBytes];
 
 namespace {
 
@@ -24,6 +33,24 @@ inline bool hip_fail(hipError_t e, const char* what)
     return true;
 }
 #define HIP_FAIL(call) hip_fail((call), #call)
+
+// Device address of `scratch` on the current device, looked up once per device (with that device current).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+bool static_scratch_of(int device, void** out)
+{
+    if (device < 0 || device >= kMaxDevices) return false;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        if (HIP_FAIL(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return false;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return true;
+}
 
 constexpr size_t kAlign = 256;
 constexpr size_t kEngineRunBytes = 1u << 20;   // shortest run for which a copy call per run pays
@@ -168,6 +195,8 @@ struct lora_ctx {
     Layout L;
     bool host_only = false;
     char* base = nullptr;
+    int device = -1;                        // the device the context was created on
+    char* static_scratch = nullptr;         // that device's copy of `scratch` (lora_layer_forward_static)
 
     // host slot table
     std::vector<int32_t> slot_adapter, slot_rank_h;
@@ -273,7 +302,8 @@ struct ForwardPlan {
     int n_kc = 1, kc_len = 0;   // K chunks of the shrink and their length
 };
 
-lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t* projs, ForwardPlan& out)
+lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t* projs, size_t part_elems,
+                         ForwardPlan& out)
 {
     const int K = c->proj[projs[0]].d_in;
     // the slices sit side by side along N, each padded to a multiple of 128 columns
@@ -340,9 +370,9 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
             }
         }
         S = std::min(S, std::max(1, (K / kBK) / 2));
-        const size_t cap = c->L.part_elems / ((size_t)Mpad * (size_t)n_pad_total);
+        const size_t cap = part_elems / ((size_t)Mpad * (size_t)n_pad_total);
         S = (int)std::min<size_t>((size_t)S, std::max<size_t>(cap, 1));
-        if ((size_t)S * Mpad * (size_t)n_pad_total > c->L.part_elems) return LORA_ERR_OOM;
+        if ((size_t)S * Mpad * (size_t)n_pad_total > part_elems) return LORA_ERR_OOM;
         // a single K range would only add the round trip of the partial tiles: the launch already fills
         // the chip, take the fused path with the same tile
         if (S == 1 && c->cfg.path == LORA_PATH_AUTO) split = false;
@@ -400,6 +430,7 @@ const char* lora_status_string(lora_status s)
         case LORA_ERR_HIP: return "HIP runtime error";
         case LORA_ERR_ID_RANGE: return "adapter id out of range";
         case LORA_ERR_STARVATION: return "no starvation-free placement";
+        case LORA_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -451,6 +482,13 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
             return LORA_ERR_OOM;
         }
         c->base = static_cast<char*>(cfg->slab);
+        // this device's copy of the static scratch array (lora_layer_forward_static), looked up once per device
+        void* sp = nullptr;
+        if (HIP_FAIL(hipGetDevice(&c->device)) || !static_scratch_of(c->device, &sp)) {
+            delete c;
+            return LORA_ERR_HIP;
+        }
+        c->static_scratch = static_cast<char*>(sp);
         bool ok = !HIP_FAIL(hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming)) &&
                   !HIP_FAIL(hipEventCreateWithFlags(&c->ev_fwd, hipEventDisableTiming));
         for (size_t u = 0; ok && u < n_units; ++u)
@@ -755,9 +793,23 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     return LORA_OK;
 }
 
-lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, const int32_t* projs,
-                                     const void* const* d_x, const void* const* d_W, const lora_segments* seg,
-                                     void* const* d_out, void* stream_v)
+}  // extern "C"
+
+namespace {
+
+// Where a forward call keeps its split-K partial tiles and shrink results: the context's slab, or the library's
+// static array (lora_layer_forward_static).
+struct ScratchRef {
+    float* vpart;
+    size_t vpart_elems;
+    float* part;
+    size_t part_elems;
+    bool is_static;
+};
+
+lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* projs, const void* const* d_x,
+                         const void* const* d_W, const lora_segments* seg, void* const* d_out, void* stream_v,
+                         const ScratchRef& scr)
 {
     if (!c || !seg || !projs || n < 1 || n > kMaxGroup) return LORA_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->n_layers) return LORA_ERR_INVALID_ARG;
@@ -788,7 +840,8 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
         }
     }
     ForwardPlan plan;
-    if (const lora_status st = plan_forward(c, T, n, projs, plan); st != LORA_OK) return st;
+    if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, plan); st != LORA_OK)
+        return (st == LORA_ERR_OOM && scr.is_static) ? LORA_ERR_SCRATCH_LIMIT : st;
     const int K = plan.K, Mpad = plan.Mpad, n_max = plan.n_max, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
     const long n_pad_total = plan.n_pad_total;
     const bool split = plan.split, dyn_shrink = plan.dyn_shrink;
@@ -799,11 +852,11 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
         return t * ((T + bm - 1) / bm);
     };
     const size_t vslice = (size_t)n_kc * T * c->cfg.max_rank;
-    if (vslice * n > c->L.vpart_elems) return LORA_ERR_OOM;
+    if (vslice * n > scr.vpart_elems) return scr.is_static ? LORA_ERR_SCRATCH_LIMIT : LORA_ERR_OOM;
 
     const DeviceView dv = c->view(T);
-    float* vpart = c->dev<float>(c->L.off_vpart);
-    float* part = c->dev<float>(c->L.off_part);
+    float* vpart = scr.vpart;
+    float* part = scr.part;
 
     GroupArgs g;
     std::memset(&g, 0, sizeof g);
@@ -929,7 +982,7 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
                     const long tail_pad = (tail_rows + 255) / 256 * 256;
                     long ts = std::max<long>(1, std::min<long>(8, (256 + tail_tiles / 2) / tail_tiles));
                     ts = std::min<long>(ts, std::max(1, (K / kBK) / 2));
-                    ts = std::min<long>(ts, (long)(c->L.part_elems / ((size_t)tail_pad * (size_t)n_pad_total)));
+                    ts = std::min<long>(ts, (long)(scr.part_elems / ((size_t)tail_pad * (size_t)n_pad_total)));
                     if (ts >= 2) {
                         m_split = (int)(m_tiles_main * 256);
                         tail_S = (int)ts;
@@ -998,6 +1051,39 @@ lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, cons
     c->have_fwd = true;
     return LORA_OK;
 }
+
+ScratchRef slab_scratch(const lora_ctx* c)
+{
+    if (!c || c->host_only) return ScratchRef{nullptr, 0, nullptr, 0, false};
+    return ScratchRef{c->dev<float>(c->L.off_vpart), c->L.vpart_elems, c->dev<float>(c->L.off_part), c->L.part_elems, false};
+}
+
+}  // namespace
+
+extern "C" {
+
+lora_status lora_model_forward_group(lora_ctx* c, int32_t layer, int32_t n, const int32_t* projs,
+                                     const void* const* d_x, const void* const* d_W, const lora_segments* seg,
+                                     void* const* d_out, void* stream_v)
+{
+    return forward_impl(c, layer, n, projs, d_x, d_W, seg, d_out, stream_v, slab_scratch(c));
+}
+
+lora_status lora_layer_forward_static(lora_ctx* c, int32_t p, const void* d_x, const void* d_W, const lora_segments* seg,
+                                      void* d_out, void* stream_v)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    if (c->host_only || !c->static_scratch) return LORA_ERR_HIP;
+    ScratchRef scr;
+    scr.part = reinterpret_cast<float*>(c->static_scratch);
+    scr.part_elems = kStaticPartBytes / 4;
+    scr.vpart = reinterpret_cast<float*>(c->static_scratch + kStaticPartBytes);
+    scr.vpart_elems = kStaticVpartBytes / 4;
+    scr.is_static = true;
+    return forward_impl(c, 0, 1, &p, &d_x, &d_W, seg, &d_out, stream_v, scr);
+}
+
+size_t lora_static_scratch_bytes(void) { return kStaticPartBytes + kStaticVpartBytes; }
 
 lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,
                                      const void* const* d_W, const lora_segments* seg, void* const* d_out,
