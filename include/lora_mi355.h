@@ -279,7 +279,9 @@ enum {
     LORA_FUSED_128x128x64_W4 = 9,
     LORA_FUSED_256x256x64_W8 = 10,
     LORA_FUSED_256x192x64_W8 = 11,
-    LORA_FUSED_256x256x32_W8 = 12         /* what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
+    LORA_FUSED_256x256x32_W8 = 12,        /* what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
+    LORA_FUSED_256x128x64_W4 = 13,        /* four wavefronts with 128 x 64 wave tiles: fewer LDS reads per MFMA */
+    LORA_FUSED_256x256x64_W4 = 14
 };
 /* Values of LORA_TUNE_SPLIT_VARIANT. */
 enum {
@@ -290,7 +292,8 @@ enum {
     LORA_SPLIT_128x128x32_W4_8STAGES = 4,
     LORA_SPLIT_256x128x64_W8 = 6,
     LORA_SPLIT_128x128x64_W4 = 7,
-    LORA_SPLIT_256x128x32_W8 = 8
+    LORA_SPLIT_256x128x32_W8 = 8,
+    LORA_SPLIT_256x128x64_W4 = 9
 };
 lora_status lora_set_tuning(lora_ctx *ctx, int32_t key, int32_t value);
 

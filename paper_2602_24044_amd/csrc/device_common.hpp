@@ -333,12 +333,18 @@ __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// LoRA expand for MB consecutive 32-row windows held by one wavefront, as one pipelined pass over the
-// (window, distinct slot) pairs: the B fragments of the next D - 1 pairs are in flight while the current
-// pair's MFMAs run, across window boundaries (every pair's fragments are a dependent global load: the depth
-// of the ring sets the duration of the pass).  slot / rank: the lane's row of each window (slot -1 or rank 0:
-// backbone only).  sV: the windows' scaled shrink results in LDS, window mb at
-// sV + mb * kPieceRows * kVStageStride.
+// LoRA expand for MB consecutive 32-row windows held by one wavefront, as one pipelined pass over work items
+// (window, distinct slot, K step of 16 ranks): an adapter of rank 8 or 16 is one item per window it appears in,
+// rank 32 two, rank 64 four.  Every item is NB loads of 16 bytes per lane (the B fragments of its rank range, one
+// per 32-column block) and NB MFMAs; the fragments of the next D - 1 items are in flight while the current
+// item's MFMAs run, across pair and window boundaries (the fragments are a dependent global load: the depth of
+// the ring sets the duration of the pass).  The loads are unconditional and the same number for every item, also
+// for the D - 1 items requested past the end of the list (they read the start of the slot region): loads behind
+// a branch, or a number of loads that depends on the adapter, would leave the compiler unable to tell an item's
+// own loads from the younger ones, and every item would wait for all loads in flight.  Lanes whose column or
+// rank range does not exist read an existing place (row N - 1, rank offset 0); what they load is replaced by zeros.
+// slot / rank: the lane's row of each window (slot -1 or rank 0: backbone only).  sV: the windows' scaled
+// shrink results in LDS, window mb at sV + mb * kPieceRows * kVStageStride.
 // ---------------------------------------------------------------------------------------------------
 template <int MB, int NB, int D>
 __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB], int n_first,
@@ -350,38 +356,43 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) todo[mb] = __ballot(slot[mb] >= 0 && rank[mb] > 0);
     struct Item {
-        int mb, s, r;
+        int mb, s, r, ks;
         bool valid;
     };
+    Item cur{0, 0, 8, 0, false};                              // the pair the generator is inside of
     auto next_item = [&]() {
-        Item q{0, -1, 0, false};
+        if (cur.valid && (cur.ks + 1) * 16 < cur.r) {         // uniform over the wave
+            ++cur.ks;
+            return cur;
+        }
+        Item q{0, 0, 8, 0, false};
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if (!q.valid && todo[mb]) {                       // uniform over the wave
                 const int leader = __ffsll((long long)todo[mb]) - 1;
                 q.mb = mb;
-                q.s = __shfl(slot[mb], leader, kWave);
-                q.r = __shfl(rank[mb], leader, kWave);
+                q.s = __builtin_amdgcn_readfirstlane(__shfl(slot[mb], leader, kWave));
+                q.r = __builtin_amdgcn_readfirstlane(__shfl(rank[mb], leader, kWave));
                 q.valid = true;
                 todo[mb] &= ~__ballot(slot[mb] == q.s);
             }
         }
+        cur = q;
         return q;
     };
     struct Frag {
-        u32x4 f[NB][4];
+        u32x4 f[NB];
     };
+    // an item past the end of the list has s = 0, r = 8, ks = 0: the first bytes of the slot region
     auto fetch = [&](const Item& q, Frag& fb) {
+        const int k = q.ks * 16 + h * 8;
+        const int kc = k < q.r ? k : 0;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const int n = n_first + nb * 32 + i;
+            int n = n_first + nb * 32 + i;
+            if (n > N - 1) n = N - 1;
             const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + ((size_t)q.r * b_unit + (size_t)n * q.r);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int k = ks * 16 + h * 8;
-                fb.f[nb][ks] = u32x4{0u, 0u, 0u, 0u};
-                if (q.valid && n < N && k < q.r) fb.f[nb][ks] = load16(Bs + k);
-            }
+            fb.f[nb] = load16(Bs + kc);
         }
     };
     auto apply = [&](const Item& q, const Frag& fb) {
@@ -389,26 +400,24 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
 #pragma unroll
         for (int mb = 1; mb < MB; ++mb)
             if (q.mb == mb) my = slot[mb];
-        const bool mine = my == q.s;
+        const int k = q.ks * 16 + h * 8;
+        const bool k_on = k < q.r;                            // beyond the rank the lane loaded a stand-in
         const uint16_t* vrow = sV + (q.mb * kPieceRows + i) * kVStageStride;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (my == q.s && k_on) v = *reinterpret_cast<const u32x4*>(vrow + k);
+        const bf16x8 vf = as_bf16x8(v);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks * 16 < q.r) {
-                const int k = ks * 16 + h * 8;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (mine && k < q.r) v = *reinterpret_cast<const u32x4*>(vrow + k);
-                const bf16x8 vf = as_bf16x8(v);
+        for (int mb = 0; mb < MB; ++mb) {
+            if (q.mb == mb) {                                 // uniform over the wave
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    if (q.mb == mb) {                         // uniform over the wave
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(as_bf16x8(fb.f[nb][ks]), vf, acc[mb][nb]);
-                    }
+                for (int nb = 0; nb < NB; ++nb) {
+                    const u32x4 bf = k_on ? fb.f[nb] : u32x4{0u, 0u, 0u, 0u};
+                    acc[mb][nb] = mfma32(as_bf16x8(bf), vf, acc[mb][nb]);
                 }
             }
         }
     };
-    // ring of D pairs, consumed in ring order; position d is refilled right after its pair has been applied
+    // ring of D items, consumed in ring order; position d is refilled right after its item has been applied
     Frag f[D];
     Item q[D];
 #pragma unroll
@@ -416,7 +425,7 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
         q[d] = next_item();
         fetch(q[d], f[d]);
     }
-    while (q[0].valid) {                                      // a pass without a pair at position 0 has none at all
+    while (q[0].valid) {                                      // a pass without an item at position 0 has none at all
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             if (q[d].valid) apply(q[d], f[d]);                // uniform over the wave

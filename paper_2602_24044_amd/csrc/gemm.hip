@@ -51,6 +51,10 @@ __device__ inline void static_for(F&& f)
 // otherwise drain all copies before any LDS read whose stage it cannot tell apart).
 __device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
 {
+    // m0 carries the LDS address.  It cannot be named as a clobber (a reserved register: the compiler rejects
+    // it) and needs none: the compiler keeps no value in m0 between statements, it writes m0 itself directly in
+    // front of each instruction of its own that reads it.  Putting the old value back after the copy was tried
+    // and stalls every copy (the write to m0 waits until the copy instruction has read it): + 0.2 us per K tile.
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
 }
 
@@ -244,8 +248,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, Shrin
                 asm volatile("" ::: "memory");
                 static_for<NI>([&](auto it) {
                     if constexpr (it.value * NM / NI == t.value) {
-                        if constexpr (COPY && it.value < QA) copy_one(fre1, it.value, k0);
-                        else read_one(I0{}, nxt, 0, it.value - (COPY ? QA : 0));
+                        // the reads first: the next iteration's first MFMA needs all of them
+                        if constexpr (it.value < NR) read_one(I0{}, nxt, 0, it.value);
+                        else copy_one(fre1, it.value - NR, k0);
                     }
                 });
                 asm volatile("" ::: "memory");

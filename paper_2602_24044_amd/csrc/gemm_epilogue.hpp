@@ -21,6 +21,9 @@
 namespace lora {
 
 constexpr int kEpiWindows = 2;                    // windows per pass
+// expand work items in flight per wave: about 16 fragment loads (64 registers)
+template <int NB>
+constexpr int kExpandDepth = NB >= 4 ? 4 : (NB == 3 ? 5 : 8);
 // bytes of the ring one wave uses in the fused epilogue: shrink results of two windows, or two windows of
 // NB * 32 bf16 output columns
 template <int NB>
@@ -116,27 +119,103 @@ __device__ __forceinline__ void store_windows(const f32x16 (&acc)[WB][NB], const
 }
 
 // Fused path, wave tiles of at most two 32-row windows: what the epilogue needs from memory besides the B rows
-// is fetched before the main loop and waits in registers.
+// is fetched ahead of it and waits in registers.  Two parts: what the segment map gives (slot and rank of the
+// lane's rows; rank and scale of the rows whose shrink results the lane converts) is there before the launch and
+// is fetched before the main loop; the shrink results themselves may come from workgroups of the same launch
+// and are fetched once those have reported (prefetch_v), in one round of loads per K chunk.
 template <int MB>
 struct TilePrefetch {
     int slot[MB], rank[MB];          // this lane's row of each window
+    int srank[MB][4];                // rank / scale of the row of each of this lane's four shares of a window
+    float sscale[MB][4];
+    f32x4 lo[MB][4], hi[MB][4];      // the shares as loaded (first K chunk), before scaling and rounding
     u32x4 v[MB][4];                  // this lane's shares of the windows' scaled shrink results (packed bf16)
 };
 
 template <int MB>
-__device__ __forceinline__ void prefetch_windows(TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int m_first)
+__device__ __forceinline__ void prefetch_rows(TilePrefetch<MB>& pf, const GemmArgs& a, int m_first)
 {
     static_assert(MB <= kEpiWindows, "prefetch covers one pass");
-    const int i = threadIdx.x & 31;
+    const int lane = threadIdx.x & (kWave - 1), i = lane & 31;
+    const int last = a.m_end - 1;                                 // every load reads an existing row
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_first + mb * 32 + i;
-        const bool ok = m < a.m_end;
-        pf.slot[mb] = ok ? a.dv.row_slot[m] : -1;
-        pf.rank[mb] = ok ? a.dv.row_rank[m] : 0;
+        const int mc = m < a.m_end ? m : last;
+        const int s = a.dv.row_slot[mc], r = a.dv.row_rank[mc];
+        pf.slot[mb] = m < a.m_end ? s : -1;
+        pf.rank[mb] = m < a.m_end ? r : 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) pf.v[mb][q] = window_v_share(q, sl.vpart, a.n_kc, m_first + mb * 32, a.dv);
+        for (int q = 0; q < 4; ++q) {
+            const int idx = lane + 64 * q;
+            const int mr = m_first + mb * 32 + (idx >> 3);
+            const bool on = mr < a.m_end && (idx & 7) * 8 < a.dv.max_rank;
+            const int mrc = mr < a.m_end ? mr : last;
+            const int rr = a.dv.row_rank[mrc];
+            const float sc = a.dv.row_scale[mrc];
+            pf.srank[mb][q] = on ? rr : 0;
+            pf.sscale[mb][q] = on ? sc : 0.f;
+            pf.v[mb][q] = u32x4{0u, 0u, 0u, 0u};
+        }
     }
+}
+
+// Shares of the scaled shrink results: share q of window mb is (row, seg) = ((lane + 64 q) / 8, (lane + 64 q) % 8)
+// -> bf16(scale_row * sum_c vpart[c][row][8 seg .. 8 seg + 7]), zero beyond the row's rank.  Every lane loads
+// (lanes without a share read row 0 and drop the result), all shares of a K chunk in one round.  Two steps, so
+// that the round trip of the first chunk can pass behind other work: prefetch_v_issue only requests it,
+// prefetch_v_finish adds the other chunks (none when the shrink ran unsplit), scales and rounds.
+template <int MB>
+__device__ __forceinline__ const float* share_address(const TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl,
+                                                      int m_first, int mb, int q)
+{
+    const int idx = (threadIdx.x & (kWave - 1)) + 64 * q;
+    const int mr = m_first + mb * 32 + (idx >> 3), seg = idx & 7;
+    const bool live = seg * 8 < pf.srank[mb][q];               // implies the row exists
+    return sl.vpart + (live ? (size_t)mr * a.dv.max_rank + seg * 8 : 0);
+}
+
+template <int MB>
+__device__ __forceinline__ void prefetch_v_issue(TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int m_first)
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float* vp = share_address(pf, a, sl, m_first, mb, q);
+            pf.lo[mb][q] = *reinterpret_cast<const f32x4*>(vp);
+            pf.hi[mb][q] = *reinterpret_cast<const f32x4*>(vp + 4);
+        }
+}
+
+template <int MB>
+__device__ __forceinline__ void prefetch_v_finish(TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int m_first)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t chunk = (size_t)a.dv.T * a.dv.max_rank;
+    for (int c = 1; c < a.n_kc; ++c) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float* vp = share_address(pf, a, sl, m_first, mb, q) + c * chunk;
+                pf.lo[mb][q] += *reinterpret_cast<const f32x4*>(vp);
+                pf.hi[mb][q] += *reinterpret_cast<const f32x4*>(vp + 4);
+            }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x8 vb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vb[e] = (__bf16)(pf.lo[mb][q][e] * pf.sscale[mb][q]);
+                vb[4 + e] = (__bf16)(pf.hi[mb][q][e] * pf.sscale[mb][q]);
+            }
+            const bool live = ((lane + 64 * q) & 7) * 8 < pf.srank[mb][q];
+            pf.v[mb][q] = live ? __builtin_bit_cast(u32x4, vb) : u32x4{0u, 0u, 0u, 0u};
+        }
 }
 
 // Epilogue of the fused path from prefetched window data.  ring: LDS free again (the caller has synchronised).
@@ -156,7 +235,7 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
 #pragma unroll
             for (int q = 0; q < 4; ++q) park_v_share(sV + mb * kPieceRows * kVStageStride, q, pf.v[mb][q]);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        expand_windows<MB, NB, (NB > 2 ? 2 : 4)>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_unit, sV);
+        expand_windows<MB, NB, kExpandDepth<NB>>(acc, pf.slot, pf.rank, n_first, sl.N, a.dv, sl.b_unit, sV);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     store_windows<MB, NB>(acc, a, sl, m_first, n_first, mine);
@@ -205,7 +284,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
                     ps[w] = slot[p * WB + w];
                     pr[w] = rank[p * WB + w];
                 }
-                expand_windows<WB, NB, (MB > 2 ? 2 : 3)>(pair, ps, pr, n_first, N, a.dv, sl.b_unit, sV);
+                expand_windows<WB, NB, kExpandDepth<NB>>(pair, ps, pr, n_first, N, a.dv, sl.b_unit, sV);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the piece is reused
             }
             store_windows<WB, NB>(pair, a, sl, m_first + p * WB * 32, n_first, mine);

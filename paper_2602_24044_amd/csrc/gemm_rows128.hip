@@ -24,6 +24,7 @@
 namespace lora {
 namespace {
 
+constexpr bool kWarmB = false;
 constexpr int kTK64 = 64;    // K extent of one LDS tile (bf16 elements): 128-byte rows
 constexpr int kRowB = 128;
 
@@ -31,7 +32,46 @@ __device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
 {
     // issued from inline assembly: the only ordering against later LDS reads is the explicit vmcnt wait +
     // barrier of the main loop
+    // m0 carries the LDS address.  It cannot be named as a clobber (a reserved register: the compiler rejects
+    // it) and needs none: the compiler keeps no value in m0 between statements, it writes m0 itself directly in
+    // front of each instruction of its own that reads it.  Putting the old value back after the copy was tried
+    // and stalls every copy (the write to m0 waits until the copy instruction has read it): + 0.2 us per K tile.
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// One dword per lane, global -> LDS (lane l lands at lds_addr + 4 l), coherent at device scope: the poll of a
+// counter that other workgroups of the launch advance.
+__device__ inline void poll4_to_lds(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off sc1" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// Touches the B rows the wave's expand will read (columns n_first .. n_first + wtn of every adapter its rows
+// use: one contiguous run of wtn * rank bf16 per adapter) so that they wait in L2 when the epilogue asks for them;
+// the loads land in a piece of LDS nobody reads.  Ordered like every other copy of the wave (vmcnt).
+template <int MB>
+__device__ __forceinline__ void warm_b_rows(const TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int n_first,
+                                            int wtn, uint32_t dump_addr)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int ncols = sl.N - n_first;
+    if (ncols > wtn) ncols = wtn;
+    if (ncols <= 0) return;                                       // uniform over the wave
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        unsigned long long todo = __ballot(pf.slot[mb] >= 0 && pf.rank[mb] > 0);
+        while (todo) {                                            // uniform over the wave
+            const int leader = __ffsll((long long)todo) - 1;
+            const int sl_id = __shfl(pf.slot[mb], leader, kWave);
+            const int r = __shfl(pf.rank[mb], leader, kWave);
+            todo &= ~__ballot(pf.slot[mb] == sl_id);
+            const uint8_t* run = reinterpret_cast<const uint8_t*>(a.dv.slots + (size_t)sl_id * a.dv.slot_stride +
+                                                                  ((size_t)r * sl.b_unit + (size_t)n_first * r));
+            const int bytes = ncols * r * 2;
+            for (int o = lane * 16; o - lane * 16 < bytes; o += 1024)
+                if (o < bytes) copy16_to_lds(run + o, dump_addr);
+        }
+    }
 }
 
 template <int N>
@@ -55,6 +95,11 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     static_assert(NS * STAGE_B <= 160 * 1024, "LDS");
 
     __shared__ __attribute__((aligned(1024))) uint8_t ring[NS * STAGE_B];
+    // fused path, shrink inside the launch: the shrink workgroups' counter as polled during the main loop, the
+    // verdict for the whole workgroup, and the landing place of the warm-up loads
+    __shared__ uint32_t s_poll[kWave];
+    __shared__ uint32_t s_early;
+    __shared__ __attribute__((aligned(1024))) uint8_t s_dump[1024];
     // split path: the workgroups past the tile grid only do shrink items
     const int extra = (int)gridDim.x - a.main_grid;          // shrink-only workgroups of this launch
     if (!FUSED && sa.on && (int)blockIdx.x >= a.main_grid) {
@@ -180,8 +225,30 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     constexpr bool PRE = FUSED && MB <= 2;
     TilePrefetch<PRE ? MB : 1> pre;
     if constexpr (PRE) {
-        if (front == 0) prefetch_windows(pre, a, sl, m0 + wm * WTM);      // else: not there yet
+        prefetch_rows(pre, a, m0 + wm * WTM);
+        if (front == 0) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);      // else: not there yet
     }
+    // Shrink inside the launch: the tile workgroups need its results only in the epilogue.  The counter of the
+    // shrink workgroups is polled four tiles before the end (a copy into LDS, ordered like the tile copies: it
+    // has landed when tile nk - 2 has); two tiles before the end one thread reads the verdict, makes the shrink
+    // results visible and publishes it; during the last tile every wave requests its shares of the results.
+    // When the poll came too early the wait after the loop takes over.
+    bool early = false;
+    const bool poll_on = PRE && front > 0 && nk >= 4;
+    const uint32_t poll_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)s_poll;
+    const uint32_t dump_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)s_dump;
+    // Past the wait for the shrink workgroups every tile workgroup takes a ticket; the one with the last ticket
+    // sets the two counters back to zero for the next launch (at the end of the kernel: nobody of this launch
+    // looks at them any more).  The ticket is requested here and read only then, so that nobody waits for it.
+    uint32_t ticket = 0;
+    bool have_ticket = false;                                // thread 0 only
+    auto passed_the_wait = [&]() {
+        ticket = atomicAdd(a.sync + 1, 1u);
+        have_ticket = true;
+        // what the shrink workgroups wrote is read from here on: drop what this CU and this L2 may hold of it
+        // (the acquire side; no wait for older loads is needed, the poll that showed the counter has landed)
+        asm volatile("buffer_inv sc1" ::: "memory");
+    };
 
     int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
     for (int j = 0; j < nk; ++j) {
@@ -192,6 +259,23 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         else if (young == 2) wait_copies_then_barrier<(NS >= 4 ? 2 : 0) * QPT>();
         else if (young == 1) wait_copies_then_barrier<QPT>();
         else wait_copies_then_barrier<0>();
+        if constexpr (PRE) {
+            if (poll_on) {
+                if (j == nk - 4 && wave == 0) poll4_to_lds(a.sync, __builtin_amdgcn_readfirstlane(poll_addr));
+                if (j == nk - 2 && threadIdx.x == 0) {
+                    const bool done = s_poll[0] >= (uint32_t)front;     // landed: older than the copies the wait above let pass
+                    if (done) passed_the_wait();
+                    s_early = done ? 1u : 0u;
+                }
+                if (j == nk - 1) {
+                    early = s_early != 0u;
+                    if (kWarmB) warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
+                    if (early) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);
+                }
+            } else if (kWarmB && front == 0 && j == nk - 1) {
+                warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
+            }
+        }
         // tile j is complete for every wave and every wave has finished tile j - 1: refill its stage
         // The copy instructions are spread over the four K steps: a wave that is held at a copy instruction
         // by a full memory pipeline cannot issue its MFMAs meanwhile.
@@ -225,7 +309,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     static_assert(!FUSED || NS * STAGE_B >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
     static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
-    if (FUSED && front > 0) {
+    if (FUSED && front > 0 && !early) {                           // uniform over the workgroup
         // The shrink results come from the workgroups at the front of this launch.  They hold the lowest
         // indices, so they were dispatched before this workgroup and never wait for anything: the wait ends.
         // It is bounded all the same; if it expires the call's result is invalid and flagged.
@@ -238,17 +322,12 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
                 }
                 __builtin_amdgcn_s_sleep(32);
             }
-            // past the wait: the last tile workgroup to get here sets the counters back for the next launch
-            const uint32_t tiles = gridDim.x - (uint32_t)front;
-            if (atomicAdd(a.sync + 1, 1u) == tiles - 1) {
-                __hip_atomic_store(a.sync, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.sync + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // what the shrink workgroups wrote is read from here on
+            passed_the_wait();
         }
         __syncthreads();
-        if constexpr (PRE) prefetch_windows(pre, a, sl, m0 + wm * WTM);
+        if constexpr (PRE) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);
     }
+    if constexpr (PRE) prefetch_v_finish(pre, a, sl, m0 + wm * WTM);
     if constexpr (PRE)
         finish_tile_prefetched<MB, NB>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, wave, reinterpret_cast<uint16_t*>(ring), pre);
     else
@@ -256,6 +335,11 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     if (!FUSED && sa.on) {
         __syncthreads();
         shrink_block_items<NWV>(sa, rest_first, gridDim.x, spf.n_items, reinterpret_cast<float*>(ring), spf);
+    }
+    if (FUSED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy of this wave is still on its way
+    if (FUSED && have_ticket && ticket == gridDim.x - (uint32_t)front - 1u) {
+        __hip_atomic_store(a.sync, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.sync + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -294,6 +378,12 @@ hipError_t launch_gemm_rows128_fused(const GemmArgs& a, const ShrinkArgs& none, 
         case 3:
             *name = "gemm_fused_256x192x64_w8";
             return launch_rows128<256, 192, 4, 2, true, 2>(a, none, stream);
+        case 4:
+            *name = "gemm_fused_256x128x64_w4";
+            return launch_rows128<256, 128, 2, 2, true, 3>(a, none, stream);
+        case 5:
+            *name = "gemm_fused_256x256x64_w4";
+            return launch_rows128<256, 256, 2, 2, true, 2>(a, none, stream);
         default:
             *name = "gemm_fused_256x128x64_w8";
             return launch_rows128<256, 128, 4, 2, true, 3>(a, none, stream);
@@ -307,6 +397,9 @@ hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, i
         case 1:
             *name = "gemm_splitk_shrink_128x128x64_w4";
             return launch_rows128<128, 128, 2, 2, false, 4>(a, sa, stream);
+        case 2:
+            *name = "gemm_splitk_shrink_256x128x64_w4";
+            return launch_rows128<256, 128, 2, 2, false, 3>(a, sa, stream);
         default:
             *name = "gemm_splitk_shrink_256x128x64_w8";
             return launch_rows128<256, 128, 4, 2, false, 3>(a, sa, stream);

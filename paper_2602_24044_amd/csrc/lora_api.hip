@@ -343,7 +343,7 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
         // Only while those workgroups can finish the items meanwhile: a batch spread over hundreds of adapters
         // has more shrink work than tile work, and every workgroup takes its share after its tile instead.
         const long pieces_bound = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
-        dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7) &&
+        dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7 || split_variant == 9) &&
                      pieces_bound * std::max(1, K / 2048) <= 512;
         const long target = dyn_shrink ? 192 : 256;
         // K splits, at most 8, by a cost model in microseconds: a workgroup walking all of K moves (bm + bn) K
@@ -917,8 +917,8 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             LaunchScope ls(c, s, "gemm_splitk");
             const char* name = nullptr;
             // 6, 7: 64-wide K tiles; 8: the 32-wide 256 x 128 kernel (its own variant 0); 1 .. 5: 32-wide variants
-            const hipError_t le = (variant == 6 || variant == 7)
-                                      ? launch_gemm_rows128_splitk(a, shrink, variant - 6, s, &name)
+            const hipError_t le = (variant == 6 || variant == 7 || variant == 9)
+                                      ? launch_gemm_rows128_splitk(a, shrink, variant == 9 ? 2 : variant - 6, s, &name)
                                       : launch_gemm_splitk(a, shrink, variant == 8 ? 0 : variant, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
@@ -998,12 +998,14 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             c->tune[LORA_TUNE_INLINE_SHRINK] != LORA_INLINE_SHRINK_OFF) {
             const int bm = fv == 9 ? 128 : 256, bn = fv == 10 ? 256 : (fv == 11 ? 192 : 128);
             const long idle = 256 - tiles_of(bm, bn);
-            const int chunks = std::max(1, std::min<int>(kMaxShrinkChunks, K / 2048));   // one round of loads per item
+            // unsplit up to K = 4096 (two rounds of loads per item): the tile workgroups then fetch one partial
+            // result per row instead of two, behind their last K tile
+            const int chunks = std::max(1, std::min<int>(kMaxShrinkChunks, K / 4096));
             const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
             const double t_main = (double)(bm + bn) * K * 2.0 / 48e3;                   // us, see plan_forward
             if (idle >= 8 && chunks <= n_kc &&      // the scratch for the shrink results is sized for n_kc chunks
                 (c->tune[LORA_TUNE_INLINE_SHRINK] == LORA_INLINE_SHRINK_ON ||
-                 (double)(pieces * chunks) * 4.0 / (double)std::min<long>(idle, 64) <= 0.6 * t_main)) {
+                 (double)(pieces * chunks) * (4.0 * (K / chunks) / 2048.0) / (double)std::min<long>(idle, 64) <= 0.6 * t_main)) {
                 front = (int)std::min<long>(idle, 64);
                 sa.n_kc = chunks;
                 sa.kc_len = ((K + chunks - 1) / chunks + kBK - 1) / kBK * kBK;
@@ -1027,7 +1029,8 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             a.sync = c->dev<uint32_t>(c->L.off_header) + 8;
             a.flags = c->d_flags();
             // 8 .. 11: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
-            const hipError_t le = (fv >= 8 && fv <= 11) ? launch_gemm_rows128_fused(a, sa, fv - 8, s, &name)
+            const hipError_t le = ((fv >= 8 && fv <= 11) || fv == 13 || fv == 14)
+                                      ? launch_gemm_rows128_fused(a, sa, fv >= 13 ? fv - 9 : fv - 8, s, &name)
                                                         : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);

@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     __syncthreads();
 
     f32x16 accw[1][1] = {{acc[0]}};
-    expand_windows<1, 1, 6>(accw, my_slot, my_rank, n_first, N, a.dv, sl.b_unit, sV);
+    expand_windows<1, 1, 12>(accw, my_slot, my_rank, n_first, N, a.dv, sl.b_unit, sV);
     acc[0] = accw[0][0];
 
     if (m_ok) {
