@@ -105,6 +105,98 @@ def calibrate_copy():
                       "big_copy_bytes_per_launch": 4 * n, "launches": 10}))
 
 
+def calibrate_stream():
+    """Read rate of a plain stream (lora_calibrate_stream): 16 bytes per lane and load, one launch per figure,
+    over a buffer far larger than the last-level cache, for a few workgroup counts."""
+    import torch
+    from paper_2602_24044_amd import binding as B
+    n = 2 << 30
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    sink = torch.zeros(65536, dtype=torch.int32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for wgs in (224, 256, 512, 1024, 2048, 4096):
+        per = 256 << 20
+        for i in range(3):
+            B.lora_calibrate_stream(buf.data_ptr() + (i % 8) * per, per, wgs, sink.data_ptr(), s)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(16):
+            B.lora_calibrate_stream(buf.data_ptr() + (i % 8) * per, per, wgs, sink.data_ptr(), s)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 16 * 1e3
+        out[str(wgs)] = {"us_per_launch": us, "gbs": per / us / 1e3}
+    best = max(v["gbs"] for v in out.values())
+    print(json.dumps({"probe": "stream", "bytes_per_launch": 256 << 20, "by_workgroups": out, "best_gbs": best,
+                      "frac_of_peak": best / HBM_PEAK_GBS}))
+
+
+def calibrate_mfma():
+    """Sustained bf16 MFMA rate and the shader clock under that load (lora_calibrate_mfma)."""
+    import torch
+    from paper_2602_24044_amd import binding as B
+    out = {}
+    for wgs in (256, 512):
+        sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+        ticks = torch.zeros(wgs * 2, dtype=torch.int64, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        iters = 8192
+        B.lora_calibrate_mfma(wgs, iters, sink.data_ptr(), ticks.data_ptr(), s)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            B.lora_calibrate_mfma(wgs, iters, sink.data_ptr(), ticks.data_ptr(), s)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 5 * 1e3
+        flops = wgs * 4 * iters * 16 * 32768.0
+        t = ticks.cpu().numpy().reshape(-1, 2).astype("float64")
+        mhz = float((t[:, 0] / t[:, 1]).mean() * 100.0)        # wall clock ticks are 10 ns
+        out[str(wgs)] = {"us_per_launch": us, "tflops": flops / us / 1e6, "shader_clock_mhz": mhz}
+    best = max(v["tflops"] for v in out.values())
+    print(json.dumps({"probe": "mfma", "by_workgroups": out, "best_tflops": best,
+                      "frac_of_peak": best / MFMA_BF16_PEAK_TFLOPS}))
+
+
+class ClockSampler:
+    """Samples `rocm-smi --showclocks` in a thread while the GPU is kept busy (the clocks of an idle GPU say nothing)."""
+
+    def __init__(self):
+        import threading
+        self.samples = []
+        self._stop = False
+        self._t = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop:
+            try:
+                txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+            except Exception:
+                return
+            m = {k: int(v) for k, v in re.findall(r"(sclk|mclk) clock level: \S+ \((\d+)Mhz\)", txt)}
+            if m:
+                self.samples.append(m)
+
+    def __enter__(self):
+        self._t.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop = True
+        self._t.join(timeout=15)
+
+    def summary(self):
+        if not self.samples:
+            return None
+        sclk = [x.get("sclk", 0) for x in self.samples]
+        mclk = [x.get("mclk", 0) for x in self.samples]
+        return {"source": "rocm-smi --showclocks while steps run", "samples": len(self.samples),
+                "sclk_mhz_max": max(sclk), "sclk_mhz_min": min(sclk), "mclk_mhz_max": max(mclk)}
+
+
 def cpu_baseline(w, budget_s: float = 15.0):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: the first n tokens of
     the step through all seven projections."""
@@ -137,9 +229,16 @@ def main():
                     help="distinct weight/slot copies rotated through (0 = 4 for configs 2 and 4, else 2)")
     ap.add_argument("--shrink", type=int, default=1, help="divide the model dimensions (debugging only)")
     ap.add_argument("--path", type=int, default=0)
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="lora_set_tuning on every context (kernel variants; repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clocks", action="store_true", help="skip the rocm-smi clock samples (about a second of extra steps)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copy kernels of known size and exit (reference for the HBM byte counters)")
+    ap.add_argument("--calibrate-stream", action="store_true",
+                    help="measure the read rate of a plain stream (the roof a weight stream can reach) and exit")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="measure the sustained bf16 MFMA rate and the clock under it and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU; the path shards by adapter with no exchange, "
@@ -148,6 +247,12 @@ def main():
 
     if args.calibrate_copy:
         calibrate_copy()
+        return
+    if args.calibrate_stream:
+        calibrate_stream()
+        return
+    if args.calibrate_mfma:
+        calibrate_mfma()
         return
 
     import torch
@@ -162,6 +267,15 @@ def main():
              4: "8B-shape many-adapter decode, 512 tokens uniform over 384 adapters ranks {8,16,32,64}",
              5: "70B-shape mixed step, 2048-token prefill chunk + 384 decode tokens, 128 slots",
              6: "Qwen2.5-7B-shape decode, 256 requests x 1 token, 32 adapters ranks {8,16,32}, Zipf(1.0) ids, q/k/v bias"}
+    metrics = {2: "LoRA-layer tokens/s at 8B-shape decode B=256; % MFMA peak & HBM GB/s",
+               3: "LoRA-layer tokens/s at 8B-shape prefill, 32 lognormal-length requests; % MFMA peak & HBM GB/s",
+               4: "LoRA-layer tokens/s at 8B-shape many-adapter decode B=512 over 384 adapters; % MFMA peak & HBM GB/s",
+               5: "LoRA-layer tokens/s at 70B-shape mixed step (2048 prefill + 384 decode) with 8 adapter loads per step; % MFMA peak & HBM GB/s",
+               6: "LoRA-layer tokens/s at Qwen2.5-7B-shape decode B=256; % MFMA peak & HBM GB/s"}
+    tune = {}
+    for kv in args.tune:
+        k, _, v = kv.partition("=")
+        tune[int(k)] = int(v)
 
     copies = args.copies if args.copies > 0 else (4 if args.config in (2, 4, 6) else 2)
     # Config 5: every step loads the batch's cold adapters again (H2D copies inside the timed region).
@@ -178,6 +292,8 @@ def main():
     sessions = []
     for _ in range(copies):
         s = Session(w, path=args.path)
+        for k, v in tune.items():
+            B.lora_set_tuning(s.ctx, k, v)
         s.load(w.resident)
         if w.missing:
             s.load(w.missing, in_use=in_use)
@@ -186,24 +302,60 @@ def main():
         sessions.append(s)
     torch.cuda.synchronize()
 
-    def run(n):
-        for i in range(n):
-            s = sessions[i % copies]
-            if reload_each_step:
-                s.load(placeholders, slots=s.cold_slots, stream=s.copy_stream)
-                s.load(w.missing, in_use=in_use, slots=s.cold_slots, stream=s.copy_stream)
+    def one_step(i, reload=reload_each_step, bucket=True):
+        s = sessions[i % copies]
+        if reload:
+            s.load(placeholders, slots=s.cold_slots, stream=s.copy_stream)
+            s.load(w.missing, in_use=in_use, slots=s.cold_slots, stream=s.copy_stream)
+        if bucket:
             s.step()
+        else:
+            s.forward_all()
 
+    def run(n, **kwargs):
+        for i in range(n):
+            one_step(i, **kwargs)
+
+    def timed(n, **kwargs):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(n, **kwargs)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    # ---- the headline figure: K steps between two synchronisations, inputs resident in HBM ----
     run(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(args.steps)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = w.T * args.steps / dt
+    per_step_s = timed(args.steps)
+    ms_per_step = per_step_s * 1e3
+    tokens_per_s = w.T / per_step_s
 
-    # second pass of the same steps with every kernel bracketed by HIP events on its stream
+    # ---- the same steps one by one between HIP events on the stream: median and min ----
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        one_step(i)
+        e1.record()
+    torch.cuda.synchronize()
+    ev_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
+    step_events = {"median_us": ev_us[len(ev_us) // 2], "min_us": ev_us[0], "max_us": ev_us[-1],
+                   "note": "one event pair per step on the stream; a pair adds about 2 us to what it brackets"}
+
+    # ---- without lora_bucket (in a model one segment map serves every layer of the step) ----
+    for s in sessions:
+        s.bucket()
+    run(min(args.warmup, 5), bucket=False)
+    no_bucket_s = timed(args.steps, bucket=False)
+
+    # ---- config 5: the same step with every adapter already resident (no copies over the host link) ----
+    compute_only = None
+    if reload_each_step:
+        run(2, reload=False)
+        co_s = timed(args.steps, reload=False)
+        compute_only = {"ms_per_step": co_s * 1e3, "tokens_per_s": w.T / co_s,
+                        "note": "all adapters resident; `value` includes the step's adapter copies over the host link"}
+
+    # ---- second pass of the same steps with every kernel bracketed by HIP events on its stream ----
     for s in sessions:
         B.lora_profile_reset(s.ctx)
         B.lora_profile_enable(s.ctx, True)
@@ -253,9 +405,54 @@ def main():
         roofline.update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": tf / MFMA_BF16_PEAK_TFLOPS, "hbm_gbs": achieved_gbs})
 
+    # ---- the LoRA part alone (HBM-bound workloads): the same step without adapters, and what the difference
+    #      moves: every used adapter's A and B once ----
+    lora_leg = None
+    if args.config in (2, 4, 6):
+        import numpy as np
+        w0 = wl.by_index(args.config, **kw)
+        w0.token_ids = np.full_like(w0.token_ids, -1)
+        w0.resident, w0.missing = [], []
+        base_sessions = []
+        for _ in range(copies):
+            s = Session(w0, path=args.path)
+            for k, v in tune.items():
+                B.lora_set_tuning(s.ctx, k, v)
+            base_sessions.append(s)
+        for i in range(args.warmup):
+            base_sessions[i % copies].step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            base_sessions[i % copies].step()
+        torch.cuda.synchronize()
+        base_s = (time.perf_counter() - t0) / args.steps
+        for s in base_sessions:
+            s.close()
+        ab_bytes = sum(2.0 * w.adapters[a].rank * sum(di + do for di, do in w.proj) for a in w.distinct_adapters())
+        d_us = (per_step_s - base_s) * 1e6
+        lora_leg = {"backbone_only_ms_per_step": base_s * 1e3, "added_us_per_step": d_us, "adapter_bytes": ab_bytes,
+                    "gbs": (ab_bytes / (d_us * 1e-6) / 1e9) if d_us > 0 else None,
+                    "frac": (ab_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS) if d_us > 0 else None,
+                    "note": "A and B of every adapter in the batch, once, over the time the adapters add to the step"}
+
+    # ---- clocks under this load ----
+    clocks = None
+    if not args.no_clocks:
+        with ClockSampler() as cs:
+            t_end = time.perf_counter() + 1.5
+            i = 0
+            while time.perf_counter() < t_end:
+                one_step(i, reload=False)
+                i += 1
+                if i % 64 == 0:
+                    torch.cuda.synchronize()
+            torch.cuda.synchronize()
+        clocks = cs.summary()
+
     step_bytes = wl.algorithmic_bytes(w)
     out = {
-        "metric": "LoRA-layer tokens/s at 8B-shape decode B=256; % MFMA peak & HBM GB/s",
+        "metric": metrics.get(args.config, metrics[2]),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -263,14 +460,22 @@ def main():
                    "h2d_adapter_bytes_per_step": (sum(2 * w.adapters[a].rank * sum(di + do for di, do in w.proj)
                                                       for a in w.missing) if reload_each_step else 0),
                    "projections": len(w.proj), "distinct_adapters": len(w.distinct_adapters()),
-                   "weight_copies_rotated": copies, "path": args.path},
+                   "weight_copies_rotated": copies, "path": args.path, "tuning": tune},
         "layer_step": {"algorithmic_bytes": step_bytes, "hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
                        "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "flops": wl.algorithmic_flops(w),
                        "tflops": wl.algorithmic_flops(w) / (ms_per_step * 1e-3) / 1e12},
+        "step_events": step_events,
+        "without_bucket": {"ms_per_step": no_bucket_s * 1e3, "tokens_per_s": w.T / no_bucket_s},
         "kernels": kernels,
         "roofline": roofline,
     }
+    if compute_only is not None:
+        out["compute_only"] = compute_only
+    if lora_leg is not None:
+        out["lora_leg"] = lora_leg
+    if clocks is not None:
+        out["clocks"] = clocks
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     for s in sessions:

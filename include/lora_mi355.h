@@ -310,6 +310,19 @@ lora_status lora_profile_enable(lora_ctx *ctx, int32_t on);
 int32_t lora_profile_collect(lora_ctx *ctx, const char **names, double *total_ms, int64_t *counts, int32_t cap);
 lora_status lora_profile_reset(lora_ctx *ctx);
 
+/* Ceiling probes for benchmarks (measurement aids, not on the serving path; the paper's latency model, Sec. 5.2,
+ * prices a step by what the weight stream and the matrix cores sustain).  Both enqueue one launch on `stream`.
+ * lora_calibrate_stream: `workgroups` workgroups of 512 threads read `bytes` of device memory at d_src (16-byte
+ * aligned) once, 16 bytes per lane and load, eight loads in flight per lane; d_sink: device, 4 * workgroups bytes
+ * (practically never written).  Bytes / launch time = the read rate a plain stream reaches on this machine.
+ * lora_calibrate_mfma: `workgroups` workgroups of four wavefronts issue iters * 16 back-to-back bf16 MFMAs
+ * (32x32x16, 32768 flop each) per wavefront; d_sink: device, 1024 * workgroups bytes; d_ticks: device,
+ * 16 * workgroups bytes: per workgroup the shader clock ticks and the 100 MHz wall clock ticks of its loop, so
+ * that the clock the chip sustained under this load can be read off.
+ * Errors: INVALID_ARG, HIP. */
+lora_status lora_calibrate_stream(const void *d_src, size_t bytes, int32_t workgroups, void *d_sink, void *stream);
+lora_status lora_calibrate_mfma(int32_t workgroups, int32_t iters, void *d_sink, void *d_ticks, void *stream);
+
 /* Adapter placement over GPUs (paper Sec. 7, the greedy caching algorithm with its feasibility test).  Host
  * code, no device access.  Input: for each of n_adapters its size (rank, > 0) and Poisson arrival rate
  * (>= 0), and the number of GPUs.  The two predictors are the caller's: given the sizes and rates of all

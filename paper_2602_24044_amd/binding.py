@@ -67,7 +67,7 @@ EXPORTS = [
     "lora_layer_forward_group",
     "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
-    "lora_last_hip_error", "lora_layer_forward_static", "lora_static_scratch_bytes", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
+    "lora_last_hip_error", "lora_calibrate_stream", "lora_calibrate_mfma", "lora_layer_forward_static", "lora_static_scratch_bytes", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
 ]
 LORA_TUNE_FUSED_VARIANT = 0
 LORA_TUNE_SPLIT_VARIANT = 1
@@ -153,6 +153,10 @@ _lib.lora_set_bias.restype = ctypes.c_int
 _lib.lora_set_bias.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, _P]
 _lib.lora_set_tuning.restype = ctypes.c_int
 _lib.lora_set_tuning.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
+_lib.lora_calibrate_stream.restype = ctypes.c_int
+_lib.lora_calibrate_stream.argtypes = [_P, ctypes.c_size_t, ctypes.c_int32, _P, _P]
+_lib.lora_calibrate_mfma.restype = ctypes.c_int
+_lib.lora_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, _P, _P, _P]
 _lib.lora_last_hip_error.restype = ctypes.c_char_p
 _lib.lora_last_hip_error.argtypes = []
 
@@ -376,6 +380,18 @@ def lora_profile_collect(ctx: int) -> Dict[str, Tuple[float, int]]:
     cnt = (ctypes.c_int64 * cap)()
     n = _lib.lora_profile_collect(_P(ctx), names, ms, cnt, cap)
     return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(min(n, cap))}
+
+
+def lora_calibrate_stream(d_src: int, nbytes: int, workgroups: int, d_sink: int, stream: int = 0) -> None:
+    st = _lib.lora_calibrate_stream(_P(d_src), int(nbytes), int(workgroups), _P(d_sink), _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_calibrate_stream")
+
+
+def lora_calibrate_mfma(workgroups: int, iters: int, d_sink: int, d_ticks: int, stream: int = 0) -> None:
+    st = _lib.lora_calibrate_mfma(int(workgroups), int(iters), _P(d_sink), _P(d_ticks), _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_calibrate_mfma")
 
 
 def lora_profile_reset(ctx: int) -> None:

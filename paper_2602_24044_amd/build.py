@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblora_mi355.so")
 SOURCES = ["lora_api.hip", "bucket.hip", "shrink.hip", "gemm.hip", "gemm_rows128.hip", "reduce_expand.hip",
-           "placement.cpp"]
+           "calibrate.hip", "placement.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 arithmetic stays off: plain v_fma_f32 / v_add_f32 only

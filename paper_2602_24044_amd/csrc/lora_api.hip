@@ -362,7 +362,16 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
                 const bool fused_instead = cand == 1 && c->cfg.path == LORA_PATH_AUTO;
                 const long per_round = fused_instead ? 256 : target;
                 const double rounds = (double)((tiles * cand + per_round - 1) / per_round);
-                const double cost = t_full * rounds / cand + (fused_instead ? 0.0 : t_part * cand);
+                double t_tiles = t_full * rounds / cand;
+                if (dyn_shrink && !fused_instead) {
+                    // the workgroups that only shrink run beside the tiles and the launch ends with the later of
+                    // the two: about 7 us until a workgroup's first item is under way, then 5 us per item (a
+                    // piece over 2048 of K); fewer splits leave more CUs to them
+                    const long shrinkers = std::max<long>(1, std::min<long>(128, 256 - tiles * cand));
+                    const double items = (double)pieces_bound * std::max(1, K / 2048);
+                    t_tiles = std::max(t_tiles, 7.0 + 5.0 * items / (double)shrinkers);
+                }
+                const double cost = t_tiles + (fused_instead ? 0.0 : t_part * cand);
                 if (cand == 1 || cost < best) {
                     best = cost;
                     S = cand;

@@ -159,9 +159,8 @@ class Session:
     def packed_groups(self) -> List[List[int]]:
         return packed_groups(self.w)
 
-    def step(self, packed: bool = True) -> None:
-        """One pass of the whole path: segment map + every projection (q|k|v and gate|up as packed calls)."""
-        self.bucket()
+    def forward_all(self, packed: bool = True) -> None:
+        """Every projection of the layer on the current segment map (q|k|v and gate|up as packed calls)."""
         if packed:
             for g in self.packed_groups():
                 if len(g) == 1:
@@ -171,6 +170,11 @@ class Session:
         else:
             for p in range(len(self.w.proj)):
                 self.forward(p)
+
+    def step(self, packed: bool = True) -> None:
+        """One pass of the whole path: segment map + every projection."""
+        self.bucket()
+        self.forward_all(packed)
 
     # ---- read-back helpers ----
     def _i32_at(self, ptr: int, n: int) -> np.ndarray:
