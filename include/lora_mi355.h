@@ -279,9 +279,12 @@ enum {
     LORA_FUSED_128x128x64_W4 = 9,
     LORA_FUSED_256x256x64_W8 = 10,
     LORA_FUSED_256x192x64_W8 = 11,
-    LORA_FUSED_256x256x32_W8 = 12,        /* what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
+    LORA_FUSED_256x256x32_W8 = 12,
     LORA_FUSED_256x128x64_W4 = 13,        /* four wavefronts with 128 x 64 wave tiles: fewer LDS reads per MFMA */
-    LORA_FUSED_256x256x64_W4 = 14
+    LORA_FUSED_256x256x64_W4 = 14,
+    LORA_FUSED_STAGED_256x256x64_W8 = 15, /* tiles staged through registers (ordinary loads, LDS writes), two LDS stages:
+                                             what LORA_FUSED_AUTO takes above 1024 tokens when the grid fills the chip */
+    LORA_FUSED_STAGED_256x256x64_W4 = 16
 };
 /* Values of LORA_TUNE_SPLIT_VARIANT. */
 enum {

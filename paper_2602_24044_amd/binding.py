@@ -78,7 +78,8 @@ LORA_INLINE_SHRINK_AUTO, LORA_INLINE_SHRINK_OFF, LORA_INLINE_SHRINK_ON = 0, 1, 2
 # values of LORA_TUNE_FUSED_VARIANT / LORA_TUNE_SPLIT_VARIANT (tile rows x columns x K tile, wavefronts)
 FUSED_VARIANTS = {"256x256x32_w4": 1, "256x256x32_w4_3stages": 2, "128x128x32_w4": 3, "256x128x32_w8": 4,
                   "256x128x32_w8_allcopy": 5, "256x128x64_w8": 8, "128x128x64_w4": 9, "256x256x64_w8": 10, "256x192x64_w8": 11,
-                  "256x256x32_w8": 12, "256x128x64_w4": 13, "256x256x64_w4": 14}
+                  "256x256x32_w8": 12, "256x128x64_w4": 13, "256x256x64_w4": 14,
+                  "staged_256x256x64_w8": 15, "staged_256x256x64_w4": 16}
 SPLIT_VARIANTS = {"256x128x32_w4": 1, "256x64x32_w4": 2, "128x128x32_w4": 3, "128x128x32_w4_8stages": 4,
                   "256x128x64_w8": 6, "128x128x64_w4": 7, "256x128x32_w8": 8, "256x128x64_w4": 9}
 

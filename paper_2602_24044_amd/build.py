@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblora_mi355.so")
-SOURCES = ["lora_api.hip", "bucket.hip", "shrink.hip", "gemm.hip", "gemm_rows128.hip", "reduce_expand.hip",
+SOURCES = ["lora_api.hip", "bucket.hip", "shrink.hip", "gemm.hip", "gemm_rows128.hip", "gemm_staged.hip", "reduce_expand.hip",
            "calibrate.hip", "placement.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

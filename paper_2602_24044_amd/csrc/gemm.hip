@@ -49,13 +49,16 @@ __device__ inline void static_for(F&& f)
 // lands at lds_addr (wave-uniform) + 16 * lane.  Issued from inline assembly so that the only ordering
 // against later LDS reads is the explicit vmcnt wait + barrier of the main loop (the compiler would
 // otherwise drain all copies before any LDS read whose stage it cannot tell apart).
-__device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
+__device__ inline void copy16_to_lds(const void* base, uint32_t byte_off, uint32_t lds_addr)
 {
+    // base: wave-uniform address (a scalar register pair), byte_off: this lane's offset from it.  The address of a
+    // tile then advances with scalar additions and the copy needs no vector ALU instruction at all: in the
+    // compute-bound kernels those share the issue port with the MFMAs.
     // m0 carries the LDS address.  It cannot be named as a clobber (a reserved register: the compiler rejects
     // it) and needs none: the compiler keeps no value in m0 between statements, it writes m0 itself directly in
     // front of each instruction of its own that reads it.  Putting the old value back after the copy was tried
     // and stalls every copy (the write to m0 waits until the copy instruction has read it): + 0.2 us per K tile.
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
 }
 
 template <int N>
@@ -89,7 +92,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, Shrin
     __shared__ __attribute__((aligned(1024))) uint16_t ring[NS * STAGE];
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;
 
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);    // a scalar: what depends on it alone stays scalar
     const int i = lane & 31, h = lane >> 5;
     const int cwave = wave;                                 // index among the copying waves
     const int wm = wave % WGM, wn = (wave / WGM) % WGN;
@@ -135,18 +139,18 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, Shrin
     // are clamped to the last valid row: they are computed, never stored.
     const int cp_row = lane >> 2;
     const int cp_chunk = (lane & 3) ^ ((cp_row >> 2) & 3);
-    uint32_t xoff[XQ], woff[WQ];                            // element offsets of this lane's 16 bytes in tile 0
+    uint32_t xoff[XQ], woff[WQ];                            // byte offsets of this lane's 16 bytes in tile 0
 #pragma unroll
     for (int q = 0; q < XQ; ++q) {
         int m = m0 + (cwave * XQ + q) * 16 + cp_row;
         if (m > T - 1) m = T - 1;
-        xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
+        xoff[q] = ((uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK)) * 2u;
     }
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         int n = n0 + (cwave * WQ + q) * 16 + cp_row;
         if (n > N - 1) n = N - 1;
-        woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK);
+        woff[q] = ((uint32_t)n * (uint32_t)K + (uint32_t)(cp_chunk * 8 + kt_begin * kTK)) * 2u;
     }
 
     f32x16 acc[MB][NB];
@@ -175,9 +179,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_kernel(GemmArgs a, Shrin
         if (!copier) return;
         const uint32_t so = (uint32_t)stage * (STAGE * 2);
         if (q < XQ)
-            copy16_to_lds(xg + (xoff[q] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + q * 1024));
+            copy16_to_lds(xg + k0, xoff[q], cp_x + so + q * 1024);
         else
-            copy16_to_lds(Wg + (woff[q - XQ] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + (q - XQ) * 1024));
+            copy16_to_lds(Wg + k0, woff[q - XQ], cp_w + so + (q - XQ) * 1024);
     };
     auto read_one = [&](auto f_c, int stage, int kk, int r) { // kk, r: compile-time constants at every call site
         constexpr int Fi = decltype(f_c)::value;

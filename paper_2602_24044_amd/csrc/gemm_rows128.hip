@@ -250,59 +250,81 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         asm volatile("buffer_inv sc1" ::: "memory");
     };
 
-    int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
-    for (int j = 0; j < nk; ++j) {
-        // own copies of tile j landed; the (at most NS - 2) younger tiles stay in flight
-        int young = nk - 1 - j;
+    // Software pipeline.  The fragments of a K step are read one step ahead, also across tiles: the barrier that
+    // makes tile j + 1 complete for every wave (and frees the stage of tile j, whose last fragments are in
+    // registers by then) sits in front of the MFMAs of tile j's last K step, and the first fragments of tile j + 1
+    // are requested right behind it, so that those MFMAs cover the LDS latency.  With the barrier at the top of a
+    // tile every wave of the workgroup would wait out that latency at the same time, with no MFMA in flight.
+    // Tile j + NS - 1 goes into the stage tile j - 1 has left, its copy instructions spread over the first
+    // three K steps of tile j (a wave that is held at a copy instruction by a full memory pipeline cannot issue
+    // its MFMAs meanwhile); all of them are out when the wave waits for tile j + 1.
+    // own copies of tile t landed (the at most NS - 2 younger tiles stay in flight), then the barrier
+    auto wait_for_tile = [&](int t) {
+        int young = nk - 1 - t;
         if (young > NS - 2) young = NS - 2;
         if (young >= 3) wait_copies_then_barrier<(NS >= 5 ? 3 : 0) * QPT>();
         else if (young == 2) wait_copies_then_barrier<(NS >= 4 ? 2 : 0) * QPT>();
         else if (young == 1) wait_copies_then_barrier<QPT>();
         else wait_copies_then_barrier<0>();
+    };
+    // what the fused path does behind the barrier of tile t (see above: poll, verdict, request)
+    auto behind_barrier = [&](int t) {
         if constexpr (PRE) {
             if (poll_on) {
-                if (j == nk - 4 && wave == 0) poll4_to_lds(a.sync, __builtin_amdgcn_readfirstlane(poll_addr));
-                if (j == nk - 2 && threadIdx.x == 0) {
-                    const bool done = s_poll[0] >= (uint32_t)front;     // landed: older than the copies the wait above let pass
+                if (t == nk - 4 && wave == 0) poll4_to_lds(a.sync, __builtin_amdgcn_readfirstlane(poll_addr));
+                if (t == nk - 2 && threadIdx.x == 0) {
+                    const bool done = s_poll[0] >= (uint32_t)front;     // landed: older than the copies the wait let pass
                     if (done) passed_the_wait();
                     s_early = done ? 1u : 0u;
                 }
-                if (j == nk - 1) {
+                if (t == nk - 1) {
                     early = s_early != 0u;
                     if (kWarmB) warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
                     if (early) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);
                 }
-            } else if (kWarmB && front == 0 && j == nk - 1) {
+            } else if (kWarmB && front == 0 && t == nk - 1) {
                 warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
             }
         }
-        // tile j is complete for every wave and every wave has finished tile j - 1: refill its stage
-        // The copy instructions are spread over the four K steps: a wave that is held at a copy instruction
-        // by a full memory pipeline cannot issue its MFMAs meanwhile.
+    };
+    bf16x8 Fw[2][NB], Fx[2][MB];
+    auto read_step = [&](int f, const uint8_t* st, int kk) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            Fw[f][nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + w_base + nb * 32 * kRowB + rd[kk]));
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            Fx[f][mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + x_base + mb * 32 * kRowB + rd[kk]));
+    };
+    if (nk > 0) {
+        wait_for_tile(0);
+        behind_barrier(0);
+        read_step(0, ring, 0);
+    }
+    int cur = 0, fre = NS - 1;                               // stages of tile j and of tile j - 1
+    for (int j = 0; j < nk; ++j) {
         const bool refill = j + NS - 1 < nk;
-
         const uint8_t* st = ring + cur * STAGE_B;
-        bf16x8 Fw[2][NB], Fx[2][MB];
-        auto read_step = [&](int f, int kk) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                Fw[f][nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + w_base + nb * 32 * kRowB + rd[kk]));
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                Fx[f][mb] = as_bf16x8(*reinterpret_cast<const u32x4*>(st + x_base + mb * 32 * kRowB + rd[kk]));
-        };
-        read_step(0, 0);
+        const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) read_step((kk + 1) & 1, kk + 1);
-            if (refill) copy_part(j + NS - 1, fre, kk * QPT / 4, (kk + 1) * QPT / 4);
+            if (kk < 3) {
+                read_step((kk + 1) & 1, st, kk + 1);
+                if (refill) copy_part(j + NS - 1, fre, kk * QPT / 3, (kk + 1) * QPT / 3);
+            } else if (j + 1 < nk) {
+                // this wave's last fragments of tile j are in registers before it lets the others refill the stage
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                wait_for_tile(j + 1);
+                behind_barrier(j + 1);
+                read_step(0, ring + nxt * STAGE_B, 0);
+            }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32(Fw[kk & 1][nb], Fx[kk & 1][mb], acc[mb][nb]);
         }
         fre = cur;
-        cur = (cur + 1 == NS) ? 0 : cur + 1;
+        cur = nxt;
     }
 
     // ---------------- epilogue ----------------

@@ -1037,10 +1037,12 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             a.shrink_front = front;
             a.sync = c->dev<uint32_t>(c->L.off_header) + 8;
             a.flags = c->d_flags();
-            // 8 .. 11: 64-wide K tiles; 12: the 32-wide 256 x 256 eight-wave kernel by name (what 0 stands for here)
+            // 8 .. 11, 13, 14: 64-wide K tiles through the copy instruction; 12: the 32-wide 256 x 256 eight-wave kernel
             const hipError_t le = ((fv >= 8 && fv <= 11) || fv == 13 || fv == 14)
                                       ? launch_gemm_rows128_fused(a, sa, fv >= 13 ? fv - 9 : fv - 8, s, &name)
-                                                        : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
+                                      // 0 (the big tile of the automatic choice), 15, 16: tiles staged through registers
+                                      : (fv == 0 || fv == 15 || fv == 16) ? launch_gemm_staged_fused(a, fv == 16 ? 1 : 0, s, &name)
+                                                                          : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
         }
