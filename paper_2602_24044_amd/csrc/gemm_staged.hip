@@ -45,7 +45,9 @@ __device__ inline void lds_done_then_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN>
+// PG: tiles in flight in registers (1: compute-bound shapes, the tile's data comes from L2 within one tile time;
+// 2: small batches, where the weight stream comes from HBM and bytes in flight set the rate).
+template <int BM, int BN, int WGM, int WGN, int PG>
 __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a)
 {
     constexpr int NWV = WGM * WGN;
@@ -99,16 +101,17 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     }
     const uint8_t* const xb = reinterpret_cast<const uint8_t*>(sl.x);
     const uint8_t* const wb = reinterpret_cast<const uint8_t*>(sl.W);
-    u32x4 stg[XQ + WQ];                                     // the tile in flight: W parts first, then x parts
+    static_assert(PG == 1 || PG == 2, "register sets");
+    u32x4 stg[PG][XQ + WQ];                                 // the tiles in flight: W parts first, then x parts
     constexpr int NST = XQ + WQ;
-    auto load_one = [&](int t, int q) {                      // q: compile-time constant at every call site
+    auto load_one = [&](int set, int t, int q) {             // set, q: compile-time constants at every call site
         const size_t k0 = (size_t)t * (kSK * 2);
-        stg[q] = q < WQ ? *reinterpret_cast<const u32x4*>(wb + k0 + woff[q])
-                        : *reinterpret_cast<const u32x4*>(xb + k0 + xoff[q - WQ]);
+        stg[set][q] = q < WQ ? *reinterpret_cast<const u32x4*>(wb + k0 + woff[q])
+                             : *reinterpret_cast<const u32x4*>(xb + k0 + xoff[q - WQ]);
     };
-    auto store_one = [&](int stage, int q) {
+    auto store_one = [&](int set, int stage, int q) {
         uint8_t* st = ring + stage * STAGE_B;
-        *reinterpret_cast<u32x4*>(st + (q < WQ ? wst[q] : xst[q - WQ])) = stg[q];
+        *reinterpret_cast<u32x4*>(st + (q < WQ ? wst[q] : xst[q - WQ])) = stg[set][q];
     };
 
     f32x16 acc[MB][NB];
@@ -134,20 +137,25 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
         acc[mb][nb] = mfma32(Fw[f][nb], Fx[f][mb], acc[mb][nb]);
     };
 
-    // prologue: tile 0 into stage 0, tile 1 into the registers
-    staged_for<NST>([&](auto q) { load_one(0, q.value); });
-    staged_for<NST>([&](auto q) { store_one(0, q.value); });
-    if (nk > 1) staged_for<NST>([&](auto q) { load_one(1, q.value); });
+    // prologue: tile 0 into stage 0, tiles 1 .. PG into the registers (tile t travels in register set t % PG)
+    staged_for<NST>([&](auto q) { load_one(0, 0, q.value); });
+    staged_for<NST>([&](auto q) { store_one(0, 0, q.value); });
+    staged_for<PG>([&](auto d) {
+        constexpr int t = decltype(d)::value + 1;
+        if (t < nk) staged_for<NST>([&](auto q) { load_one(t % PG, t, q.value); });
+    });
     lds_done_then_barrier();
     staged_for<NR>([&](auto r) { read_one(0, ring, 0, r.value); });
 
-    // One tile.  STORE: tile j + 1 waits in the registers and goes into the other stage during K step 0; LOAD:
-    // tile j + 2 is requested during K step 1; NEXT: there is a tile j + 1 to hand over to.  The instruction
-    // order is written out and pinned: behind every MFMA one LDS read of the next K step's
-    // fragments and its share of the K step's LDS writes (step 0) or global loads (step 1), so that neither a
-    // row of writes that wait for their loads nor a row of reads stands in front of the MFMAs (scheduling
-    // barriers: plain compiler fences do not hold MFMAs in place, they are not memory operations).
-    auto tile = [&](auto store_c, auto load_c, auto next_c, int j) {
+    // One tile.  STORE: tile j + 1 waits in its registers and goes into the other stage during K step 0; LOAD:
+    // tile j + 1 + PG is requested into the same registers during K step 1; NEXT: there is a tile j + 1 to hand
+    // over to.  SET: the register set of tile j + 1.  The instruction order is written out and pinned: behind
+    // every MFMA one LDS read of the next K step's fragments and its share of the K step's LDS writes (step 0) or
+    // global loads (step 1), so that neither a row of writes that wait for their loads nor a row of reads stands
+    // in front of the MFMAs (scheduling barriers: plain compiler fences do not hold MFMAs in place, they are not
+    // memory operations).
+    auto tile = [&](auto set_c, auto store_c, auto load_c, auto next_c, int j) {
+        constexpr int SET = decltype(set_c)::value;
         constexpr bool STORE = decltype(store_c)::value, LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value;
         const uint8_t* st = ring + (j & 1) * STAGE_B;
         const int other = (j & 1) ^ 1;
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (t < NR) read_one(1, st, 1, t);
             if constexpr (STORE)
-                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { store_one(other, t * NST / NM + q.value); });
+                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { store_one(SET, other, t * NST / NM + q.value); });
             __builtin_amdgcn_sched_barrier(0);
         });
         staged_for<NM>([&](auto tc) {                           // K step 1
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (t < NR) read_one(0, st, 2, t);
             if constexpr (LOAD)
-                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { load_one(j + 2, t * NST / NM + q.value); });
+                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { load_one(SET, j + 1 + PG, t * NST / NM + q.value); });
             __builtin_amdgcn_sched_barrier(0);
         });
         staged_for<NM>([&](auto tc) {                           // K step 2
@@ -187,14 +195,34 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     };
     using Yes = std::true_type;
     using No = std::false_type;
-    {
+    // tile j + 1 sits in register set (j + 1) % PG: with two sets the steady state walks two tiles per round so
+    // that the set is a compile-time constant
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    if constexpr (PG == 1) {
         int j = 0;
-        for (; j + 2 < nk; ++j) tile(Yes{}, Yes{}, Yes{}, j);
+        for (; j + 2 < nk; ++j) tile(S0{}, Yes{}, Yes{}, Yes{}, j);
         if (j + 1 < nk) {
-            tile(Yes{}, No{}, Yes{}, j);
+            tile(S0{}, Yes{}, No{}, Yes{}, j);
             ++j;
         }
-        if (j < nk) tile(No{}, No{}, No{}, j);
+        if (j < nk) tile(S0{}, No{}, No{}, No{}, j);
+    } else {
+        int j = 0;                                               // even here and after every round
+        for (; j + 4 < nk; j += 2) {                             // tiles j, j + 1: both store and load (j + 1 + 3 < nk)
+            tile(S1{}, Yes{}, Yes{}, Yes{}, j);
+            tile(S0{}, Yes{}, Yes{}, Yes{}, j + 1);
+        }
+        // at most four tiles are left, none of them loads except where a tile j + 3 still exists
+        for (; j < nk; j += 2) {
+            if (j + 3 < nk) tile(S1{}, Yes{}, Yes{}, Yes{}, j);
+            else if (j + 1 < nk) tile(S1{}, Yes{}, No{}, Yes{}, j);
+            else tile(S1{}, No{}, No{}, No{}, j);
+            if (j + 1 < nk) {
+                if (j + 2 < nk) tile(S0{}, Yes{}, No{}, Yes{}, j + 1);
+                else tile(S0{}, No{}, No{}, No{}, j + 1);
+            }
+        }
     }
 
     // ---------------- epilogue ----------------
@@ -202,7 +230,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     finish_tile<MB, NB, true>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, 0, wave, reinterpret_cast<uint16_t*>(ring));
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int PG>
 hipError_t launch_staged(GemmArgs a, hipStream_t stream)
 {
     a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
@@ -212,7 +240,7 @@ hipError_t launch_staged(GemmArgs a, hipStream_t stream)
         a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
     }
     const int grid = a.tiles_m * a.tiles_n;
-    hipLaunchKernelGGL((gemm_staged_kernel<BM, BN, WGM, WGN>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream, a);
+    hipLaunchKernelGGL((gemm_staged_kernel<BM, BN, WGM, WGN, PG>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -223,10 +251,16 @@ hipError_t launch_gemm_staged_fused(const GemmArgs& a, int variant, hipStream_t 
     switch (variant) {
         case 1:
             *name = "gemm_fused_staged_256x256x64_w4";
-            return launch_staged<256, 256, 2, 2>(a, stream);
+            return launch_staged<256, 256, 2, 2, 1>(a, stream);
+        case 2:
+            *name = "gemm_fused_staged_256x128x64_w8";
+            return launch_staged<256, 128, 4, 2, 2>(a, stream);
+        case 3:
+            *name = "gemm_fused_staged_256x128x64_w8_pg1";
+            return launch_staged<256, 128, 4, 2, 1>(a, stream);
         default:
             *name = "gemm_fused_staged_256x256x64_w8";
-            return launch_staged<256, 256, 2, 4>(a, stream);
+            return launch_staged<256, 256, 2, 4, 1>(a, stream);
     }
 }
 

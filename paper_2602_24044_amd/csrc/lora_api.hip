@@ -1041,7 +1041,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             const hipError_t le = ((fv >= 8 && fv <= 11) || fv == 13 || fv == 14)
                                       ? launch_gemm_rows128_fused(a, sa, fv >= 13 ? fv - 9 : fv - 8, s, &name)
                                       // 0 (the big tile of the automatic choice), 15, 16: tiles staged through registers
-                                      : (fv == 0 || fv == 15 || fv == 16) ? launch_gemm_staged_fused(a, fv == 16 ? 1 : 0, s, &name)
+                                      : (fv == 0 || (fv >= 15 && fv <= 18)) ? launch_gemm_staged_fused(a, fv == 0 ? 0 : fv - 15, s, &name)
                                                                           : launch_gemm_fused(a, fv == 12 ? 0 : fv, s, &name);
             if (HIP_FAIL(le)) return LORA_ERR_HIP;
             ls.rename(name);
