@@ -138,16 +138,23 @@ typedef struct {
     uint64_t epoch; /* identifies the lora_bucket call that produced this map */
 } lora_segments;
 
-/* Device bytes the context needs for `cfg` (slot region + scratch); 0 if cfg is invalid.
+/* Device bytes the context needs for `cfg` (slot region + scratch); 0 if cfg is invalid.  Paper Sec. 2.2: the
+ * serving engine reserves a fixed GPU region for at most A_max simultaneously loaded adapters, each slot sized for
+ * the largest adapter (S_max; Sec. 8.1 sets S_max to the largest adapter of the scenario).
  * Slot region = n_slots * n_layers * max_rank * sum_p (d_in_p + d_out_p) * 2 bytes: every slot has the
- * uniform S_max footprint, but kernels only ever read an adapter's own rank rows. */
+ * uniform S_max footprint, but kernels only ever read an adapter's own rank rows.  The scratch behind it is
+ * sized for the compute units of the current device: query on the device the context will be created on. */
 size_t lora_slab_bytes(const lora_config *cfg);
 
-/* Creates a context on the current device.  cfg->slab must hold lora_slab_bytes(cfg) bytes
- * (LORA_ERR_OOM otherwise).  All slots start empty.  Errors: INVALID_ARG, SHAPE, OOM, HIP. */
+/* Creates a context on the current device: the adapter cache of one serving instance (paper Sec. 2.2: A_max slots
+ * of S_max, adapters swapped in from CPU memory; Sec. 8.1: one instance per GPU) together with the scratch of its
+ * projection calls.  cfg->slab must hold lora_slab_bytes(cfg) bytes (LORA_ERR_OOM otherwise).  All slots start
+ * empty.  One context serves one stream of steps: calls on it are not thread-safe, and its forward calls and
+ * segment maps share scratch (see lora_layer_forward).  Errors: INVALID_ARG, SHAPE, OOM, HIP. */
 lora_status lora_create(const lora_config *cfg, lora_ctx **out);
 
-/* Waits for the context's own events, releases host resources.  The slab stays the caller's. */
+/* Ends the adapter cache (paper Sec. 2.2; unloading costs nothing, Sec. 5.2): waits for the device, releases the
+ * context's events and host tables.  The slab stays the caller's.  Errors: INVALID_ARG (NULL). */
 lora_status lora_destroy(lora_ctx *ctx);
 
 /* Makes n adapters resident (paper Sec. 2.2 / Sec. 5.1.3: adapters are loaded from CPU memory
@@ -164,27 +171,39 @@ lora_status lora_destroy(lora_ctx *ctx);
  * lora_bucket / lora_layer_forward calls on other streams wait through those events, each
  * forward only for the copies of its own projection (layer), and the copies themselves wait
  * for forward work already enqueued (a slot is never overwritten while an earlier step may
- * still read it).
+ * still read it: forward calls of a context are chained across streams, see lora_layer_forward, so the wait for
+ * the latest one covers all of them).
  * Errors: INVALID_ARG, ID_RANGE, SLOT_RANGE, RANK_EXCEEDS_SMAX, SHAPE (rank not a multiple of
  * 8), SLOTS_EXHAUSTED, HIP. */
 lora_status lora_slots_load(lora_ctx *ctx, int32_t n, lora_adapter_desc *descs,
                             const int32_t *in_use, int32_t n_in_use, void *copy_stream);
 
 /* Builds the token->adapter segment map for one step (shared by all projections and layers
- * of the step).  d_token_adapter: device, int32[T], adapter id per token or -1.  Integer work
+ * of the step).  Paper Sec. 2.2: requests of different adapters run inside the same batch (each adapter's
+ * matrices are then streamed once per step, for the tokens that use it); Sec. 2.1: a step mixes the tokens of
+ * prefill chunks with one-token decode requests; Sec. 2.2: a request can run only while its adapter is in GPU
+ * memory (hence the residency flag).  d_token_adapter: device, int32[T], adapter id per token or -1.  Integer work
  * only; the result is unique: SORTED = stable ascending sort of token indices by slot (slot -1
  * first) + run-length encoding; RUNS = identity order + run-length encoding.  A token whose
  * adapter id is out of range or not resident sets LORA_FLAG_NOT_RESIDENT in the device flag
- * word and is treated as -1.  T = 0 is valid (n_seg = 0).
+ * word and is treated as -1.  T = 0 is valid (n_seg = 0).  The map replaces the previous one: when `stream` is
+ * not the stream of the context's previous forward call, the library first orders it behind that call.
  * Errors: INVALID_ARG (T < 0, T > max_tokens, bad mode, null pointers), HIP. */
 lora_status lora_bucket(lora_ctx *ctx, const int32_t *d_token_adapter, int32_t T, int32_t mode,
                         lora_segments *out, void *stream);
 
 /* One projection of the step: d_out[t,:] = bf16(x[t,:] W^T + s (x[t,:] A^T) B^T) for every token,
- * in original token order.  d_x: device bf16 [T, d_in_p]; d_W: device bf16 [d_out_p, d_in_p];
+ * in original token order (paper Sec. 2.2: a LoRA adapter is two low-rank matrices per targeted layer whose
+ * activations are added to the backbone layer's output; Sec. 1: adapters stay unmerged over one shared backbone).
+ * d_x: device bf16 [T, d_in_p]; d_W: device bf16 [d_out_p, d_in_p];
  * d_out: device bf16 [T, d_out_p]; all row-major, 16-byte aligned, not aliased.  seg must be
- * the map of the latest lora_bucket on this context, and the call must be ordered after that
- * lora_bucket (same stream, or an event).  T = 0 is a no-op.
+ * the map of the latest lora_bucket on this context.  T = 0 is a no-op.
+ * Stream ordering: all forward calls (and segment maps) of one context share its scratch (split-K partial tiles,
+ * shrink results, the counters of a launch), so they must not overlap in time.  The library sees to that itself:
+ * a call whose stream differs from the stream of the context's previous lora_bucket / forward call is ordered
+ * behind it with an event before anything is enqueued.  Calls that should run concurrently need contexts of
+ * their own.  When the call uses the shrink inside its launch and lora_poll_device_flags later reports
+ * LORA_FLAG_INTERNAL, the outputs written since the previous poll are undefined.
  * Errors: INVALID_ARG (proj out of range, stale seg, null or misaligned pointers), HIP. */
 lora_status lora_layer_forward(lora_ctx *ctx, int32_t proj, const void *d_x, const void *d_W,
                                const lora_segments *seg, void *d_out, void *stream);
@@ -238,7 +257,10 @@ lora_status lora_model_forward_group(lora_ctx *ctx, int32_t layer, int32_t n, co
  * Errors: INVALID_ARG (layer or proj out of range, misaligned pointer). */
 lora_status lora_set_bias(lora_ctx *ctx, int32_t layer, int32_t proj, const void *d_bias);
 
-/* Blocking read-and-clear of the device flag word (synchronises `stream`).  Returns
+/* Blocking read-and-clear of the device flag word (synchronises `stream`).  Paper Sec. 2.2: a request is
+ * processed only while its adapter resides in GPU memory; a token that violated this was served backbone-only and
+ * is reported here.  After LORA_FLAG_INTERNAL the context also sets the counters of the launch back and from then
+ * on runs the shrink as a launch of its own (the assumption behind the shrink inside a launch failed once).  Returns
  * LORA_ERR_NOT_RESIDENT if LORA_FLAG_NOT_RESIDENT was set (LORA_ERR_HIP if LORA_FLAG_INTERNAL was), else LORA_OK; *flags (may be NULL)
  * receives the raw word. */
 lora_status lora_poll_device_flags(lora_ctx *ctx, uint32_t *flags, void *stream);
@@ -253,7 +275,11 @@ enum {
     LORA_TUNE_FUSED_VARIANT = 0, /* tile shape / wave layout of the fused GEMM */
     LORA_TUNE_SPLIT_VARIANT = 1, /* tile shape / wave layout of the split-K GEMM */
     LORA_TUNE_COPY_ENGINE = 2,   /* what carries an adapter's matrices into its slot (lora_slots_load) */
-    LORA_TUNE_INLINE_SHRINK = 3  /* fused path up to 1024 tokens: shrink by the first workgroups of the GEMM launch */
+    LORA_TUNE_INLINE_SHRINK = 3, /* fused path up to 1024 tokens: shrink by the first workgroups of the GEMM launch */
+    LORA_TUNE_SHRINK_WAIT_TEST = 4 /* test aid, value n > 0: in such a launch the tile workgroups expect one report more
+                                      than will come and give up after n polls, so that the expired-wait handling
+                                      (LORA_FLAG_INTERNAL, counter reset, fallback) can be exercised from the host
+                                      with every kernel ending normally; the outputs of that launch are still right */
 };
 /* Values of LORA_TUNE_INLINE_SHRINK. */
 enum {

@@ -74,6 +74,7 @@ LORA_TUNE_SPLIT_VARIANT = 1
 LORA_TUNE_COPY_ENGINE = 2
 LORA_COPY_AUTO, LORA_COPY_KERNEL, LORA_COPY_ENGINE = 0, 1, 2
 LORA_TUNE_INLINE_SHRINK = 3
+LORA_TUNE_SHRINK_WAIT_TEST = 4
 LORA_INLINE_SHRINK_AUTO, LORA_INLINE_SHRINK_OFF, LORA_INLINE_SHRINK_ON = 0, 1, 2
 # values of LORA_TUNE_FUSED_VARIANT / LORA_TUNE_SPLIT_VARIANT (tile rows x columns x K tile, wavefronts)
 FUSED_VARIANTS = {"256x256x32_w4": 1, "256x256x32_w4_3stages": 2, "128x128x32_w4": 3, "256x128x32_w8": 4,

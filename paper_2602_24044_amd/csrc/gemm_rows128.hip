@@ -120,8 +120,10 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         float* sRed = reinterpret_cast<float*>(ring);
         const ShrinkPrefetch pa = shrink_prefetch(sa, blockIdx.x);
         shrink_block_items<NWV>(sa, blockIdx.x, front, pa.n_items, sRed, pa);
-        // every wave's results have reached L2, then one thread makes them visible to the device and reports
-        // (a device-scope fence writes back / invalidates caches: one per workgroup, not one per wave)
+        // Every wave orders its stores at workgroup scope and meets the others; one thread then issues the single
+        // device-scope release (a write-back of this L2's dirty lines: one per workgroup, not one per wave) and
+        // reports.  That the other waves' stores are covered by that one release rests on the hardware (one CU,
+        // one L2 behind it, stores of a CU reach the L2 in order), not on the language's memory model.
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
             if (poll_on) {
                 if (t == nk - 4 && wave == 0) poll4_to_lds(a.sync, __builtin_amdgcn_readfirstlane(poll_addr));
                 if (t == nk - 2 && threadIdx.x == 0) {
-                    const bool done = s_poll[0] >= (uint32_t)front;     // landed: older than the copies the wait let pass
+                    const bool done = s_poll[0] >= (uint32_t)a.front_expect;     // landed: older than the copies the wait let pass
                     if (done) passed_the_wait();
                     s_early = done ? 1u : 0u;
                 }
@@ -337,8 +339,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         // It is bounded all the same; if it expires the call's result is invalid and flagged.
         if (threadIdx.x == 0) {
             int spins = 0;
-            while (__hip_atomic_load(a.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)front) {
-                if (++spins > kShrinkWaitSpins) {
+            while (__hip_atomic_load(a.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)a.front_expect) {
+                if (++spins > a.wait_spins) {
                     atomicOr(a.flags, kFlagInternal);
                     break;
                 }

@@ -89,21 +89,33 @@ const void* device_view_of_pinned(const void* p)
     return at.devicePointer;
 }
 
-int auto_split_cap(int N)
+// Compute units of the current device (256 on an MI355X); 256 when there is no device to ask.
+int device_cus()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n < 8) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return n;
+}
+
+int auto_split_cap(int N, int n_cus)
 {
     const int tiles_n = (N + 127) / 128;
-    int s = (256 + tiles_n - 1) / tiles_n;
+    int s = (n_cus + tiles_n - 1) / tiles_n;
     return std::max(1, std::min(16, s));
 }
 
-// Tile shape of the fused GEMM: rounds of workgroups over the 256 CUs times the cost of one tile, with the
+// Tile shape of the fused GEMM: rounds of workgroups over the CUs times the cost of one tile, with the
 // per-flop efficiencies measured for the three shapes (256x256: 1, 256x128: 0.78, 128x128: 0.65).  Large
 // problems take the big tile; a projection with few big tiles (k/v at a few thousand tokens) fills the chip
 // better with small ones.
 template <typename TilesOf>
-int pick_fused_variant(int /*T*/, int /*N*/, TilesOf&& tiles_of)
+int pick_fused_variant(int n_cus, TilesOf&& tiles_of)
 {
-    auto rounds = [&](int bm, int bn) { return (double)((tiles_of(bm, bn) + 255) / 256); };
+    auto rounds = [&](int bm, int bn) { return (double)((tiles_of(bm, bn) + n_cus - 1) / n_cus); };
     const double big = rounds(256, 256) * 1.0, mid = rounds(256, 128) * (0.5 / 0.78), small = rounds(128, 128) * (0.25 / 0.65);
     if (big <= mid * 1.1 && big <= small * 1.1) return 0;      // near ties go to the big tile (measured)
     return mid <= small ? 4 : 3;
@@ -129,7 +141,7 @@ bool valid_config(const lora_config* c)
     return true;
 }
 
-Layout make_layout(const lora_config* c)
+Layout make_layout(const lora_config* c, int n_cus)
 {
     Layout L;
     size_t e = 0;
@@ -173,7 +185,7 @@ Layout make_layout(const lora_config* c)
     L.off_vpart = take(4 * L.vpart_elems);
     size_t part_cols = 0;
     for (int p = 0; p < c->n_proj; ++p) {
-        const int s = c->split_k > 0 ? c->split_k : auto_split_cap(c->proj[p].d_out);
+        const int s = c->split_k > 0 ? c->split_k : auto_split_cap(c->proj[p].d_out, n_cus);
         part_cols = std::max(part_cols, align_up((size_t)c->proj[p].d_out, 32) * (size_t)s);
     }
     L.part_elems = align_up(Ts, 256) * part_cols;
@@ -196,6 +208,7 @@ struct lora_ctx {
     bool host_only = false;
     char* base = nullptr;
     int device = -1;                        // the device the context was created on
+    int n_cus = 256;                        // its compute units: what a launch can keep busy at once
     char* static_scratch = nullptr;         // that device's copy of `scratch` (lora_layer_forward_static)
 
     // host slot table
@@ -219,6 +232,7 @@ struct lora_ctx {
     bool have_fwd = false;
 
     int32_t tune[8] = {0};
+    bool inline_shrink_off = false;         // a bounded wait inside a launch has expired once: shrink as a launch of its own from then on
     std::vector<const uint16_t*> bias;      // [n_layers * n_proj] device, caller-owned (lora_set_bias)
 
     // current segment map
@@ -326,7 +340,7 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
     int split_variant = c->tune[LORA_TUNE_SPLIT_VARIANT];
     if (T <= kSplitMaxTokens) {
         if (c->cfg.path == LORA_PATH_SPLITK) split = true;
-        else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < 128;
+        else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < c->n_cus / 2;
     }
     if (split) {
         // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
@@ -345,7 +359,7 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
         const long pieces_bound = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
         dyn_shrink = c->n_resident > 0 && (split_variant == 6 || split_variant == 7 || split_variant == 9) &&
                      pieces_bound * std::max(1, K / 2048) <= 512;
-        const long target = dyn_shrink ? 192 : 256;
+        const long target = dyn_shrink ? c->n_cus * 3 / 4 : c->n_cus;
         // K splits, at most 8, by a cost model in microseconds: a workgroup walking all of K moves (bm + bn) K
         // bf16 through its CU at about 48 GB/s, a launch takes ceil(tiles S / target) rounds of 1 / S of that
         // (one workgroup per CU: a grid just above the CU count costs a whole extra round), and every split
@@ -360,14 +374,14 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
                 // a single K range takes the fused path instead (below): every CU can hold a tile and there are
                 // no partial tiles at all
                 const bool fused_instead = cand == 1 && c->cfg.path == LORA_PATH_AUTO;
-                const long per_round = fused_instead ? 256 : target;
+                const long per_round = fused_instead ? c->n_cus : target;
                 const double rounds = (double)((tiles * cand + per_round - 1) / per_round);
                 double t_tiles = t_full * rounds / cand;
                 if (dyn_shrink && !fused_instead) {
                     // the workgroups that only shrink run beside the tiles and the launch ends with the later of
                     // the two: about 7 us until a workgroup's first item is under way, then 5 us per item (a
                     // piece over 2048 of K); fewer splits leave more CUs to them
-                    const long shrinkers = std::max<long>(1, std::min<long>(128, 256 - tiles * cand));
+                    const long shrinkers = std::max<long>(1, std::min<long>(c->n_cus / 2, c->n_cus - tiles * cand));
                     const double items = (double)pieces_bound * std::max(1, K / 2048);
                     t_tiles = std::max(t_tiles, 7.0 + 5.0 * items / (double)shrinkers);
                 }
@@ -448,7 +462,7 @@ size_t lora_slab_bytes(const lora_config* cfg)
 {
     if (!valid_config(cfg)) return 0;
     if (cfg->flags & LORA_CREATE_HOST_ONLY) return 0;
-    return make_layout(cfg).total;
+    return make_layout(cfg, device_cus()).total;
 }
 
 lora_status lora_create(const lora_config* cfg, lora_ctx** out)
@@ -467,8 +481,9 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
     c->cfg = *cfg;
     c->proj.assign(cfg->proj, cfg->proj + cfg->n_proj);
     c->cfg.proj = c->proj.data();
-    c->L = make_layout(&c->cfg);
     c->host_only = (cfg->flags & LORA_CREATE_HOST_ONLY) != 0;
+    c->n_cus = c->host_only ? 256 : device_cus();
+    c->L = make_layout(&c->cfg, c->n_cus);
     c->n_layers = std::max(1, cfg->n_layers);
     const size_t n_flat = (size_t)c->n_layers * cfg->n_proj;
     const size_t n_units = c->n_layers > 1 ? (size_t)c->n_layers : (size_t)cfg->n_proj;
@@ -760,6 +775,11 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     if (c->meta_pending && s != c->copy_stream) {
         if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_meta, 0))) return LORA_ERR_HIP;
     }
+    // the segment arrays are read by the forwards of the previous step: a map built on another stream waits for them
+    if (c->have_fwd && c->last_fwd_stream != s) {
+        if (HIP_FAIL(hipEventRecord(c->ev_fwd, c->last_fwd_stream))) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_fwd, 0))) return LORA_ERR_HIP;
+    }
     BucketArgs a;
     a.ids = d_token_adapter;
     a.T = T;
@@ -842,6 +862,12 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             return LORA_ERR_INVALID_ARG;
     }
     hipStream_t s = static_cast<hipStream_t>(stream_v);
+    // forwards (and segment maps) of one context share its scratch and its segment arrays: a call on another
+    // stream than the previous one is ordered behind it
+    if (c->have_fwd && c->last_fwd_stream != s) {
+        if (HIP_FAIL(hipEventRecord(c->ev_fwd, c->last_fwd_stream))) return LORA_ERR_HIP;
+        if (HIP_FAIL(hipStreamWaitEvent(s, c->ev_fwd, 0))) return LORA_ERR_HIP;
+    }
     for (int k = 0; k < n; ++k) {
         const int u = c->unit_of(layer, projs[k]);
         if (c->unit_pending[u] && s != c->copy_stream && (k == 0 || u != c->unit_of(layer, projs[k - 1]))) {
@@ -913,7 +939,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
     if (split && dyn_shrink) {
         const int bm = split_bm(split_variant);
         const long main_wgs = tiles_of(bm, 128) * S;
-        ga.main_grid = (int)std::max<long>(0, std::min<long>(128, 256 - main_wgs));   // on entry: shrink-only workgroups
+        ga.main_grid = (int)std::max<long>(0, std::min<long>(c->n_cus / 2, c->n_cus - main_wgs));   // on entry: shrink-only workgroups
         // items a shrink-only workgroup finishes while a tile workgroup walks its K range: a 64-wide K tile of
         // the tile workgroup takes about 1 us, an item about 8
         const int nk = std::max(1, K / kBK / S);
@@ -954,7 +980,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
         const bool auto_variant = fv == 0;
         if (auto_variant) {
-            fv = pick_fused_variant(T, n_max, tiles_of);
+            fv = pick_fused_variant(c->n_cus, tiles_of);
             // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
             // (128-row tiles up to 128 tokens)
             if (T <= kSplitMaxTokens) fv = T <= 128 ? 9 : (fv == 4 ? 8 : (fv == 3 ? 9 : 10));
@@ -964,7 +990,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
                 const struct { int v, bm, bn; } cand[] = {{10, 256, 256}, {11, 256, 192}, {8, 256, 128}, {9, 128, 128}};
                 double best = 0.0;
                 for (const auto& cd : cand) {
-                    const double cost = (double)((tiles_of(cd.bm, cd.bn) + 255) / 256) * (cd.bm + cd.bn);
+                    const double cost = (double)((tiles_of(cd.bm, cd.bn) + c->n_cus - 1) / c->n_cus) * (cd.bm + cd.bn);
                     if (best == 0.0 || cost < best * 0.97) {
                         best = cost;
                         fv = cd.v;
@@ -980,16 +1006,16 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         int tail_S = 1;
         if (auto_variant && fv == 0 && c->cfg.path == LORA_PATH_AUTO && T > kSplitMaxTokens) {
             const long tiles_m_big = (T + 255) / 256, tiles_big = tiles_of(256, 256), tiles_n_big = tiles_big / tiles_m_big;
-            const long full = tiles_big / 256, rest = tiles_big % 256;
-            if (full >= 1 && rest > 0 && rest <= 128) {
-                const long m_tiles_main = std::min(tiles_m_big - 1, full * 256 / tiles_n_big);
+            const long full = tiles_big / c->n_cus, rest = tiles_big % c->n_cus;
+            if (full >= 1 && rest > 0 && rest <= c->n_cus / 2) {
+                const long m_tiles_main = std::min(tiles_m_big - 1, full * c->n_cus / tiles_n_big);
                 const long tail_rows = (long)T - m_tiles_main * 256;
                 if (m_tiles_main >= 1 && tail_rows > 0 && tail_rows <= kSplitMaxTokens) {
                     long tail_tiles = 0;
                     for (int k = 0; k < n; ++k) tail_tiles += (c->proj[projs[k]].d_out + 127) / 128;
                     tail_tiles *= (tail_rows + 255) / 256;
                     const long tail_pad = (tail_rows + 255) / 256 * 256;
-                    long ts = std::max<long>(1, std::min<long>(8, (256 + tail_tiles / 2) / tail_tiles));
+                    long ts = std::max<long>(1, std::min<long>(8, (c->n_cus + tail_tiles / 2) / tail_tiles));
                     ts = std::min<long>(ts, std::max(1, (K / kBK) / 2));
                     ts = std::min<long>(ts, (long)(scr.part_elems / ((size_t)tail_pad * (size_t)n_pad_total)));
                     if (ts >= 2) {
@@ -1003,10 +1029,10 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         // for Qwen2.5-7B).  When those CUs can finish the shrink well inside the time the tiles stream, they do
         // it as the first workgroups of the GEMM launch and the separate shrink launch goes.
         int front = 0;
-        if (sa.on && fv >= 8 && fv <= 11 && T <= kSplitMaxTokens && m_split == T &&
+        if (sa.on && fv >= 8 && fv <= 11 && T <= kSplitMaxTokens && m_split == T && !c->inline_shrink_off &&
             c->tune[LORA_TUNE_INLINE_SHRINK] != LORA_INLINE_SHRINK_OFF) {
             const int bm = fv == 9 ? 128 : 256, bn = fv == 10 ? 256 : (fv == 11 ? 192 : 128);
-            const long idle = 256 - tiles_of(bm, bn);
+            const long idle = c->n_cus - tiles_of(bm, bn);
             // unsplit up to K = 4096 (two rounds of loads per item): the tile workgroups then fetch one partial
             // result per row instead of two, behind their last K tile
             const int chunks = std::max(1, std::min<int>(kMaxShrinkChunks, K / 4096));
@@ -1014,8 +1040,8 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             const double t_main = (double)(bm + bn) * K * 2.0 / 48e3;                   // us, see plan_forward
             if (idle >= 8 && chunks <= n_kc &&      // the scratch for the shrink results is sized for n_kc chunks
                 (c->tune[LORA_TUNE_INLINE_SHRINK] == LORA_INLINE_SHRINK_ON ||
-                 (double)(pieces * chunks) * (4.0 * (K / chunks) / 2048.0) / (double)std::min<long>(idle, 64) <= 0.6 * t_main)) {
-                front = (int)std::min<long>(idle, 64);
+                 (double)(pieces * chunks) * (4.0 * (K / chunks) / 2048.0) / (double)std::min<long>(idle, c->n_cus / 4) <= 0.6 * t_main)) {
+                front = (int)std::min<long>(idle, c->n_cus / 4);
                 sa.n_kc = chunks;
                 sa.kc_len = ((K + chunks - 1) / chunks + kBK - 1) / kBK * kBK;
                 sa.n_kc = (K + sa.kc_len - 1) / sa.kc_len;
@@ -1035,6 +1061,11 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             GemmArgs a = ga;
             a.m_end = m_split;
             a.shrink_front = front;
+            // LORA_TUNE_SHRINK_WAIT_TEST: the tile workgroups expect one report more than will come and give up
+            // after that many polls (host-forced exercise of the expired wait; every kernel still ends normally)
+            const int wait_test = c->tune[LORA_TUNE_SHRINK_WAIT_TEST];
+            a.front_expect = front + (wait_test > 0 && front > 0 ? 1 : 0);
+            a.wait_spins = wait_test > 0 ? wait_test : kShrinkWaitSpins;
             a.sync = c->dev<uint32_t>(c->L.off_header) + 8;
             a.flags = c->d_flags();
             // 8 .. 11, 13, 14: 64-wide K tiles through the copy instruction; 12: the 32-wide 256 x 256 eight-wave kernel
@@ -1123,7 +1154,9 @@ lora_status lora_poll_device_flags(lora_ctx* c, uint32_t* flags, void* stream_v)
     if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
     if (flags) *flags = word;
     if (word & LORA_FLAG_INTERNAL) {
-        // a bounded wait inside a kernel expired: the counters it used may be left half-way
+        // a bounded wait inside a kernel expired: the counters it used may be left half-way, and the assumption
+        // the wait rests on (the launch's first workgroups run first) failed once: no more shrink inside a launch
+        c->inline_shrink_off = true;
         if (HIP_FAIL(launch_fill_i32(c->dev<int32_t>(c->L.off_header) + 8, 0, 2, s))) return LORA_ERR_HIP;
         if (HIP_FAIL(hipStreamSynchronize(s))) return LORA_ERR_HIP;
         g_last_hip_error = "a kernel's bounded wait for the launch's shrink workgroups expired";

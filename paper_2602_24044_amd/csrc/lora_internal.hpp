@@ -138,6 +138,8 @@ struct GemmArgs {
     // sync[0]: shrink workgroups that have finished, sync[1]: tile workgroups past the wait; the last of those
     // sets both back to zero.  The wait is bounded: when it expires, LORA_FLAG_INTERNAL is set in *flags.
     int32_t shrink_front;
+    int32_t front_expect;       // reports the tile workgroups wait for: shrink_front (one more in the host-forced test of the expired wait)
+    int32_t wait_spins;         // polls of the bounded wait
     int32_t pad_;
     uint32_t* sync;
     uint32_t* flags;
