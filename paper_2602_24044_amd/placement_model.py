@@ -17,23 +17,29 @@ This is a steady-state estimate, not the paper's models:
 from __future__ import annotations
 
 import json
+import os
 import sys
-from dataclasses import dataclass
-from typing import List, Sequence, Tuple
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+# the measured laws: written by `python -m paper_2602_24044_amd.latency_model --write profiles/latency_law.md`
+LATENCY_LAW = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles", "latency_law.md")
 
 
 @dataclass
 class ServingModel:
-    # Eq. 1 constants of one layer-step on this library (us), Llama-3.1-8B shapes
-    k4: float = 0.31
-    k5: float = 140.0
-    k6: float = 0.0047
-    k7: float = 1.0
+    # Eq. 1 constants of one layer-step on this library (us), Llama-3.1-8B shapes: no defaults, they are measured
+    # (from_profile reads them from the committed measurement)
+    k4: float
+    k5: float
+    k6: float
+    k7: float
+    # Lat_load: ms per adapter (whole model, host link): a table over the measured sizes, else the fitted line
+    load_ms_fixed: float
+    load_ms_per_rank: float
+    load_table_ms: Dict[int, float] = field(default_factory=dict)
     n_layers: int = 32
     other_us_per_step: float = 4000.0         # attention, norms, sampling: not part of this library
-    # Lat_load: ms per adapter = load_ms_fixed + load_ms_per_rank * rank (whole model, host link)
-    load_ms_fixed: float = 0.1
-    load_ms_per_rank: float = 0.094
     # memory
     hbm_bytes: float = 288e9
     backbone_bytes: float = 16.1e9
@@ -42,6 +48,26 @@ class ServingModel:
     # workload: global mean lengths (the paper approximates traces this way, Sec. 6)
     mean_input: float = 250.0
     mean_output: float = 230.0
+
+    @classmethod
+    def from_profile(cls, path: Optional[str] = None, **overrides) -> "ServingModel":
+        """The model with the constants of the committed measurement (profiles/latency_law.md)."""
+        from .latency_model import read_profile
+        kv = read_profile(path or LATENCY_LAW)
+        need = ("K4_us_per_token", "K5_us", "K6_per_adapter", "K7", "load_fixed_ms", "load_per_rank_ms")
+        missing = [k for k in need if k not in kv]
+        if missing:
+            raise ValueError(f"{path or LATENCY_LAW}: no value for {missing}")
+        args = dict(k4=kv["K4_us_per_token"], k5=kv["K5_us"], k6=kv["K6_per_adapter"], k7=kv["K7"],
+                    load_ms_fixed=kv["load_fixed_ms"], load_ms_per_rank=kv["load_per_rank_ms"],
+                    load_table_ms=dict(kv.get("load_table_ms", {})), n_layers=int(kv.get("load_layers", 32)))
+        args.update(overrides)
+        return cls(**args)
+
+    def load_ms(self, size: int) -> float:
+        if int(size) in self.load_table_ms:
+            return self.load_table_ms[int(size)]
+        return self.load_ms_fixed + self.load_ms_per_rank * size
 
     def max_requests(self, s_max: int, a_max: int) -> float:
         free = self.hbm_bytes - self.backbone_bytes - a_max * s_max * self.rank_unit_bytes
@@ -65,7 +91,7 @@ class ServingModel:
         # share of the step time lost to loads: requests of adapters outside the a_max most requested ones
         by_rate = sorted(zip(rates, sizes), reverse=True)
         miss = by_rate[a_max:]
-        load_s_per_s = sum(r * (self.load_ms_fixed + self.load_ms_per_rank * s) * 1e-3 for r, s in miss)
+        load_s_per_s = sum(r * self.load_ms(s) * 1e-3 for r, s in miss)
         busy = max(0.05, 1.0 - load_s_per_s)
         # requests in flight by Little's law: B = lam * mean_output * step(B) / busy, by fixed-point iteration
         b = 1.0
@@ -95,7 +121,7 @@ def place(size: Sequence[int], rate: Sequence[float], n_gpus: int, model: Servin
 def main() -> None:
     import numpy as np
     rng = np.random.default_rng(0)
-    model = ServingModel()
+    model = ServingModel.from_profile()
     out = []
     # workloads in the style of the paper's evaluation (Sec. 8.1, 8.3): sizes from {8, 16, 32}, Poisson rates from the
     # upper part of its rate set (a GPU of this size is then full before it holds 384 adapters, the last count

@@ -119,7 +119,7 @@ def test_placement_under_the_analytic_serving_model():
     # the stand-in predictors built from the measured laws: sanity of the model and validity of what the greedy
     # algorithm returns under it
     from paper_2602_24044_amd.placement_model import ServingModel, place
-    m = ServingModel()
+    m = ServingModel.from_profile()      # constants of the committed measurement (profiles/latency_law.md)
     assert m.max_requests(32, 8) > m.max_requests(32, 384) > 0            # slots take memory from the KV cache
     assert m.step_seconds(256, 32) > m.step_seconds(256, 1) > m.step_seconds(32, 1)
     light, heavy = [0.1] * 16, [40.0] * 16
@@ -131,7 +131,9 @@ def test_placement_under_the_analytic_serving_model():
     rng = np.random.default_rng(3)
     n = 1500
     size = [int(v) for v in rng.choice([8, 16, 32], size=n)]
-    rate = [float(v) for v in rng.choice([1.6, 0.8, 0.4, 0.1, 0.05, 0.025], size=n)]
+    # rates from the upper part of the paper's set: a GPU is then full well before it holds 384 adapters, the last
+    # count at which the algorithm tests an allocation (whatever the measured constants of the day are)
+    rate = [float(v) for v in rng.choice([3.2, 1.6, 0.8, 0.4], size=n)]
     gpu_of, a_max = place(size, rate, 32, m)
     assert gpu_of == P.greedy(32, size, rate, m.throughput, m.starvation)[0]
     used = max(gpu_of) + 1
