@@ -74,3 +74,30 @@ def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=
         return errs
     finally:
         sess.close()
+
+
+N_UNIFORM = 400
+BLOCK = 128        # the smallest output tile any GEMM variant here owns is 128 x 128 (the largest 256 x 256)
+TAIL_ROWS = 1024   # at least the rows the library may hand to the split-K path behind the full rounds
+
+
+def stratified_samples(rng, perm, seg_start, n_seg, T, d_out, n_uniform=N_UNIFORM):
+    """(token, column) pairs: one per BLOCK x BLOCK block of (position, column), two per segment, one per position
+    of the last TAIL_ROWS, n_uniform uniform ones, the corners.  Positions index the segment map's order; a
+    position becomes a token through perm."""
+    pos, col = [], []
+    for r0 in range(0, T, BLOCK):
+        for c0 in range(0, d_out, BLOCK):
+            pos.append(r0 + rng.integers(0, min(BLOCK, T - r0)))
+            col.append(c0 + rng.integers(0, min(BLOCK, d_out - c0)))
+    for s in range(n_seg):
+        for _ in range(2):
+            pos.append(rng.integers(seg_start[s], seg_start[s + 1]))
+            col.append(rng.integers(0, d_out))
+    for m in range(max(0, T - TAIL_ROWS), T):
+        pos.append(m)
+        col.append(rng.integers(0, d_out))
+    pos += list(rng.integers(0, T, size=n_uniform)) + [0, 0, T - 1, T - 1]
+    col += list(rng.integers(0, d_out, size=n_uniform)) + [0, d_out - 1, 0, d_out - 1]
+    pos = np.asarray(pos, dtype=np.int64)
+    return perm[pos].astype(np.int32), np.asarray(col, dtype=np.int32)
