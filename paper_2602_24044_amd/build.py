@@ -43,5 +43,43 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+# Host code with AddressSanitizer and UndefinedBehaviorSanitizer; the device side of a source is compiled as always.
+SAN_FLAGS = [f for opt in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all",
+                           "-fno-omit-frame-pointer") for f in ("-Xarch_host", opt)]
+# the sources that hold host logic (argument checks, slot table, launch planning, placement); the others are
+# kernels with a launcher each and come from the ordinary build
+SAN_SOURCES = ["lora_api.hip", "placement.cpp"]
+
+
+def build_sanitized(out_dir: str, driver_src: str) -> str:
+    """Builds, under out_dir, a copy of the library whose host logic is instrumented (a CPU test aid: run by
+    the tests that need no GPU) and links `driver_src`, a C++ program that calls it, into an executable with the
+    sanitizer runtimes.  Returns the executable's path."""
+    os.makedirs(out_dir, exist_ok=True)
+    os.makedirs(OBJ, exist_ok=True)
+    plain = [s for s in SOURCES if s not in SAN_SOURCES]
+    missing = [s for s in plain if not os.path.exists(os.path.join(OBJ, os.path.splitext(s)[0] + ".o"))]
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        list(ex.map(_compile, missing))
+
+    def compile_san(src: str) -> str:
+        obj = os.path.join(out_dir, os.path.splitext(os.path.basename(src))[0] + ".san.o")
+        flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g", *SAN_FLAGS]
+        res = subprocess.run([HIPCC, *flags, "-c", src, "-o", obj], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed for {src}:\n{res.stderr}")
+        return obj
+
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(compile_san, [os.path.join(CSRC, s) for s in SAN_SOURCES] + [driver_src]))
+    objs += [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in plain]
+    exe = os.path.join(out_dir, "host_driver")
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, *objs],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link (sanitized) failed:\n" + res.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     build()

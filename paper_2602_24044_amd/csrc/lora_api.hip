@@ -439,8 +439,13 @@ extern "C" {
 
 const char* lora_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
-const char* lora_status_string(lora_status s)
+const char* lora_status_string(lora_status status)
 {
+    // a C caller may hand in any integer: read the bits, not the enumeration (a value outside its range is not
+    // one a C++ enumeration may hold)
+    int s;
+    std::memcpy(&s, &status, sizeof s);
+    static_assert(sizeof(int) == sizeof(lora_status), "lora_status is passed as an int");
     switch (s) {
         case LORA_OK: return "ok";
         case LORA_ERR_INVALID_ARG: return "invalid argument";
