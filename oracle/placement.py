@@ -1,34 +1,41 @@
-"""CPU checker for the adapter placement step (paper Sec. 7: the greedy caching algorithm, Alg. 1, with its
-feasibility test, Alg. 2).  TEST INFRASTRUCTURE ONLY: nothing in the product path imports this module, and it
-shares no code with the library's own implementation.
+"""CPU checker for the adapter placement step (paper Sec. 7: greedy caching over GPUs with a feasibility test at
+fixed adapter counts).  TEST INFRASTRUCTURE ONLY: nothing in the product path imports this module, and it shares
+no code with the library's own implementation.
 
-The method is a heuristic, so this file takes its steps in the paper's order and names:
+The paper gives the method as a queue-driven procedure.  This file does not replay that procedure; it states what
+the procedure's result *is* and computes it from that statement, GPU by GPU:
 
-* ``priority_sorting``  - adapters by size, largest first; inside a group of equal size by arrival rate in
-  zigzag order (highest, lowest, second highest, second lowest, ...).
-* ``greedy``  - adapters leave the sorted queue one by one and are provisionally included in the GPU at the head of
-  the GPU queue; when that GPU's adapter count reaches a testing point the provisional set is tested: on success
-  it is committed, A_max[g] takes the tested configuration and the GPU stays at the head of the queue; on failure
-  the provisional set is rolled back into the adapter queue and the GPU leaves the queue.  An adapter with no GPU
-  left, or a failing test of what is still provisional when the queue is empty, raises ``Starvation``.
-* ``test_allocation``  - predicted throughput under the GPU's current A_max and under the next candidate of the
-  same list of counts; the better one is kept; the allocation is rejected if starvation is predicted for it.
+* Adapters are ranked once (``priority_order``): by size, largest first; adapters of one size by arrival rate,
+  alternating between the high end and the low end of what is left (highest, lowest, second highest, ...).
+* Rolled-back adapters return to the front of the ranked sequence and a GPU only ever takes from its front, so the
+  adapters of one GPU are a contiguous stretch of the ranking and the GPUs are used in index order.  What one GPU
+  ends up with therefore depends only on the part of the ranking that is still unplaced (``fill_gpu``): it grows
+  through the checkpoint counts 8, 16, ..., 384; at each checkpoint the first `count` unplaced adapters are judged
+  as a set; the GPU keeps the largest checkpoint that was judged free of starvation before the first one that was
+  not, and after a failed judgement takes nothing more.  If every checkpoint up to the number of unplaced adapters
+  passes, the GPU also takes the remainder, which is judged once as a whole; failing that judgement, or running
+  out of GPUs, means no starvation-free placement exists under this method (``Starvation``).
+* Each judgement also moves the GPU's configuration A_max (``choose_config``): the candidate is the next count of
+  the checkpoint list above the current A_max; the GPU keeps whichever of the two the throughput predictor rates
+  higher for the judged set (the candidate on a tie or when there is no current one), and the starvation predictor
+  is asked about the set under that choice.
 
-The two predictors (the paper's ML models) are inputs: callables (sizes, rates, a_max) -> throughput and
-(sizes, rates, a_max) -> bool, given the sizes and rates of every adapter on the GPU (committed first, then
-provisional, each in the order it arrived).
+``check`` is the converse: given any placement it verifies those properties one by one, without building the
+placement itself.  The tests run it on this file's own results and on the library's.
 
-Readings where the pseudocode is silent: a GPU that has no configuration yet (A_max = 0) takes the first candidate
-without a comparison; the candidate after the last of the list is the last itself; ties in a sort are broken by
-adapter index; rolled-back adapters re-enter the queue at their place in the priority order.
+The two predictors (the paper trains ML models for them) are inputs: callables (sizes, rates, a_max) -> throughput
+and (sizes, rates, a_max) -> bool, given the sizes and rates of the judged set in ranking order.
 
-Pins (tests, CPU only): a hand-worked sorting example, hand-worked runs with a predictor that allows a fixed number
+Readings where the paper is silent: a GPU without a configuration takes the first candidate without a comparison;
+the candidate above the last checkpoint is the last checkpoint; ties in a ranking go to the lower adapter index.
+
+Pins (tests, CPU only): a hand-worked ranking example, hand-worked runs with a predictor that allows a fixed number
 of adapters per GPU (fill counts, the GPU that closes, the error cases), the A_max walk under a throughput curve with
-a known peak, and validity of the result on random inputs.
+a known peak, the order in which the predictors see the adapters, and ``check`` on random inputs (including that it
+rejects perturbed placements).
 """
 from __future__ import annotations
 
-from collections import deque
 from typing import Callable, List, Sequence, Tuple
 
 TESTING_POINTS = (8, 16, 32, 64, 96, 128, 160, 192, 256, 320, 384)
@@ -38,89 +45,99 @@ class Starvation(Exception):
     """No starvation-free allocation was found (paper Sec. 7)."""
 
 
-def priority_sorting(size: Sequence[int], rate: Sequence[float]) -> List[int]:
-    order: List[int] = []
+def priority_order(size: Sequence[int], rate: Sequence[float]) -> List[int]:
+    """Ranking of the adapters: position k of a size group of m adapters, sorted by falling rate, holds the
+    (k/2)-th from the top when k is even and the (k/2)-th from the bottom when k is odd."""
+    ranking: List[int] = []
     for s in sorted(set(size), reverse=True):
-        group = sorted((a for a in range(len(size)) if size[a] == s), key=lambda a: (-rate[a], a))
-        lo, hi, take_high = 0, len(group) - 1, True
-        while lo <= hi:
-            if take_high:
-                order.append(group[lo])
-                lo += 1
-            else:
-                order.append(group[hi])
-                hi -= 1
-            take_high = not take_high
-    return order
+        falling = sorted((a for a in range(len(size)) if size[a] == s), key=lambda a: (-rate[a], a))
+        m = len(falling)
+        ranking += [falling[k // 2] if k % 2 == 0 else falling[m - 1 - k // 2] for k in range(m)]
+    return ranking
 
 
-def next_gpu_config(p: int) -> int:
-    for t in TESTING_POINTS:
-        if t > p:
-            return t
-    return TESTING_POINTS[-1]
+def candidate_after(a_max: int) -> int:
+    higher = [c for c in TESTING_POINTS if c > a_max]
+    return higher[0] if higher else TESTING_POINTS[-1]
 
 
-def test_allocation(alloc: Sequence[int], prov: Sequence[int], size, rate, p: int,
-                    predict_throughput: Callable, predict_starvation: Callable) -> Tuple[bool, List[int], int]:
-    p_next = next_gpu_config(p)
-    everyone = list(alloc) + list(prov)
-    sizes = [size[a] for a in everyone]
-    rates = [rate[a] for a in everyone]
-    if p == 0:
-        p_best = p_next
-    else:
-        t_now = predict_throughput(sizes, rates, p)
-        t_next = predict_throughput(sizes, rates, p_next)
-        p_best = p if t_now > t_next else p_next
-    if predict_starvation(sizes, rates, p_best):
-        return False, [], 0
-    return True, list(prov), p_best
+def choose_config(sizes, rates, a_max: int, predict_throughput: Callable) -> int:
+    cand = candidate_after(a_max)
+    if a_max == 0:
+        return cand
+    return a_max if predict_throughput(sizes, rates, a_max) > predict_throughput(sizes, rates, cand) else cand
 
 
-def greedy(n_gpus: int, size: Sequence[int], rate: Sequence[float], predict_throughput: Callable,
-           predict_starvation: Callable) -> Tuple[List[int], List[int]]:
-    """Returns (g[a] for every adapter, A_max[g] for every GPU; 0 for a GPU left empty)."""
-    n = len(size)
-    g_of = [-1] * n
+def fill_gpu(sizes: Sequence[int], rates: Sequence[float], predict_throughput: Callable,
+             predict_starvation: Callable) -> Tuple[int, int, bool]:
+    """One GPU facing the unplaced adapters (sizes / rates in ranking order).  Returns (how many of them it keeps,
+    its A_max, whether it is closed).  Raises Starvation when the judgement of the remainder fails."""
+    kept, a_max = 0, 0
+    stops = [c for c in TESTING_POINTS if c <= len(sizes)]
+    if len(sizes) not in stops:
+        stops.append(len(sizes))                      # the remainder, judged once everything else is placed
+    for count in stops:
+        choice = choose_config(sizes[:count], rates[:count], a_max, predict_throughput)
+        if predict_starvation(sizes[:count], rates[:count], choice):
+            if count not in TESTING_POINTS:
+                raise Starvation("the last %d adapters do not fit their GPU" % (count - kept))
+            return kept, a_max, True
+        kept, a_max = count, choice
+    return kept, a_max, False
+
+
+def place(n_gpus: int, size: Sequence[int], rate: Sequence[float], predict_throughput: Callable,
+          predict_starvation: Callable) -> Tuple[List[int], List[int]]:
+    """Returns (GPU of every adapter, A_max of every GPU; 0 for a GPU that holds nothing)."""
+    ranking = priority_order(size, rate)
+    gpu_of = [-1] * len(size)
     a_max = [0] * n_gpus
-    order = priority_sorting(size, rate)
-    place = {a: k for k, a in enumerate(order)}
-    a_q = deque(order)
-    g_q = deque(range(n_gpus))
-    alloc: List[List[int]] = [[] for _ in range(n_gpus)]
-    prov: List[List[int]] = [[] for _ in range(n_gpus)]
-
-    def commit(g: int, alloc_set: List[int], p_new: int) -> None:
-        alloc[g] += prov[g]
-        prov[g] = []
-        for a in alloc_set:
-            g_of[a] = g
-        a_max[g] = p_new
-
-    while a_q:
-        a = a_q.popleft()
-        if not g_q:
-            raise Starvation("no GPU left for adapter %d" % a)
-        g = g_q.popleft()
-        prov[g].append(a)
-        if len(alloc[g]) + len(prov[g]) in TESTING_POINTS:
-            ok, alloc_set, p_new = test_allocation(alloc[g], prov[g], size, rate, a_max[g], predict_throughput,
-                                                   predict_starvation)
-            if ok:
-                commit(g, alloc_set, p_new)
-                g_q.appendleft(g)
-            else:
-                un_alloc = prov[g]
-                prov[g] = []
-                a_q = deque(sorted(list(a_q) + un_alloc, key=lambda b: place[b]))
-        else:
-            g_q.appendleft(g)
+    first = 0                                         # ranking[first:] is unplaced
     for g in range(n_gpus):
-        if prov[g]:
-            ok, alloc_set, p_new = test_allocation(alloc[g], prov[g], size, rate, a_max[g], predict_throughput,
-                                                   predict_starvation)
-            if not ok:
-                raise Starvation("GPU %d cannot take its last %d adapters" % (g, len(prov[g])))
-            commit(g, alloc_set, p_new)
-    return g_of, a_max
+        if first == len(ranking):
+            break
+        rest = ranking[first:]
+        kept, a_max[g], _ = fill_gpu([size[a] for a in rest], [rate[a] for a in rest], predict_throughput,
+                                     predict_starvation)
+        for a in rest[:kept]:
+            gpu_of[a] = g
+        first += kept
+    if first < len(ranking):
+        raise Starvation("no GPU left for adapter %d" % ranking[first])
+    return gpu_of, a_max
+
+
+def check(n_gpus: int, size: Sequence[int], rate: Sequence[float], predict_throughput: Callable,
+          predict_starvation: Callable, gpu_of: Sequence[int], a_max: Sequence[int]) -> None:
+    """Asserts that (gpu_of, a_max) has the properties the method's result must have; builds nothing."""
+    n = len(size)
+    ranking = priority_order(size, rate)
+    assert len(gpu_of) == n and len(a_max) == n_gpus
+    assert all(0 <= g < n_gpus for g in gpu_of)
+    along = [gpu_of[a] for a in ranking]
+    assert along == sorted(along), "a GPU's adapters must be one stretch of the ranking, GPUs in index order"
+    first = 0
+    for g in range(n_gpus):
+        count = along.count(g)
+        rest = ranking[first:]
+        sz, rt = [size[a] for a in rest], [rate[a] for a in rest]
+        last_gpu_with_work = first + count == n
+        # the walk of A_max over the checkpoints this GPU passed, and that each of them was free of starvation
+        walk = 0
+        passed = [c for c in TESTING_POINTS if c <= count]
+        if count and count not in TESTING_POINTS:
+            assert last_gpu_with_work, "only the GPU that takes the end of the ranking holds an off-checkpoint count"
+            assert passed == [c for c in TESTING_POINTS if c <= len(rest)]
+            passed.append(count)
+        for c in passed:
+            walk = choose_config(sz[:c], rt[:c], walk, predict_throughput)
+            assert not predict_starvation(sz[:c], rt[:c], walk), (g, c)
+        assert a_max[g] == walk, (g, a_max[g], walk)
+        # a GPU that stopped short of the unplaced adapters did so because its next checkpoint was judged to starve
+        if not last_gpu_with_work and first < n:
+            nxt = [c for c in TESTING_POINTS if c > count]
+            assert nxt and nxt[0] <= len(rest), (g, count)
+            choice = choose_config(sz[:nxt[0]], rt[:nxt[0]], walk, predict_throughput)
+            assert predict_starvation(sz[:nxt[0]], rt[:nxt[0]], choice), (g, count)
+        first += count
+    assert first == n

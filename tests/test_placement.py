@@ -35,7 +35,7 @@ def _predictors(rng):
 
 def _both(size, rate, n_gpus, thr, starve):
     try:
-        want = P.greedy(n_gpus, size, rate, thr, starve)
+        want = P.place(n_gpus, size, rate, thr, starve)
     except P.Starvation:
         want = None
     try:
@@ -58,6 +58,8 @@ def test_placement_matches_the_oracle(seed):
     if want is not None:
         assert got[0] == want[0]
         assert got[1] == want[1]
+        # and the library's result on its own against the properties the method's result must have
+        P.check(n_gpus, size, rate, thr, starve, got[0], got[1])
 
 
 def test_both_outcomes_occur_in_the_random_cases():
@@ -75,7 +77,7 @@ def test_both_outcomes_occur_in_the_random_cases():
 def test_priority_sorting_matches_the_oracle(seed):
     rng = np.random.default_rng(seed)
     size, rate = _workload(rng, int(rng.integers(0, 400)))
-    assert B.lora_priority_sorting(size, rate) == P.priority_sorting(size, rate)
+    assert B.lora_priority_sorting(size, rate) == P.priority_order(size, rate)
 
 
 def test_hand_worked_cases_on_the_library():
@@ -135,7 +137,8 @@ def test_placement_under_the_analytic_serving_model():
     # count at which the algorithm tests an allocation (whatever the measured constants of the day are)
     rate = [float(v) for v in rng.choice([3.2, 1.6, 0.8, 0.4], size=n)]
     gpu_of, a_max = place(size, rate, 32, m)
-    assert gpu_of == P.greedy(32, size, rate, m.throughput, m.starvation)[0]
+    assert gpu_of == P.place(32, size, rate, m.throughput, m.starvation)[0]
+    P.check(32, size, rate, m.throughput, m.starvation, gpu_of, a_max)
     used = max(gpu_of) + 1
     assert 1 < used <= 32
     for g in range(used):
