@@ -132,6 +132,58 @@ def calibrate_stream():
                       "frac_of_peak": best / HBM_PEAK_GBS}))
 
 
+def calibrate_gemm():
+    """Context for the MFMA fraction of the prefill GEMM: the library's backbone GEMM (no adapter rows) and the
+    vendor library's bf16 GEMM (torch.matmul) on one prefill-sized problem, first on normally distributed data, then
+    on zeros, with the shader clock that rocm-smi shows under each.  Operands of zeros toggle almost no bits in
+    the MFMA data path, so the difference between the two data sets is what the power limit costs; the vendor's
+    figure on the same data is what a tuned kernel reaches on this chip."""
+    import numpy as np
+    import torch
+    from paper_2602_24044_amd import binding as B
+    from paper_2602_24044_amd import workloads as wl
+    from paper_2602_24044_amd.runtime import Session
+    T, N, K = 8192, 14336, 4096
+    flops = 2.0 * T * N * K
+    ids = np.full(T, -1, dtype=np.int32)
+    w = wl.custom("calibrate_gemm", 0, [(K, N)], ["p"], 8, 16, wl.BUCKET_SORTED, ids, {0: 16}, resident=[])
+    sess = Session(w, path=B.LORA_PATH_FUSED)
+    sess.bucket()
+    x, W = sess.x[0], sess.W[0]
+    out = {}
+
+    def timed(fn, iters=12):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        with ClockSampler() as cs:                           # keep the load up while the clocks are read
+            t_end = time.time() + 1.5
+            while time.time() < t_end:
+                for _ in range(iters):
+                    fn()
+                torch.cuda.synchronize()
+        clocks = cs.summary() or {}
+        us = e0.elapsed_time(e1) / iters * 1e3
+        return {"us": us, "tflops": flops / us / 1e6, "frac_of_peak": flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+                "sclk_mhz": [clocks.get("sclk_mhz_min"), clocks.get("sclk_mhz_max")]}
+
+    for data in ("normal", "zeros"):
+        if data == "zeros":
+            x.zero_()
+            W.zero_()
+        out[data] = {"library": timed(lambda: sess.forward(0)),
+                     "library_kernel": B.lora_last_launches(sess.ctx),
+                     "vendor_matmul": timed(lambda: torch.matmul(x, W.t()))}
+    sess.close()
+    print(json.dumps({"probe": "gemm", "shape": {"T": T, "N": N, "K": K}, "dtype": "bf16", "results": out}))
+
+
 def calibrate_mfma():
     """Sustained bf16 MFMA rate and the shader clock under that load (lora_calibrate_mfma)."""
     import torch
@@ -237,6 +289,8 @@ def main():
                     help="run plain device copy kernels of known size and exit (reference for the HBM byte counters)")
     ap.add_argument("--calibrate-stream", action="store_true",
                     help="measure the read rate of a plain stream (the roof a weight stream can reach) and exit")
+    ap.add_argument("--calibrate-gemm", action="store_true",
+                    help="backbone GEMM of the library and the vendor library's GEMM on normal data and on zeros")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="measure the sustained bf16 MFMA rate and the clock under it and exit")
     args = ap.parse_args()
@@ -250,6 +304,9 @@ def main():
         return
     if args.calibrate_stream:
         calibrate_stream()
+        return
+    if args.calibrate_gemm:
+        calibrate_gemm()
         return
     if args.calibrate_mfma:
         calibrate_mfma()

@@ -5,7 +5,7 @@
 // by the slot their adapter occupies so that each adapter's A and B are streamed once per step.
 // SORTED: stable counting sort of token indices by slot; RUNS: token order kept, runs of equal
 // slot.  One 1024-thread workgroup: LDS histogram, LDS prefix scan, wavefront ballots for the
-// stable rank of a token among equal keys.
+// stable rank of a token among equal keys.  RUNS above 4096 tokens: one workgroup per 1024 tokens, two launches.
 #include "lora_internal.hpp"
 
 namespace lora {
@@ -248,6 +248,115 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     }
 }
 
+// RUNS mode above kFastT tokens (a prefill batch).  The order is the token order, so everything but the numbering of
+// the segments and pieces depends on a token and its predecessor only: one workgroup per kBT tokens, in two
+// launches.  The first writes the per-row tables and counts the heads of segments and pieces in its chunk
+// (a.tok_key[2 c], [2 c + 1]: the array is unused in this mode); the second numbers them from the counts of the
+// chunks in front.  A piece ends at every multiple of kPieceRows, which every chunk boundary is, so no piece
+// spans two chunks.
+__device__ inline int runs_key(const BucketArgs& a, int t, bool* bad)
+{
+    const int id = a.ids[t];
+    if (id < 0) return 0;
+    int s = -1;
+    if (id < a.n_ids) s = a.id2slot[id];
+    if (s >= 0 && s < a.n_slots) return s + 1;
+    *bad = true;
+    return 0;
+}
+
+__global__ __launch_bounds__(kBT) void bucket_runs_rows_kernel(BucketArgs a)
+{
+    __shared__ int s_wave[kNW + 1];
+    __shared__ int s_key[kBT];
+    static_assert(kBT % kPieceRows == 0, "pieces must not span chunks");
+    const int tid = threadIdx.x, c = blockIdx.x;
+    const int t = c * kBT + tid;
+    const bool valid = t < a.T;
+    bool bad = false;
+    const int key = valid ? runs_key(a, t, &bad) : 0;
+    bool prev_bad = false;                                   // reported by the chunk that owns that token
+    const int first_prev = (tid == 0 && c > 0) ? runs_key(a, t - 1, &prev_bad) : 0;
+    s_key[tid] = key;
+    if (bad) atomicOr(a.flags, 1u);
+    __syncthreads();
+    int seg_head = 0, piece_head = 0;
+    if (valid) {
+        const int s = key - 1;
+        a.perm[t] = t;
+        a.row_slot[t] = s;
+        a.row_rank[t] = s >= 0 ? a.slot_rank[s] : 0;
+        a.row_scale[t] = s >= 0 ? a.slot_scale[s] : 0.f;
+        const int prev = tid > 0 ? s_key[tid - 1] : first_prev;
+        seg_head = (t == 0) || prev != key;
+        piece_head = seg_head || (t % kPieceRows) == 0;
+    }
+    int n_seg, n_piece;
+    block_excl_scan(seg_head, s_wave, &n_seg);
+    block_excl_scan(piece_head, s_wave, &n_piece);
+    if (tid == 0) {
+        a.tok_key[2 * c] = n_seg;
+        a.tok_key[2 * c + 1] = n_piece;
+    }
+}
+
+__global__ __launch_bounds__(kBT) void bucket_runs_number_kernel(BucketArgs a)
+{
+    __shared__ int s_wave[kNW + 1];
+    __shared__ int s_slot[kBT + 1];                          // [0]: the token in front of the chunk
+    __shared__ int s_pstart[kBT + 1];
+    const int tid = threadIdx.x, c = blockIdx.x, n_chunks = gridDim.x;
+    const int t = c * kBT + tid;
+    const int T = a.T;
+    const bool valid = t < T;
+    const int chunk_end = (c + 1) * kBT < T ? (c + 1) * kBT : T;
+    // heads in the chunks in front of this one
+    int seg_before = 0, piece_before = 0;
+    for (int k = tid; k < c; k += kBT) {
+        seg_before += a.tok_key[2 * k];
+        piece_before += a.tok_key[2 * k + 1];
+    }
+    int seg_base, piece_base;
+    block_excl_scan(seg_before, s_wave, &seg_base);
+    block_excl_scan(piece_before, s_wave, &piece_base);
+    const int s = valid ? a.row_slot[t] : -2;
+    s_slot[tid + 1] = s;
+    if (tid == 0) s_slot[0] = c > 0 ? a.row_slot[t - 1] : -2;
+    __syncthreads();
+    int seg_head = 0, piece_head = 0;
+    if (valid) {
+        seg_head = (t == 0) || s_slot[tid] != s;
+        piece_head = seg_head || (t % kPieceRows) == 0;
+    }
+    int n_seg, n_piece;
+    const int seg_ex = block_excl_scan(seg_head, s_wave, &n_seg);
+    const int piece_ex = block_excl_scan(piece_head, s_wave, &n_piece);
+    if (seg_head) {
+        a.seg_start[seg_base + seg_ex] = t;
+        a.seg_slot[seg_base + seg_ex] = s;
+    }
+    if (piece_head) s_pstart[piece_ex] = t;
+    if (tid == 0) s_pstart[n_piece] = chunk_end;
+    __syncthreads();
+    if (piece_head) {
+        const int p = piece_base + piece_ex;
+        a.piece_start[p] = t;
+        a.piece_slot[p] = s;
+        int4 rec;
+        rec.x = t;
+        rec.y = s_pstart[piece_ex + 1] - t;
+        rec.z = s;
+        rec.w = s >= 0 ? a.slot_rank[s] : 0;
+        reinterpret_cast<int4*>(a.piece_info)[p] = rec;
+    }
+    if (c == n_chunks - 1 && tid == 0) {
+        a.seg_start[seg_base + n_seg] = T;
+        a.piece_start[piece_base + n_piece] = T;
+        *a.n_seg = seg_base + n_seg;
+        *a.n_pieces = piece_base + n_piece;
+    }
+}
+
 __global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
@@ -291,6 +400,12 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t value, size_t n)
 
 hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream)
 {
+    if (a.mode != 0 && a.T > kFastT) {
+        const int chunks = (a.T + kBT - 1) / kBT;
+        hipLaunchKernelGGL(bucket_runs_rows_kernel, dim3(chunks), dim3(kBT), 0, stream, a);
+        hipLaunchKernelGGL(bucket_runs_number_kernel, dim3(chunks), dim3(kBT), 0, stream, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(kBT), 0, stream, a);
     return hipGetLastError();
 }

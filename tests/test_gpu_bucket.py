@@ -58,3 +58,41 @@ def test_segment_map_bit_exact(mode, T, n_slots, seed):
         assert check_segments(sess, w2) == 0
     finally:
         sess.close()
+
+
+def test_runs_map_over_several_workgroups_with_runs_across_their_boundaries():
+    # above 4096 tokens the RUNS map is built by one workgroup per 1024 tokens: runs that end exactly at, one
+    # before, one after and far across those boundaries, a run of one token on each side of a boundary, tokens of an
+    # adapter that is not resident (flag, served backbone-only), and a ragged last chunk; the projection on top reads
+    # the per-row tables and the piece records of the same call
+    from gpu_util import TOL, rel_err
+    from paper_2602_24044_amd.runtime import bf16_tensor_to_bits
+    T = 5 * 1024 + 77
+    ids = np.full(T, -1, dtype=np.int32)
+    cuts = [0, 5, 1023, 1024, 1025, 2047, 2049, 3072, 3073, 3500, 4096 + 31, 4096 + 32, 4096 + 33, 5120, 5121, T]
+    for k, (b, e) in enumerate(zip(cuts[:-1], cuts[1:])):
+        ids[b:e] = [0, 1, 2, -1, 3, 7][k % 6]            # adapter 7 is never loaded
+    ranks = {0: 8, 1: 16, 2: 32, 3: 8, 7: 8}
+    w = wl.custom("runs_chunks", 31, [(128, 96)], ["p"], 6, 32, wl.BUCKET_RUNS, ids, ranks, resident=[0, 1, 2, 3])
+    announce(f"bucket runs over several workgroups T={T}")
+    sess = Session(w)
+    try:
+        sess.load(w.resident, slots=[4, 0, 5, 2])
+        sess.bucket()
+        assert check_segments(sess, w) == oracle.FLAG_NOT_RESIDENT
+        out = sess.forward(0)
+        torch.cuda.synchronize()
+        st, word = B.lora_poll_device_flags(sess.ctx)
+        assert st == B.LORA_ERR_NOT_RESIDENT and word == B.LORA_FLAG_NOT_RESIDENT
+        served = np.where(ids == 7, -1, ids).astype(np.int32)
+        y_ref = oracle.project(w.x[0], w.W[0], served, oracle.adapters_of(w, 0))
+        assert rel_err(bf16_tensor_to_bits(out), y_ref) <= TOL
+        # the same context, a shorter step through the single-workgroup kernel, then the long one again
+        short = torch.from_numpy(ids[:700].copy()).to(sess.device)
+        sess.bucket(short)
+        w_short = wl.custom("runs_short", 31, [(128, 96)], ["p"], 6, 32, wl.BUCKET_RUNS, ids[:700].copy(), ranks, resident=[])
+        assert check_segments(sess, w_short) == 0
+        sess.bucket()
+        assert check_segments(sess, w) == oracle.FLAG_NOT_RESIDENT
+    finally:
+        sess.close()
