@@ -348,7 +348,9 @@ def main():
     in_use = w.distinct_adapters()
     sessions = []
     for _ in range(copies):
-        s = Session(w, path=args.path)
+        # adapters that travel inside the timed region are kept as one pinned buffer each (A and B of a projection
+        # back to back, as inside a slot): the load then moves one run per projection
+        s = Session(w, path=args.path, packed_host=reload_each_step)
         for k, v in tune.items():
             B.lora_set_tuning(s.ctx, k, v)
         s.load(w.resident)

@@ -289,7 +289,7 @@ enum {
 };
 /* Values of LORA_TUNE_COPY_ENGINE. */
 enum {
-    LORA_COPY_AUTO = 0,   /* the copy engine for whole-layer runs of at least 1 MiB (n_layers > 1), else the kernel */
+    LORA_COPY_AUTO = 0,   /* the copy engine when every contiguous run of the load has at least 128 KiB, else the kernel */
     LORA_COPY_KERNEL = 1, /* a kernel that reads the pinned host memory, a batch of runs per launch */
     LORA_COPY_ENGINE = 2  /* hipMemcpyAsync per run */
 };

@@ -53,7 +53,8 @@ bool static_scratch_of(int device, void** out)
 }
 
 constexpr size_t kAlign = 256;
-constexpr size_t kEngineRunBytes = 1u << 20;   // shortest run for which a copy call per run pays
+constexpr size_t kEngineRunBytes = 128u << 10; // shortest run for which a copy call per run pays
+constexpr int kMarkedCallsPerLoad = 64;        // calls after a load that still mark their end for the next load (see lora_ctx)
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
@@ -230,6 +231,24 @@ struct lora_ctx {
     hipStream_t copy_stream = nullptr;      // stream of the latest load
     hipStream_t last_fwd_stream = nullptr;
     bool have_fwd = false;
+    // A context that loads adapters between its steps marks the end of each of its calls with ev_fwd (fwd_marked:
+    // ev_fwd stands behind the last call), so that a load waits for this context's work only; the calls after
+    // which that is still done are counted down from every load.  Without the mark a load records the event at
+    // the tail of the stream and so also waits for what other contexts have enqueued there since.
+    bool fwd_marked = false;
+    int marks_left = 0;
+    bool work_enqueued(hipStream_t s)
+    {
+        last_fwd_stream = s;
+        have_fwd = true;
+        fwd_marked = false;
+        if (marks_left > 0) {
+            --marks_left;
+            if (hipEventRecord(ev_fwd, s) != hipSuccess) return false;
+            fwd_marked = true;
+        }
+        return true;
+    }
 
     int32_t tune[8] = {0};
     bool inline_shrink_off = false;         // a bounded wait inside a launch has expired once: shrink as a launch of its own from then on
@@ -317,7 +336,7 @@ struct ForwardPlan {
 };
 
 lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t* projs, size_t part_elems,
-                         ForwardPlan& out)
+                         size_t vpart_elems, ForwardPlan& out)
 {
     const int K = c->proj[projs[0]].d_in;
     // the slices sit side by side along N, each padded to a multiple of 128 columns
@@ -417,6 +436,17 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
             const long pieces = (long)n * std::min<long>(T, (long)c->n_resident + (T + kPieceRows - 1) / kPieceRows);
             if (pieces <= wgs) n_kc = (int)std::max<long>(1, std::min<long>(n_kc, wgs / std::max<long>(pieces, 1)));
         }
+        kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
+        n_kc = (K + kc_len - 1) / kc_len;
+    } else {
+        // Larger batches run the shrink as a launch of its own, one item (piece x K chunk) per workgroup, two
+        // workgroups per CU at a time.  A mixed step of a few thousand tokens has only a few hundred pieces, each a
+        // chain of loads over all of K: K is cut until the launch has about four rounds of items (chunks of at least
+        // 1024, as many as the scratch for the partial results holds).
+        const long pieces = (long)n * ((T + kPieceRows - 1) / kPieceRows + std::min<long>(T, (long)c->n_resident));
+        const long want = (8L * c->n_cus + pieces - 1) / std::max<long>(pieces, 1);
+        const long room = (long)(vpart_elems / ((size_t)n * (size_t)T * (size_t)c->cfg.max_rank));
+        n_kc = (int)std::max<long>(1, std::min<long>({want, (long)(K / kShrinkKC), room, (long)kMaxShrinkChunks}));
         kc_len = ((K + n_kc - 1) / n_kc + kBK - 1) / kBK * kBK;
         n_kc = (K + kc_len - 1) / kc_len;
     }
@@ -672,9 +702,10 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     hipStream_t cs = static_cast<hipStream_t>(copy_stream_v);
     if (c->have_fwd && c->last_fwd_stream != cs) {
         // earlier steps may still read the slots about to be overwritten
-        if (HIP_FAIL(hipEventRecord(c->ev_fwd, c->last_fwd_stream))) return LORA_ERR_HIP;
+        if (!c->fwd_marked && HIP_FAIL(hipEventRecord(c->ev_fwd, c->last_fwd_stream))) return LORA_ERR_HIP;
         if (HIP_FAIL(hipStreamWaitEvent(cs, c->ev_fwd, 0))) return LORA_ERR_HIP;
     }
+    c->marks_left = kMarkedCallsPerLoad;
     for (size_t b = 0; b < steps.size(); b += kMetaBatch) {
         MetaUpdates u;
         std::memset(&u, 0, sizeof u);
@@ -700,9 +731,9 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     // one on an idle GPU and for short runs (a copy call per run costs the host and the engine about 10 us), but
     // its workgroups find no free compute unit while forward kernels run.  The copy engine (hipMemcpyAsync per
     // run): needs no compute unit, so a load in the shadow of a running step keeps its rate.  Unless told
-    // otherwise the engine carries the loads of a context with several layers whose runs all reach
-    // kEngineRunBytes (whole layers of an adapter kept as one host buffer), the kernel everything else; a source
-    // that is not device-visible pinned host memory always goes through hipMemcpyAsync.
+    // otherwise the engine carries a load whose runs all reach kEngineRunBytes (the matrices of a projection,
+    // or whole layers, of an adapter kept as one host buffer), the kernel everything else; a source that is not
+    // device-visible pinned host memory always goes through hipMemcpyAsync.
     char* slots = c->base + c->L.off_slots;
     const bool by_layer = c->n_layers > 1;
     const int n_units = by_layer ? c->n_layers : n_proj;
@@ -739,7 +770,7 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     }
     const int tuned = c->tune[LORA_TUNE_COPY_ENGINE];
     const bool engine = tuned == LORA_COPY_ENGINE ||
-                        (tuned != LORA_COPY_KERNEL && by_layer && shortest >= kEngineRunBytes);
+                        (tuned != LORA_COPY_KERNEL && shortest >= kEngineRunBytes);
     for (int u = 0; u < n_units; ++u) {
         CopyBatch batch;
         batch.n = 0;
@@ -815,8 +846,7 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     c->epoch += 1;
     c->seg_T = T;
     c->seg_mode = mode;
-    c->last_fwd_stream = s;
-    c->have_fwd = true;
+    if (!c->work_enqueued(s)) return LORA_ERR_HIP;
     out->perm = a.perm;
     out->seg_start = a.seg_start;
     out->seg_slot = a.seg_slot;
@@ -880,7 +910,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         }
     }
     ForwardPlan plan;
-    if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, plan); st != LORA_OK)
+    if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, scr.vpart_elems, plan); st != LORA_OK)
         return (st == LORA_ERR_OOM && scr.is_static) ? LORA_ERR_SCRATCH_LIMIT : st;
     const int K = plan.K, Mpad = plan.Mpad, n_max = plan.n_max, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
     const long n_pad_total = plan.n_pad_total;
@@ -1097,8 +1127,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         const lora_status st = launch_split(ga, sa, split_variant);
         if (st != LORA_OK) return st;
     }
-    c->last_fwd_stream = s;
-    c->have_fwd = true;
+    if (!c->work_enqueued(s)) return LORA_ERR_HIP;
     return LORA_OK;
 }
 

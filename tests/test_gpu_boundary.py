@@ -88,3 +88,39 @@ def test_expired_wait_inside_a_launch_is_flagged_and_the_context_recovers():
         assert B.lora_poll_device_flags(sess.ctx) == (B.LORA_OK, 0)
     finally:
         sess.close()
+
+
+def test_loads_on_a_copy_stream_between_steps_wait_for_this_contexts_forwards_only():
+    """Two contexts share the compute stream; context A reloads two slots before each of its steps on a copy stream
+    of its own.  The load must wait for A's previous forwards (they read the slots it overwrites) and may run while
+    B's step, enqueued in between, is still computing: A's outputs are checked after every step against the adapters
+    that were in the slots for that step."""
+    wa = wl.config2(shrink=8, n_tokens=300)
+    wb = wl.config2(shrink=4, n_tokens=512)
+    announce(f"loads between steps: A={wa.name} B={wb.name}")
+    A, Bs = Session(wa), Session(wb)
+    copy = torch.cuda.Stream()
+    try:
+        A.load(wa.resident)
+        Bs.load(wb.resident)
+        ids = sorted(wa.distinct_adapters())
+        a0, a1 = ids[0], ids[1]
+        slot0, slot1 = B.lora_slot_of(A.ctx, a0), B.lora_slot_of(A.ctx, a1)
+        torch.cuda.synchronize()
+        outs = []
+        for step in range(6):
+            # swap the two adapters' slots before every step: tokens of a0 must still get a0's weights
+            tgt = (slot1, slot0) if step % 2 == 0 else (slot0, slot1)
+            A.load([a0, a1], in_use=ids, slots=list(tgt), stream=copy)
+            A.step()
+            outs.append([o.clone() for o in A.out])
+            Bs.step()                                  # long work of another context behind A's step
+        torch.cuda.synchronize()
+        for step, out in enumerate(outs):
+            for p in range(len(wa.proj)):
+                y_ref = oracle.project(wa.x[p], wa.W[p], wa.token_ids, oracle.adapters_of(wa, p), bias=wa.bias_of(p))
+                assert rel_err(bf16_tensor_to_bits(out[p]), y_ref) <= TOL, (step, p)
+        assert B.lora_poll_device_flags(A.ctx) == (B.LORA_OK, 0)
+    finally:
+        A.close()
+        Bs.close()
