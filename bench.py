@@ -132,7 +132,7 @@ def calibrate_stream():
                       "frac_of_peak": best / HBM_PEAK_GBS}))
 
 
-def calibrate_gemm():
+def calibrate_gemm(sample_clocks: bool = True):
     """Context for the MFMA fraction of the prefill GEMM: the library's backbone GEMM (no adapter rows) and the
     vendor library's bf16 GEMM (torch.matmul) on one prefill-sized problem, first on normally distributed data, then
     on zeros, with the shader clock that rocm-smi shows under each.  Operands of zeros toggle almost no bits in
@@ -162,13 +162,15 @@ def calibrate_gemm():
             fn()
         e1.record()
         torch.cuda.synchronize()
-        with ClockSampler() as cs:                           # keep the load up while the clocks are read
-            t_end = time.time() + 1.5
-            while time.time() < t_end:
-                for _ in range(iters):
-                    fn()
-                torch.cuda.synchronize()
-        clocks = cs.summary() or {}
+        clocks = {}
+        if sample_clocks:                                    # (starts rocm-smi as a child: not under a counter run)
+            with ClockSampler() as cs:                       # keep the load up while the clocks are read
+                t_end = time.time() + 1.5
+                while time.time() < t_end:
+                    for _ in range(iters):
+                        fn()
+                    torch.cuda.synchronize()
+            clocks = cs.summary() or {}
         us = e0.elapsed_time(e1) / iters * 1e3
         return {"us": us, "tflops": flops / us / 1e6, "frac_of_peak": flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
                 "sclk_mhz": [clocks.get("sclk_mhz_min"), clocks.get("sclk_mhz_max")]}
@@ -306,7 +308,7 @@ def main():
         calibrate_stream()
         return
     if args.calibrate_gemm:
-        calibrate_gemm()
+        calibrate_gemm(sample_clocks=not args.no_clocks)
         return
     if args.calibrate_mfma:
         calibrate_mfma()
