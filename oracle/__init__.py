@@ -282,3 +282,105 @@ class SlotTable:
             placed_now.add(s)
             out.append((s, True))
         return out
+
+
+# ---------------------------------------------------------------------------
+# the same slot table over a pool of pages (unified paging of the adapter region)
+# ---------------------------------------------------------------------------
+class PagedSlotTable(SlotTable):
+    """The slot table with the adapters' weights in a pool of ``n_pages`` pages instead of one region of the
+    largest rank per slot (paper Sec. 2.2: memory management that pages adapters of different sizes into one
+    pool, against the uniform per-adapter footprint the paper's setting uses).  One page holds 8 rank units; an
+    adapter of rank r occupies r / 8 consecutive pages (none for rank 0), found first-fit: the lowest first page
+    whose run is free.
+
+    A request that needs a copy first gets its slot by the rules of ``SlotTable`` (whoever sat there leaves and
+    frees its pages, as does the adapter's own old slot when it moves).  While the pool then has no free run of
+    the needed length, further adapters leave, chosen like a slot victim: not in ``in_use``, not placed by this
+    call, smallest last_used, ties to the lowest slot; their slots become empty.  No such adapter left ->
+    SlotsExhausted, and the whole call is undone.  ``first_page[s]``: first page of slot s, -1 for an empty slot
+    or a rank-0 adapter."""
+
+    PAGE_RANKS = 8
+
+    def __init__(self, n_slots: int, n_pages: int):
+        super().__init__(n_slots)
+        self.n_pages = n_pages
+        self.first_page = [-1] * n_slots
+        self.owner = [-1] * n_pages          # slot that holds each page, -1 = free
+
+    def load(self, requests, in_use=()):
+        saved = (list(self.adapter), list(self.rank), list(self.last_used), self.tick, list(self.first_page),
+                 list(self.owner))
+        try:
+            return self._load(requests, in_use)
+        except SlotsExhausted:
+            self.adapter, self.rank, self.last_used, self.tick, self.first_page, self.owner = saved
+            raise
+
+    def _release(self, s: int) -> None:
+        self.adapter[s] = -1
+        self.rank[s] = 0
+        self.first_page[s] = -1
+        self.owner = [-1 if o == s else o for o in self.owner]
+
+    def _first_fit(self, k: int) -> int:
+        for p in range(self.n_pages - k + 1):
+            if all(o < 0 for o in self.owner[p:p + k]):
+                return p
+        return -1
+
+    def _load(self, requests, in_use):
+        self.tick += 1
+        protected = set(int(a) for a in in_use)
+        for a in protected:
+            s = self.slot_of(a)
+            if s >= 0:
+                self.last_used[s] = self.tick
+        placed_now = set()
+        out = []
+        for (aid, rank, want) in requests:
+            cur = self.slot_of(aid)
+            if cur >= 0 and (want < 0 or want == cur):
+                self.last_used[cur] = self.tick
+                placed_now.add(cur)
+                out.append((cur, False))
+                continue
+            if want >= 0:
+                s = want
+            else:
+                empties = [k for k in range(self.n_slots) if self.adapter[k] < 0]
+                if empties:
+                    s = empties[0]
+                else:
+                    cands = [k for k in range(self.n_slots)
+                             if self.adapter[k] not in protected and k not in placed_now]
+                    if not cands:
+                        raise SlotsExhausted()
+                    s = min(cands, key=lambda k: (self.last_used[k], k))
+            if cur >= 0:
+                self._release(cur)
+            if self.adapter[s] >= 0:
+                self._release(s)
+            placed_now.add(s)
+            need = rank // self.PAGE_RANKS
+            first = -1
+            if need > 0:
+                if need > self.n_pages:
+                    raise SlotsExhausted()
+                first = self._first_fit(need)
+                while first < 0:
+                    cands = [k for k in range(self.n_slots) if self.adapter[k] >= 0
+                             and self.adapter[k] not in protected and k not in placed_now]
+                    if not cands:
+                        raise SlotsExhausted()
+                    self._release(min(cands, key=lambda k: (self.last_used[k], k)))
+                    first = self._first_fit(need)
+                for p in range(first, first + need):
+                    self.owner[p] = s
+            self.adapter[s] = aid
+            self.rank[s] = rank
+            self.first_page[s] = first
+            self.last_used[s] = self.tick
+            out.append((s, True))
+        return out
