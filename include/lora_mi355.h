@@ -101,6 +101,11 @@ typedef struct {
     uint32_t flags;         /* LORA_CREATE_* */
     int32_t n_layers;       /* decoder layers that share the slot table, 1 .. 256 (0 is read as 1): a slot then
                                holds one adapter's matrices for every layer, see lora_model_forward_group */
+    int32_t n_pages;        /* 0: every slot owns room for an adapter of max_rank (the uniform footprint of the paper's
+                               setting, Sec. 2.2 / 8.1).  > 0: the adapters share a pool of n_pages pages of 8 rank
+                               units each (unified paging, Sec. 2.2): an adapter of rank r takes r / 8 consecutive
+                               pages wherever a run is free, and a slot is an entry of a table that says where.
+                               At least max_rank / 8; the slab is sized for the pool instead of n_slots regions. */
 } lora_config;
 
 /* One adapter to make resident.  A[p] / B[p]: pinned host, row-major bf16, A[p] is
@@ -268,6 +273,8 @@ lora_status lora_poll_device_flags(lora_ctx *ctx, uint32_t *flags, void *stream)
 /* Slot-table queries (host state, no device access). */
 int32_t lora_slot_of(const lora_ctx *ctx, int32_t adapter_id);      /* slot or -1 */
 int32_t lora_slot_adapter(const lora_ctx *ctx, int32_t slot);       /* adapter id or -1 */
+int32_t lora_slot_first_page(const lora_ctx *ctx, int32_t slot);    /* n_pages > 0: first page of the slot's adapter;
+                                                                        -1: empty slot, rank 0, or a context without pages */
 
 /* Kernel-variant selection for experiments and autotuning; value 0 is always the default variant and
  * unknown values fall back to it.  Every variant computes the same result to the same tolerance. */

@@ -65,7 +65,7 @@ LORA_CREATE_HOST_ONLY = 1
 EXPORTS = [
     "lora_slab_bytes", "lora_create", "lora_destroy", "lora_slots_load", "lora_bucket", "lora_layer_forward",
     "lora_layer_forward_group",
-    "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_last_launches",
+    "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_slot_first_page", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
     "lora_last_hip_error", "lora_calibrate_stream", "lora_calibrate_mfma", "lora_layer_forward_static", "lora_static_scratch_bytes", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
 ]
@@ -94,7 +94,7 @@ class lora_config(ctypes.Structure):
                 ("proj", ctypes.POINTER(lora_proj_shape)), ("max_tokens", ctypes.c_int32),
                 ("max_adapter_id", ctypes.c_int32), ("slab", ctypes.c_void_p), ("slab_bytes", ctypes.c_size_t),
                 ("path", ctypes.c_int32), ("split_k", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("n_layers", ctypes.c_int32)]
+                ("n_layers", ctypes.c_int32), ("n_pages", ctypes.c_int32)]
 
 
 class lora_adapter_desc(ctypes.Structure):
@@ -140,6 +140,8 @@ _lib.lora_slot_of.restype = ctypes.c_int32
 _lib.lora_slot_of.argtypes = [_P, ctypes.c_int32]
 _lib.lora_slot_adapter.restype = ctypes.c_int32
 _lib.lora_slot_adapter.argtypes = [_P, ctypes.c_int32]
+_lib.lora_slot_first_page.restype = ctypes.c_int32
+_lib.lora_slot_first_page.argtypes = [_P, ctypes.c_int32]
 _lib.lora_last_launches.restype = ctypes.c_int32
 _lib.lora_last_launches.argtypes = [_P, ctypes.POINTER(ctypes.c_char_p), ctypes.c_int32]
 _lib.lora_profile_enable.restype = ctypes.c_int
@@ -180,11 +182,11 @@ def lora_last_hip_error() -> str:
 
 def make_config(proj: Sequence[Tuple[int, int]], n_slots: int, max_rank: int, max_tokens: int,
                 max_adapter_id: int, slab_ptr: int = 0, slab_bytes: int = 0, path: int = LORA_PATH_AUTO,
-                split_k: int = 0, flags: int = 0, n_layers: int = 1):
+                split_k: int = 0, flags: int = 0, n_layers: int = 1, n_pages: int = 0):
     arr = (lora_proj_shape * len(proj))(*[lora_proj_shape(int(a), int(b)) for a, b in proj])
     cfg = lora_config(int(n_slots), int(max_rank), len(proj), arr, int(max_tokens), int(max_adapter_id),
                       ctypes.c_void_p(slab_ptr or None), int(slab_bytes), int(path), int(split_k), int(flags),
-                      int(n_layers))
+                      int(n_layers), int(n_pages))
     cfg._keep = arr
     return cfg
 
@@ -347,6 +349,10 @@ def lora_slot_of(ctx: int, adapter_id: int) -> int:
 
 def lora_slot_adapter(ctx: int, slot: int) -> int:
     return int(_lib.lora_slot_adapter(_P(ctx), int(slot)))
+
+
+def lora_slot_first_page(ctx: int, slot: int) -> int:
+    return int(_lib.lora_slot_first_page(_P(ctx), int(slot)))
 
 
 def lora_set_bias(ctx: int, proj: int, d_bias: int, layer: int = 0) -> None:

@@ -91,6 +91,7 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     __shared__ int s_pstart[kFastPieces + 1];
     __shared__ int s_pslot[kFastPieces];
     __shared__ int s_rank[kMaxKeys];     // fast path: slot tables
+    __shared__ int s_loc[kMaxKeys];
     __shared__ float s_scale[kMaxKeys];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int T = a.T;
@@ -103,6 +104,7 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     if (fast) {
         for (int k = tid; k < a.n_slots; k += kBT) {
             s_rank[k] = a.slot_rank[k];
+            s_loc[k] = a.slot_loc[k];
             s_scale[k] = a.slot_scale[k];
         }
     }
@@ -212,9 +214,11 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
         const int s = rs[m];
         if (fast) {
             a.row_rank[m] = s >= 0 ? s_rank[s] : 0;
+            a.row_loc[m] = s >= 0 ? s_loc[s] : -1;
             a.row_scale[m] = s >= 0 ? s_scale[s] : 0.f;
         } else {
             a.row_rank[m] = s >= 0 ? a.slot_rank[s] : 0;
+            a.row_loc[m] = s >= 0 ? a.slot_loc[s] : -1;
             a.row_scale[m] = s >= 0 ? a.slot_scale[s] : 0.f;
         }
     }
@@ -227,22 +231,24 @@ __global__ __launch_bounds__(kBT) void bucket_kernel(BucketArgs a)
     // one 16-byte record per piece for the shrink work loop
     const int n_pieces = *a.n_pieces;
     for (int p = tid; p < n_pieces; p += kBT) {
-        int begin, end, s, r;
+        int begin, end, s, r, loc;
         if (fast) {
             begin = s_pstart[p];
             end = s_pstart[p + 1];
             s = s_pslot[p];
             r = s >= 0 ? s_rank[s] : 0;
+            loc = s >= 0 ? s_loc[s] : -1;
         } else {
             begin = a.piece_start[p];
             end = a.piece_start[p + 1];
             s = a.piece_slot[p];
             r = s >= 0 ? a.slot_rank[s] : 0;
+            loc = s >= 0 ? a.slot_loc[s] : -1;
         }
         int4 rec;
         rec.x = begin;
         rec.y = end - begin;
-        rec.z = s;
+        rec.z = loc;
         rec.w = r;
         reinterpret_cast<int4*>(a.piece_info)[p] = rec;
     }
@@ -286,6 +292,7 @@ __global__ __launch_bounds__(kBT) void bucket_runs_rows_kernel(BucketArgs a)
         a.perm[t] = t;
         a.row_slot[t] = s;
         a.row_rank[t] = s >= 0 ? a.slot_rank[s] : 0;
+        a.row_loc[t] = s >= 0 ? a.slot_loc[s] : -1;
         a.row_scale[t] = s >= 0 ? a.slot_scale[s] : 0.f;
         const int prev = tid > 0 ? s_key[tid - 1] : first_prev;
         seg_head = (t == 0) || prev != key;
@@ -345,7 +352,7 @@ __global__ __launch_bounds__(kBT) void bucket_runs_number_kernel(BucketArgs a)
         int4 rec;
         rec.x = t;
         rec.y = s_pstart[piece_ex + 1] - t;
-        rec.z = s;
+        rec.z = s >= 0 ? a.slot_loc[s] : -1;
         rec.w = s >= 0 ? a.slot_rank[s] : 0;
         reinterpret_cast<int4*>(a.piece_info)[p] = rec;
     }
@@ -357,13 +364,14 @@ __global__ __launch_bounds__(kBT) void bucket_runs_number_kernel(BucketArgs a)
     }
 }
 
-__global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot)
+__global__ void meta_update_kernel(MetaUpdates u, int32_t* slot_rank, float* slot_scale, int32_t* slot_loc, int32_t* id2slot)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     for (int i = 0; i < u.n; ++i) {
         if (u.evicted[i] >= 0) id2slot[u.evicted[i]] = -1;
         slot_rank[u.slot[i]] = u.rank[i];
         slot_scale[u.slot[i]] = u.scale[i];
+        slot_loc[u.slot[i]] = u.loc[i];
         if (u.adapter[i] >= 0) id2slot[u.adapter[i]] = u.slot[i];
     }
 }
@@ -410,10 +418,10 @@ hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot,
-                              hipStream_t stream)
+hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* slot_loc,
+                              int32_t* id2slot, hipStream_t stream)
 {
-    hipLaunchKernelGGL(meta_update_kernel, dim3(1), dim3(kWave), 0, stream, u, slot_rank, slot_scale, id2slot);
+    hipLaunchKernelGGL(meta_update_kernel, dim3(1), dim3(kWave), 0, stream, u, slot_rank, slot_scale, slot_loc, id2slot);
     return hipGetLastError();
 }
 

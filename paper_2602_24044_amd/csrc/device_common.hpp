@@ -149,8 +149,8 @@ __device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_piec
     const int kc = item - pk * a.n_kc;
     const int si = pk / n_pieces;                       // slice (projection of a packed group)
     const Slice sl = pick_slice(a.g, si);
-    const int m_begin = rec.x, nrows = rec.y, slot = rec.z, r = rec.w;
-    if (slot < 0 || r <= 0) return;
+    const int m_begin = rec.x, nrows = rec.y, loc = rec.z, r = rec.w;
+    if (loc < 0 || r <= 0) return;
     const int c_begin = kc * a.kc_len;
     int c_end = c_begin + a.kc_len;
     if (c_end > K) c_end = K;
@@ -161,7 +161,7 @@ __device__ inline void shrink_one_item(const ShrinkArgs& a, int item, int n_piec
     if (k_end > c_end) k_end = c_end;
 
     const uint16_t* xrow = sl.x + (size_t)tok * K + h * 32;
-    const uint16_t* As = a.dv.slots + (size_t)slot * a.dv.slot_stride + (size_t)r * sl.a_unit;
+    const uint16_t* As = a.dv.slots + (size_t)loc * kLocUnit + (size_t)r * sl.a_unit;
     const bool a0_ok = i < r, a1_ok = (32 + i) < r;
     const uint16_t* arow0 = As + (size_t)(a0_ok ? i : 0) * K + h * 32;
     const uint16_t* arow1 = As + (size_t)(a1_ok ? 32 + i : 0) * K + h * 32;
@@ -343,7 +343,8 @@ __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 // a branch, or a number of loads that depends on the adapter, would leave the compiler unable to tell an item's
 // own loads from the younger ones, and every item would wait for all loads in flight.  Lanes whose column or
 // rank range does not exist read an existing place (row N - 1, rank offset 0); what they load is replaced by zeros.
-// slot / rank: the lane's row of each window (slot -1 or rank 0: backbone only).  sV: the windows' scaled
+// slot / rank: the lane's row of each window; `slot` holds the location of the row's adapter in the slot region
+// (DeviceView::row_loc: one value per resident adapter, so it also tells adapters apart; -1 or rank 0: backbone only).  sV: the windows' scaled
 // shrink results in LDS, window mb at sV + mb * kPieceRows * kVStageStride.
 // ---------------------------------------------------------------------------------------------------
 template <int MB, int NB, int D>
@@ -391,7 +392,7 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
         for (int nb = 0; nb < NB; ++nb) {
             int n = n_first + nb * 32 + i;
             if (n > N - 1) n = N - 1;
-            const uint16_t* Bs = dv.slots + (size_t)q.s * dv.slot_stride + ((size_t)q.r * b_unit + (size_t)n * q.r);
+            const uint16_t* Bs = dv.slots + (size_t)q.s * kLocUnit + ((size_t)q.r * b_unit + (size_t)n * q.r);
             fb.f[nb] = load16(Bs + kc);
         }
     };

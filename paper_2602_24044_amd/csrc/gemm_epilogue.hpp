@@ -142,7 +142,7 @@ __device__ __forceinline__ void prefetch_rows(TilePrefetch<MB>& pf, const GemmAr
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_first + mb * 32 + i;
         const int mc = m < a.m_end ? m : last;
-        const int s = a.dv.row_slot[mc], r = a.dv.row_rank[mc];
+        const int s = a.dv.row_loc[mc], r = a.dv.row_rank[mc];
         pf.slot[mb] = m < a.m_end ? s : -1;
         pf.rank[mb] = m < a.m_end ? r : 0;
 #pragma unroll
@@ -259,7 +259,7 @@ __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArg
         for (int mb = 0; mb < MB; ++mb) {
             const int m = m_first + mb * 32 + i;
             const bool ok = m < T;
-            slot[mb] = ok ? a.dv.row_slot[m] : -1;
+            slot[mb] = ok ? a.dv.row_loc[m] : -1;
             rank[mb] = ok ? a.dv.row_rank[m] : 0;
         }
         uint8_t* mine = reinterpret_cast<uint8_t*>(ring) + wave * epilogue_bytes_per_wave<NB>();

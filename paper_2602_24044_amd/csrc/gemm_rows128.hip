@@ -24,7 +24,6 @@
 namespace lora {
 namespace {
 
-constexpr bool kWarmB = false;
 constexpr int kTK64 = 64;    // K extent of one LDS tile (bf16 elements): 128-byte rows
 constexpr int kRowB = 128;
 
@@ -44,34 +43,6 @@ __device__ inline void copy16_to_lds(const void* gptr, uint32_t lds_addr)
 __device__ inline void poll4_to_lds(const void* gptr, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off sc1" ::"v"(gptr), "s"(lds_addr) : "memory");
-}
-
-// Touches the B rows the wave's expand will read (columns n_first .. n_first + wtn of every adapter its rows
-// use: one contiguous run of wtn * rank bf16 per adapter) so that they wait in L2 when the epilogue asks for them;
-// the loads land in a piece of LDS nobody reads.  Ordered like every other copy of the wave (vmcnt).
-template <int MB>
-__device__ __forceinline__ void warm_b_rows(const TilePrefetch<MB>& pf, const GemmArgs& a, const Slice& sl, int n_first,
-                                            int wtn, uint32_t dump_addr)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    int ncols = sl.N - n_first;
-    if (ncols > wtn) ncols = wtn;
-    if (ncols <= 0) return;                                       // uniform over the wave
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        unsigned long long todo = __ballot(pf.slot[mb] >= 0 && pf.rank[mb] > 0);
-        while (todo) {                                            // uniform over the wave
-            const int leader = __ffsll((long long)todo) - 1;
-            const int sl_id = __shfl(pf.slot[mb], leader, kWave);
-            const int r = __shfl(pf.rank[mb], leader, kWave);
-            todo &= ~__ballot(pf.slot[mb] == sl_id);
-            const uint8_t* run = reinterpret_cast<const uint8_t*>(a.dv.slots + (size_t)sl_id * a.dv.slot_stride +
-                                                                  ((size_t)r * sl.b_unit + (size_t)n_first * r));
-            const int bytes = ncols * r * 2;
-            for (int o = lane * 16; o - lane * 16 < bytes; o += 1024)
-                if (o < bytes) copy16_to_lds(run + o, dump_addr);
-        }
-    }
 }
 
 template <int N>
@@ -95,11 +66,10 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     static_assert(NS * STAGE_B <= 160 * 1024, "LDS");
 
     __shared__ __attribute__((aligned(1024))) uint8_t ring[NS * STAGE_B];
-    // fused path, shrink inside the launch: the shrink workgroups' counter as polled during the main loop, the
-    // verdict for the whole workgroup, and the landing place of the warm-up loads
+    // fused path, shrink inside the launch: the shrink workgroups' counter as polled during the main loop and the
+    // verdict for the whole workgroup
     __shared__ uint32_t s_poll[kWave];
     __shared__ uint32_t s_early;
-    __shared__ __attribute__((aligned(1024))) uint8_t s_dump[1024];
     // split path: the workgroups past the tile grid only do shrink items
     const int extra = (int)gridDim.x - a.main_grid;          // shrink-only workgroups of this launch
     if (!FUSED && sa.on && (int)blockIdx.x >= a.main_grid) {
@@ -238,7 +208,6 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     bool early = false;
     const bool poll_on = PRE && front > 0 && nk >= 4;
     const uint32_t poll_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)s_poll;
-    const uint32_t dump_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)s_dump;
     // Past the wait for the shrink workgroups every tile workgroup takes a ticket; the one with the last ticket
     // sets the two counters back to zero for the next launch (at the end of the kernel: nobody of this launch
     // looks at them any more).  The ticket is requested here and read only then, so that nobody waits for it.
@@ -281,11 +250,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
                 }
                 if (t == nk - 1) {
                     early = s_early != 0u;
-                    if (kWarmB) warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
                     if (early) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);
                 }
-            } else if (kWarmB && front == 0 && t == nk - 1) {
-                warm_b_rows(pre, a, sl, n0 + wn * WTN, WTN, __builtin_amdgcn_readfirstlane(dump_addr));
             }
         }
     };

@@ -58,7 +58,8 @@ constexpr int kMarkedCallsPerLoad = 64;        // calls after a load that still 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t slot_stride_elems = 0;          // bf16 elements per slot
+    size_t slot_stride_elems = 0;          // bf16 elements per slot (uniform slots)
+    size_t page_stride_elems = 0;          // bf16 elements per page of kPageRanks rank units (paged slots)
     // An adapter sits in its slot packed at its own rank r: layer after layer, per layer the A [r, d_in] and
     // B [d_out, r] of every projection back to back.  a_unit / b_unit [n_layers * n_proj]: elements in front of
     // that matrix per unit of rank (its offset inside the slot is r times that), so one adapter is one run of
@@ -66,7 +67,7 @@ struct Layout {
     std::vector<size_t> a_unit, b_unit;
     size_t unit_total = 0;
     size_t off_slots = 0, off_slot_rank = 0, off_slot_scale = 0, off_id2slot = 0, off_header = 0;
-    size_t off_row_rank = 0, off_row_scale = 0;
+    size_t off_row_rank = 0, off_row_scale = 0, off_row_loc = 0, off_slot_loc = 0;
     size_t off_perm = 0, off_row_slot = 0, off_seg_start = 0, off_seg_slot = 0, off_piece_start = 0,
            off_piece_slot = 0, off_piece_info = 0, off_tok_key = 0, off_vpart = 0, off_part = 0;
     size_t vpart_elems = 0, part_elems = 0;
@@ -132,6 +133,16 @@ bool valid_config(const lora_config* c)
     if (c->max_tokens < 1 || c->max_adapter_id < 0) return false;
     if (c->path < LORA_PATH_AUTO || c->path > LORA_PATH_SPLITK) return false;
     if (c->split_k < 0 || c->split_k > 16) return false;
+    if (c->n_pages < 0 || (c->n_pages > 0 && c->n_pages < c->max_rank / kPageRanks)) return false;
+    {
+        // an adapter's place in the slot region is a 32-bit count of 128-byte units
+        uint64_t unit = 0;
+        for (int p = 0; p < c->n_proj; ++p) unit += (uint64_t)std::max(0, c->proj[p].d_in) + (uint64_t)std::max(0, c->proj[p].d_out);
+        unit *= (uint64_t)std::max(1, c->n_layers);
+        const uint64_t region = c->n_pages > 0 ? (unit * kPageRanks + kLocUnit) * (uint64_t)c->n_pages
+                                               : (unit * (uint64_t)c->max_rank + 2 * kLocUnit) * (uint64_t)c->n_slots;
+        if (region / kLocUnit >= (1ull << 31)) return false;
+    }
     for (int p = 0; p < c->n_proj; ++p) {
         if (c->proj[p].d_in < 64 || c->proj[p].d_in % 64) return false;
         if (c->proj[p].d_out < 8 || c->proj[p].d_out % 8) return false;
@@ -161,11 +172,14 @@ Layout make_layout(const lora_config* c, int n_cus)
         }
     L.unit_total = e;
     L.slot_stride_elems = align_up(e * (size_t)c->max_rank * 2, kAlign) / 2;
+    L.page_stride_elems = align_up(e * (size_t)kPageRanks * 2, (size_t)kLocUnit * 2) / 2;
     const size_t Tm = (size_t)c->max_tokens;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, kAlign); return at; };
-    L.off_slots = take(L.slot_stride_elems * 2 * (size_t)c->n_slots);
+    L.off_slots = c->n_pages > 0 ? take(L.page_stride_elems * 2 * (size_t)c->n_pages)
+                                 : take(L.slot_stride_elems * 2 * (size_t)c->n_slots);
     L.off_slot_rank = take(4 * (size_t)c->n_slots);
+    L.off_slot_loc = take(4 * (size_t)c->n_slots);
     L.off_slot_scale = take(4 * (size_t)c->n_slots);
     L.off_id2slot = take(4 * ((size_t)c->max_adapter_id + 1));
     L.off_header = take(256);
@@ -173,6 +187,7 @@ Layout make_layout(const lora_config* c, int n_cus)
     L.off_row_slot = take(4 * Tm);
     L.off_row_rank = take(4 * Tm);
     L.off_row_scale = take(4 * Tm);
+    L.off_row_loc = take(4 * Tm);
     L.off_seg_start = take(4 * (Tm + 1));
     L.off_seg_slot = take(4 * Tm);
     const size_t max_pieces = Tm + Tm / kPieceRows + 2;
@@ -217,6 +232,8 @@ struct lora_ctx {
     std::vector<float> slot_scale_h;
     std::vector<uint64_t> slot_last_used;
     std::vector<int32_t> id2slot_h;
+    // paged slots (cfg.n_pages > 0): first page of every slot's adapter (-1: none) and the slot that holds each page
+    std::vector<int32_t> slot_first_page, page_owner;
     uint64_t tick = 0;
     int n_resident = 0;
 
@@ -269,6 +286,13 @@ struct lora_ctx {
 
     template <typename Tp> Tp* dev(size_t off) const { return reinterpret_cast<Tp*>(base + off); }
     int32_t* d_slot_rank() const { return dev<int32_t>(L.off_slot_rank); }
+    int32_t* d_slot_loc() const { return dev<int32_t>(L.off_slot_loc); }
+    // where the adapter of a slot starts, in kLocUnit-element units from the start of the slot region
+    int32_t loc_of(int slot, int first_page) const
+    {
+        if (cfg.n_pages > 0) return first_page < 0 ? -1 : (int32_t)((size_t)first_page * L.page_stride_elems / kLocUnit);
+        return (int32_t)((size_t)slot * L.slot_stride_elems / kLocUnit);
+    }
     float* d_slot_scale() const { return dev<float>(L.off_slot_scale); }
     int32_t* d_id2slot() const { return dev<int32_t>(L.off_id2slot); }
     uint32_t* d_flags() const { return dev<uint32_t>(L.off_header); }
@@ -279,11 +303,11 @@ struct lora_ctx {
     {
         DeviceView v;
         v.slots = dev<uint16_t>(L.off_slots);
-        v.slot_stride = L.slot_stride_elems;
         v.slot_rank = d_slot_rank();
         v.slot_scale = d_slot_scale();
         v.perm = dev<int32_t>(L.off_perm);
         v.row_slot = dev<int32_t>(L.off_row_slot);
+        v.row_loc = dev<int32_t>(L.off_row_loc);
         v.row_rank = dev<int32_t>(L.off_row_rank);
         v.row_scale = dev<float>(L.off_row_scale);
         v.piece_start = dev<int32_t>(L.off_piece_start);
@@ -530,6 +554,8 @@ lora_status lora_create(const lora_config* cfg, lora_ctx** out)
     c->slot_scale_h.assign(cfg->n_slots, 0.f);
     c->slot_last_used.assign(cfg->n_slots, 0);
     c->id2slot_h.assign((size_t)cfg->max_adapter_id + 1, -1);
+    c->slot_first_page.assign(cfg->n_slots, -1);
+    c->page_owner.assign((size_t)std::max(0, cfg->n_pages), -1);
 
     if (!c->host_only) {
         if (!cfg->slab || (reinterpret_cast<uintptr_t>(cfg->slab) % kAlign) != 0) {
@@ -598,6 +624,12 @@ int32_t lora_slot_adapter(const lora_ctx* c, int32_t slot)
     return c->slot_adapter[slot];
 }
 
+int32_t lora_slot_first_page(const lora_ctx* c, int32_t slot)
+{
+    if (!c || slot < 0 || slot >= c->cfg.n_slots || c->cfg.n_pages <= 0) return -1;
+    return c->slot_first_page[slot];
+}
+
 lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, const int32_t* in_use,
                             int32_t n_in_use, void* copy_stream_v)
 {
@@ -626,6 +658,9 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     std::vector<int32_t> adapter = c->slot_adapter, rank = c->slot_rank_h, id2slot = c->id2slot_h;
     std::vector<float> scale = c->slot_scale_h;
     std::vector<uint64_t> last_used = c->slot_last_used;
+    std::vector<int32_t> first_page = c->slot_first_page, owner = c->page_owner;
+    const bool paged = c->cfg.n_pages > 0;
+    const int n_pages = c->cfg.n_pages;
     const uint64_t tick = c->tick + 1;
     std::vector<char> is_protected((size_t)max_id + 1, 0), placed_now(n_slots, 0);
     for (int i = 0; i < n_in_use; ++i) {
@@ -633,7 +668,22 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
         const int s = id2slot[in_use[i]];
         if (s >= 0) last_used[s] = tick;
     }
-    struct Step { int slot, adapter, evicted, rank; float scale; bool copied; };
+    struct Step { int slot, adapter, evicted, rank; float scale; bool copied; int first_page; };
+    // paged slots: the pages of a slot go back to the pool; the lowest first page of a free run of k pages
+    auto free_pages_of = [&](int slot) {
+        if (!paged) return;
+        first_page[slot] = -1;
+        for (int p = 0; p < n_pages; ++p)
+            if (owner[p] == slot) owner[p] = -1;
+    };
+    auto first_fit = [&](int k) {
+        int run = 0;
+        for (int p = 0; p < n_pages; ++p) {
+            run = owner[p] < 0 ? run + 1 : 0;
+            if (run == k) return p - k + 1;
+        }
+        return -1;
+    };
     std::vector<Step> steps;
     steps.reserve(n);
     std::vector<int> out_slot(n), out_copied(n);
@@ -664,21 +714,54 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             }
         }
         if (cur >= 0) {  // the adapter moves to an explicit other slot: its old slot becomes empty
-            steps.push_back({cur, -1, d.adapter_id, 0, 0.f, false});
+            steps.push_back({cur, -1, d.adapter_id, 0, 0.f, false, -1});
             adapter[cur] = -1;
             rank[cur] = 0;
             scale[cur] = 0.f;
             id2slot[d.adapter_id] = -1;
+            free_pages_of(cur);
         }
         const int evicted = adapter[s];
-        if (evicted >= 0) id2slot[evicted] = -1;
+        if (evicted >= 0) {
+            id2slot[evicted] = -1;
+            free_pages_of(s);
+        }
+        placed_now[s] = 1;
+        int first = -1;
+        if (paged && d.rank > 0) {
+            // a run of rank / 8 pages, first fit; while there is none, further adapters leave in the order of slot
+            // victims (not in use, not placed by this call, least recently used, lowest slot)
+            const int need = d.rank / kPageRanks;
+            first = first_fit(need);
+            while (first < 0) {
+                int v = -1;
+                uint64_t best = 0;
+                for (int k = 0; k < n_slots; ++k) {
+                    if (adapter[k] < 0 || placed_now[k] || is_protected[adapter[k]]) continue;
+                    if (v < 0 || last_used[k] < best) {
+                        v = k;
+                        best = last_used[k];
+                    }
+                }
+                if (v < 0) return LORA_ERR_SLOTS_EXHAUSTED;
+                steps.push_back({v, -1, adapter[v], 0, 0.f, false, -1});
+                id2slot[adapter[v]] = -1;
+                adapter[v] = -1;
+                rank[v] = 0;
+                scale[v] = 0.f;
+                free_pages_of(v);
+                first = first_fit(need);
+            }
+            for (int p = first; p < first + need; ++p) owner[p] = s;
+            first_page[s] = first;
+        }
         adapter[s] = d.adapter_id;
         rank[s] = d.rank;
         scale[s] = d.scale;
         id2slot[d.adapter_id] = s;
         last_used[s] = tick;
         placed_now[s] = 1;
-        steps.push_back({s, d.adapter_id, evicted, d.rank, d.scale, true});
+        steps.push_back({s, d.adapter_id, evicted, d.rank, d.scale, true, first});
         out_slot[i] = s;
         out_copied[i] = 1;
     }
@@ -689,6 +772,8 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
     c->slot_scale_h.swap(scale);
     c->slot_last_used.swap(last_used);
     c->id2slot_h.swap(id2slot);
+    c->slot_first_page.swap(first_page);
+    c->page_owner.swap(owner);
     c->tick = tick;
     c->n_resident = 0;
     for (int k = 0; k < n_slots; ++k) c->n_resident += c->slot_adapter[k] >= 0;
@@ -717,8 +802,9 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
             u.evicted[i] = st.evicted;
             u.rank[i] = st.rank;
             u.scale[i] = st.scale;
+            u.loc[i] = st.adapter >= 0 ? c->loc_of(st.slot, st.first_page) : -1;
         }
-        if (HIP_FAIL(launch_meta_update(u, c->d_slot_rank(), c->d_slot_scale(), c->d_id2slot(), cs)))
+        if (HIP_FAIL(launch_meta_update(u, c->d_slot_rank(), c->d_slot_scale(), c->d_slot_loc(), c->d_id2slot(), cs)))
             return LORA_ERR_HIP;
     }
     if (HIP_FAIL(hipEventRecord(c->ev_meta, cs))) return LORA_ERR_HIP;
@@ -745,8 +831,11 @@ lora_status lora_slots_load(lora_ctx* c, int32_t n, lora_adapter_desc* descs, co
         std::vector<Run>& runs = unit_runs[u];
         for (int i = 0; i < n; ++i) {
             if (!out_copied[i] || descs[i].rank <= 0) continue;
+            // a later request of the same call may have taken the slot (an explicit slot overrides everything):
+            // the adapter is then not resident and its place may belong to somebody else
+            if (c->slot_adapter[out_slot[i]] != descs[i].adapter_id) continue;
             const size_t r = descs[i].rank;
-            char* slot_base = slots + (size_t)out_slot[i] * c->L.slot_stride_elems * 2;
+            char* slot_base = slots + (size_t)c->loc_of(out_slot[i], c->slot_first_page[out_slot[i]]) * (kLocUnit * 2);
             const size_t first = runs.size();
             auto add = [&](const void* src, size_t dst_elems, size_t bytes) {
                 const char* sp = static_cast<const char*>(src);
@@ -826,6 +915,8 @@ lora_status lora_bucket(lora_ctx* c, const int32_t* d_token_adapter, int32_t T, 
     a.perm = c->dev<int32_t>(c->L.off_perm);
     a.row_slot = c->dev<int32_t>(c->L.off_row_slot);
     a.row_rank = c->dev<int32_t>(c->L.off_row_rank);
+    a.row_loc = c->dev<int32_t>(c->L.off_row_loc);
+    a.slot_loc = c->d_slot_loc();
     a.row_scale = c->dev<float>(c->L.off_row_scale);
     a.slot_rank = c->d_slot_rank();
     a.slot_scale = c->d_slot_scale();

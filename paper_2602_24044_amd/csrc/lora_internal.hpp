@@ -18,25 +18,27 @@ constexpr int kMetaBatch = 16;       // slot-metadata updates carried by one ker
 constexpr int kSplitMaxTokens = 1024;// largest T served by the split-K path
 constexpr int kShrinkKC = 1024;      // K extent of one shrink work item on the split-K path
 constexpr int kMaxShrinkChunks = 64;
+constexpr int kLocUnit = 64;               // bf16 elements (128 bytes) per unit of an adapter's location in the slot region
+constexpr int kPageRanks = 8;              // rank units per page of a paged slot region
 constexpr uint32_t kFlagInternal = 2u;     // LORA_FLAG_INTERNAL: a bounded wait inside a kernel expired
 constexpr int kShrinkWaitSpins = 400000;  // bounded wait of the tile workgroups for the launch's shrink workgroups (~1 us each)
 
 // Device-side view of a context: everything the kernels need, passed by value.
 struct DeviceView {
     // slot region
-    const uint16_t* slots;     // bf16 bits
-    size_t slot_stride;        // elements (bf16) between consecutive slots
+    const uint16_t* slots;     // bf16 bits: the slot region (uniform slots, or the pool of pages)
     const int32_t* slot_rank;  // [n_slots]
     const float* slot_scale;   // [n_slots]
     // segment map of the current step (grouped order)
     const int32_t* perm;       // [T]
     const int32_t* row_slot;   // [T] slot of each grouped position
+    const int32_t* row_loc;    // [T] where that slot's adapter starts: kLocUnit-element units from `slots`; -1: none
     const int32_t* row_rank;   // [T] rank of that slot's adapter (0 for backbone-only rows)
     const float* row_scale;    // [T] scale of that slot's adapter
     const int32_t* piece_start;// [n_pieces + 1]
     const int32_t* piece_slot; // [n_pieces]
     const int32_t* n_pieces;   // [1]
-    const int32_t* piece_info; // [n_pieces][4]: first grouped row, rows, slot, rank (one 16-byte load)
+    const int32_t* piece_info; // [n_pieces][4]: first grouped row, rows, location of the adapter (as row_loc), rank (one 16-byte load)
     int32_t T;
     int32_t max_rank;
 };
@@ -50,6 +52,8 @@ struct BucketArgs {
     int32_t n_slots;
     int32_t* perm;
     int32_t* row_slot;
+    int32_t* row_loc;
+    const int32_t* slot_loc;   // [n_slots] location of the adapter in each slot (see DeviceView::row_loc)
     int32_t* row_rank;
     float* row_scale;
     const int32_t* slot_rank;
@@ -71,6 +75,7 @@ struct MetaUpdates {
     int32_t adapter[kMetaBatch];   // adapter now in the slot (or -1)
     int32_t evicted[kMetaBatch];   // adapter that left the slot (or -1)
     int32_t rank[kMetaBatch];
+    int32_t loc[kMetaBatch];       // where the adapter's weights start (DeviceView::row_loc units), -1: none
     float scale[kMetaBatch];
 };
 
@@ -158,8 +163,8 @@ struct ReduceArgs {
 
 // launchers (defined next to their kernels); every launch is asynchronous on `stream`
 hipError_t launch_bucket(const BucketArgs& a, hipStream_t stream);
-hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* id2slot,
-                              hipStream_t stream);
+hipError_t launch_meta_update(const MetaUpdates& u, int32_t* slot_rank, float* slot_scale, int32_t* slot_loc,
+                              int32_t* id2slot, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int32_t value, size_t n, hipStream_t stream);
 hipError_t launch_copy_batch(const CopyBatch& b, hipStream_t stream);
 hipError_t launch_shrink(const ShrinkArgs& a, int grid, hipStream_t stream);

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     // The kernel is a chain of memory round trips; everything whose address is known at the start is requested
     // at the start, oldest first what the next dependent load needs: this lane's row (slot, rank, token), the
     // rank and scale of the row this thread stages, then the partial tiles.
-    const int my_slot[1] = {m_ok ? a.dv.row_slot[m] : -1};
+    const int my_slot[1] = {m_ok ? a.dv.row_loc[m] : -1};
     const int my_rank[1] = {m_ok ? a.dv.row_rank[m] : 0};
     const int my_tok = m_ok ? a.dv.perm[m] : 0;
     const int st_row = tid >> 3, st_seg = tid & 7;

@@ -67,7 +67,8 @@ def packed_groups(w: Workload) -> List[List[int]]:
 
 class Session:
     def __init__(self, w: Workload, path: int = B.LORA_PATH_AUTO, split_k: int = 0, device: str = "cuda:0",
-                 max_tokens: Optional[int] = None, upload_inputs: bool = True, packed_host: bool = False):
+                 max_tokens: Optional[int] = None, upload_inputs: bool = True, packed_host: bool = False,
+                 n_pages: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
         self.w = w
@@ -76,7 +77,7 @@ class Session:
         torch.cuda.set_device(self.device)
         self.max_tokens = int(max_tokens or max(w.T, 1))
         cfg = B.make_config(w.proj, w.n_slots, w.max_rank, self.max_tokens, w.max_adapter_id, path=path,
-                            split_k=split_k)
+                            split_k=split_k, n_pages=n_pages)
         nbytes = B.lora_slab_bytes(cfg)
         if nbytes == 0:
             raise B.LoraError(B.LORA_ERR_SHAPE, "lora_slab_bytes")

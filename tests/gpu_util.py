@@ -32,12 +32,13 @@ def rel_err(out_bits, y_ref):
     return float(np.max(np.abs(got - y_ref)) / (denom if denom > 0 else 1.0))
 
 
-def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=True, tol=TOL, packed=False, tuning=None):
+def run_and_check(w, path=B.LORA_PATH_AUTO, split_k=0, preload=None, check_maps=True, tol=TOL, packed=False, tuning=None,
+                  n_pages=0):
     """Loads the resident adapters, runs one step, compares every projection with the oracle.  packed: q|k|v
     and gate|up go through lora_layer_forward_group (each projection still has its own x).  tuning: {key: value}
-    passed to lora_set_tuning (kernel variants)."""
-    announce(f"{w.name} T={w.T} path={path} split_k={split_k} packed={packed} tuning={tuning} proj={w.proj}")
-    sess = Session(w, path=path, split_k=split_k)
+    passed to lora_set_tuning (kernel variants).  n_pages > 0: the adapters share a pool of that many pages."""
+    announce(f"{w.name} T={w.T} path={path} split_k={split_k} packed={packed} tuning={tuning} n_pages={n_pages} proj={w.proj}")
+    sess = Session(w, path=path, split_k=split_k, n_pages=n_pages)
     try:
         for key, value in (tuning or {}).items():
             B.lora_set_tuning(sess.ctx, key, value)

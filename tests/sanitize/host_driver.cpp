@@ -5,6 +5,8 @@
 //
 //   ctx  <n_slots> <max_rank> <max_adapter_id> <n_layers> <n_proj> (<d_in> <d_out>)*      -> ctx <status>
 //   load <n_in_use> <id>* <n_req> (<id> <rank> <slot>)*        -> load <status> (<slot>:<copied>)*   then   state <id>*
+//   ctxp <n_slots> <max_rank> <max_adapter_id> <n_layers> <n_pages> <n_proj> (<d_in> <d_out>)*   -> ctx <status>  (slots over a pool of pages)
+//   pages                                                      -> pages <first page>*
 //   map  <n_ids>                                               -> map <slot>*
 //   slab <n_slots> <max_rank> <max_tokens> <n_layers> <n_proj> (<d_in> <d_out>)*          -> slab <bytes>
 //   str  <status>                                              -> str <text>
@@ -87,7 +89,7 @@ int main()
     int32_t n_slots = 0;
     std::string cmd;
     while (std::cin >> cmd) {
-        if (cmd == "ctx") {
+        if (cmd == "ctx" || cmd == "ctxp") {
             if (ctx) lora_destroy(ctx);
             ctx = nullptr;
             lora_config cfg{};
@@ -95,6 +97,7 @@ int main()
             cfg.max_rank = next<int32_t>(std::cin);
             cfg.max_adapter_id = next<int32_t>(std::cin);
             cfg.n_layers = next<int32_t>(std::cin);
+            if (cmd == "ctxp") cfg.n_pages = next<int32_t>(std::cin);
             Shapes s = read_shapes(std::cin);
             cfg.n_proj = s.n_proj;
             cfg.proj = s.proj.get();
@@ -121,6 +124,10 @@ int main()
                 for (int32_t i = 0; i < n; ++i) std::printf(" %d:%d", d[i].slot, d[i].copied);
             std::printf("\nstate");
             for (int32_t s = 0; s < n_slots; ++s) std::printf(" %d", lora_slot_adapter(ctx, s));
+            std::printf("\n");
+        } else if (cmd == "pages") {
+            std::printf("pages");
+            for (int32_t s = 0; s < n_slots; ++s) std::printf(" %d", lora_slot_first_page(ctx, s));
             std::printf("\n");
         } else if (cmd == "map") {
             const int32_t n_ids = next<int32_t>(std::cin);

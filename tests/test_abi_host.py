@@ -12,8 +12,8 @@ from paper_2602_24044_amd import binding as B
 from test_oracle_slots import parse_trace
 
 
-def _host_ctx(n_slots=3, max_rank=32, proj=((64, 64),), max_adapter_id=63):
-    cfg = B.make_config(proj, n_slots, max_rank, 16, max_adapter_id, flags=B.LORA_CREATE_HOST_ONLY)
+def _host_ctx(n_slots=3, max_rank=32, proj=((64, 64),), max_adapter_id=63, n_pages=0):
+    cfg = B.make_config(proj, n_slots, max_rank, 16, max_adapter_id, flags=B.LORA_CREATE_HOST_ONLY, n_pages=n_pages)
     return B.lora_create(cfg)
 
 
@@ -202,5 +202,71 @@ def test_layers_in_the_config():
         # the slot table is one for all layers: a load names the adapter once
         assert B.lora_slots_load(ctx, [dict(adapter_id=5, rank=8, scale=1.0)]) == [(0, True)]
         assert B.lora_slot_of(ctx, 5) == 0
+    finally:
+        B.lora_destroy(ctx)
+
+
+# ---- slots over a pool of pages (lora_config.n_pages) ----
+def test_hand_traced_page_sequence_on_the_library():
+    n_slots, n_pages, calls = parse_trace(os.path.join(GOLDEN, "page_trace.txt"))
+    ctx = _host_ctx(n_slots, n_pages=n_pages)
+    try:
+        for in_use, reqs, exp, state, pages in calls:
+            descs = [dict(adapter_id=a, rank=r, scale=1.0, slot=s) for (a, r, s) in reqs]
+            if exp is None:
+                with pytest.raises(B.LoraError) as e:
+                    B.lora_slots_load(ctx, descs, in_use)
+                assert e.value.status == B.LORA_ERR_SLOTS_EXHAUSTED
+            else:
+                assert B.lora_slots_load(ctx, descs, in_use) == exp
+            assert [B.lora_slot_adapter(ctx, s) for s in range(n_slots)] == state
+            assert [B.lora_slot_first_page(ctx, s) for s in range(n_slots)] == pages
+    finally:
+        B.lora_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed,n_pages", [(0, 4), (1, 7), (2, 12), (3, 24), (4, 5)])
+def test_random_sequences_match_the_paged_slot_oracle(seed, n_pages):
+    rng = np.random.default_rng(seed)
+    n_slots, n_ids = 6, 20
+    ctx = _host_ctx(n_slots, n_pages=n_pages)
+    tab = oracle.PagedSlotTable(n_slots, n_pages)
+    try:
+        for _ in range(400):
+            ads = rng.choice(n_ids, size=int(rng.integers(1, 4)), replace=False)
+            reqs = [(int(a), int(rng.choice([0, 8, 16, 32])), int(rng.integers(0, n_slots)) if rng.random() < 0.1 else -1)
+                    for a in ads]
+            in_use = [int(v) for v in rng.choice(n_ids, size=int(rng.integers(0, 7)), replace=False)]
+            descs = [dict(adapter_id=a, rank=r, scale=1.0, slot=s) for (a, r, s) in reqs]
+            try:
+                want = tab.load(reqs, in_use)
+            except oracle.SlotsExhausted:
+                with pytest.raises(B.LoraError) as e:
+                    B.lora_slots_load(ctx, descs, in_use)
+                assert e.value.status == B.LORA_ERR_SLOTS_EXHAUSTED
+            else:
+                assert B.lora_slots_load(ctx, descs, in_use) == want
+            assert [B.lora_slot_adapter(ctx, s) for s in range(n_slots)] == tab.adapter
+            assert [B.lora_slot_first_page(ctx, s) for s in range(n_slots)] == tab.first_page
+            assert [B.lora_slot_of(ctx, i) for i in range(n_ids)] == tab.id2slot(n_ids).tolist()
+    finally:
+        B.lora_destroy(ctx)
+
+
+def test_page_pool_in_the_config():
+    proj = [(4096, 4096), (4096, 14336)]
+    uniform = B.lora_slab_bytes(B.make_config(proj, 384, 64, 512, 400))
+    # 384 slots over a pool that holds their adapters at an average rank of 32 instead of 64 each
+    pooled = B.lora_slab_bytes(B.make_config(proj, 384, 64, 512, 400, n_pages=384 * 4))
+    unit = sum(a + b for a, b in proj) * 2                   # bytes per rank unit
+    assert uniform - pooled >= 384 * 32 * unit - 4096 * 384  # the other half of the region, up to alignment
+    assert pooled >= 384 * 4 * 8 * unit
+    # a pool that cannot hold one adapter of the largest rank is refused; without pages the query says -1
+    with pytest.raises(B.LoraError):
+        B.lora_create(B.make_config([(64, 64)], 4, 32, 16, 9, flags=B.LORA_CREATE_HOST_ONLY, n_pages=3))
+    ctx = _host_ctx()
+    try:
+        B.lora_slots_load(ctx, [dict(adapter_id=1, rank=8, scale=1.0)])
+        assert B.lora_slot_first_page(ctx, 0) == -1
     finally:
         B.lora_destroy(ctx)

@@ -150,6 +150,36 @@ def test_slot_table_hand_trace_and_random_sequences(host_exe):
     assert out == want
 
 
+def test_paged_slot_table_hand_trace_and_random_sequences(host_exe):
+    script, want = [], []
+    n_slots, n_pages, calls = parse_trace(os.path.join(GOLDEN, "page_trace.txt"))
+    script.append(f"ctxp {n_slots} 32 63 1 {n_pages} 1 64 64")
+    want.append("ctx 0")
+    for in_use, reqs, exp, state, pages in calls:
+        script += [_load_line(in_use, reqs), "pages"]
+        want += _expect_load(state, B.LORA_ERR_SLOTS_EXHAUSTED if exp is None else exp)
+        want.append("pages " + " ".join(map(str, pages)))
+    rng = np.random.default_rng(11)
+    n_slots, n_ids, n_pages = 6, 20, 9
+    script.append(f"ctxp {n_slots} 32 {n_ids - 1} 2 {n_pages} 2 64 64 128 24")
+    want.append("ctx 0")
+    tab = oracle.PagedSlotTable(n_slots, n_pages)
+    for _ in range(400):
+        ads = rng.choice(n_ids, size=int(rng.integers(1, 4)), replace=False)
+        reqs = [(int(a), int(rng.choice([0, 8, 16, 32])), int(rng.integers(0, n_slots)) if rng.random() < 0.1 else -1)
+                for a in ads]
+        in_use = [int(v) for v in rng.choice(n_ids, size=int(rng.integers(0, 7)), replace=False)]
+        script += [_load_line(in_use, reqs), "pages"]
+        try:
+            res = tab.load(reqs, in_use)
+        except oracle.SlotsExhausted:
+            res = B.LORA_ERR_SLOTS_EXHAUSTED
+        want += _expect_load(tab.adapter, res)
+        want.append("pages " + " ".join(map(str, tab.first_page)))
+    out = run_clean([host_exe], stdin="\n".join(script) + "\n").splitlines()
+    assert out == want
+
+
 def test_argument_errors_and_queries(host_exe):
     script = ["ctx 2 16 7 1 1 64 64",
               "load 0 1 9 8 -1", "load 0 1 1 32 -1", "load 0 1 1 12 -1", "load 0 1 1 8 2", "load 0 1 1 -8 -1",
