@@ -212,7 +212,7 @@ class ModelSession:
     of every layer.  Owns tensors and forwards to the C ABI; no arithmetic of the method happens here."""
 
     def __init__(self, layers: Sequence[Workload], path: int = B.LORA_PATH_AUTO, split_k: int = 0,
-                 device: str = "cuda:0", n_slots: Optional[int] = None, packed_host: bool = True):
+                 device: str = "cuda:0", n_slots: Optional[int] = None, packed_host: bool = True, n_pages: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("liblora_mi355 needs a GPU; there is no CPU path")
         self.layers = list(layers)
@@ -223,7 +223,7 @@ class ModelSession:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         cfg = B.make_config(w.proj, n_slots or w.n_slots, w.max_rank, max(w.T, 1), w.max_adapter_id, path=path,
-                            split_k=split_k, n_layers=len(self.layers))
+                            split_k=split_k, n_layers=len(self.layers), n_pages=n_pages)
         nbytes = B.lora_slab_bytes(cfg)
         if nbytes == 0:
             raise B.LoraError(B.LORA_ERR_SHAPE, "lora_slab_bytes")

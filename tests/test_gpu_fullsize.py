@@ -17,9 +17,9 @@ from paper_2602_24044_amd.runtime import Session, bf16_tensor_to_bits
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(w, packed=True):
-    announce(f"full-size {w.name} T={w.T} packed={packed} proj={w.proj}")
-    sess = Session(w)
+def _run_full(w, packed=True, n_pages=0):
+    announce(f"full-size {w.name} T={w.T} packed={packed} n_pages={n_pages} proj={w.proj}")
+    sess = Session(w, n_pages=n_pages)
     try:
         sess.load(w.resident)
         if w.missing:
@@ -78,6 +78,17 @@ def test_config4_full_lora_term_alone():
     for p in range(len(w.proj)):
         w.W[p] = np.zeros_like(w.W[p])
     _run_full(w)
+
+
+def test_config4_full_from_a_pool_of_pages():
+    # the 384 adapters at their own ranks in a pool that fits them exactly (against 384 regions of rank 64)
+    w = wl.config4()
+    pages = sum(w.adapters[a].rank // 8 for a in w.resident)
+    uniform = B.lora_slab_bytes(B.make_config(w.proj, w.n_slots, w.max_rank, w.T, w.max_adapter_id))
+    pooled = B.lora_slab_bytes(B.make_config(w.proj, w.n_slots, w.max_rank, w.T, w.max_adapter_id, n_pages=pages))
+    announce(f"  slab bytes: uniform slots {uniform / 2**30:.2f} GiB, pool of {pages} pages {pooled / 2**30:.2f} GiB")
+    assert pooled < 0.6 * uniform
+    _run_full(w, n_pages=pages)
 
 
 def test_config3_full():

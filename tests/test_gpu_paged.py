@@ -78,3 +78,23 @@ def test_the_pool_is_smaller_than_uniform_slots():
     saved = (w.n_slots * w.max_rank - sum(w.adapters[a].rank for a in w.resident)) * unit
     announce(f"slab bytes uniform={uniform} pooled={pooled} saved={uniform - pooled} expected about {saved}")
     assert 0.9 * saved <= uniform - pooled <= 1.1 * saved
+
+
+def test_whole_model_context_over_a_pool():
+    # several layers: a page holds 8 rank units of every layer's matrices, so an adapter is still one run
+    from paper_2602_24044_amd.runtime import ModelSession
+    layers = wl.model_layers(wl.qwen_decode(shrink=8, n_tokens=150), 3)
+    lw0 = layers[0]
+    ms = ModelSession(layers, n_pages=_pages_needed(lw0))
+    announce(f"paged model step {lw0.name} layers=3 T={lw0.T} pages={_pages_needed(lw0)}")
+    try:
+        ms.load(lw0.resident)
+        ms.step()
+        torch.cuda.synchronize()
+        for l, lw in enumerate(ms.layers):
+            for p in range(len(lw.proj)):
+                y_ref = oracle.project(lw.x[p], lw.W[p], lw.token_ids, oracle.adapters_of(lw, p), bias=lw.bias_of(p))
+                assert rel_err(bf16_tensor_to_bits(ms.out[l][p]), y_ref) <= TOL, (l, p)
+        assert B.lora_poll_device_flags(ms.ctx) == (B.LORA_OK, 0)
+    finally:
+        ms.close()
