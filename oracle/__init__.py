@@ -384,3 +384,26 @@ class PagedSlotTable(SlotTable):
             self.last_used[s] = self.tick
             out.append((s, True))
         return out
+
+
+# ---------------------------------------------------------------------------
+# gated MLP input: silu(gate) * up on two projections of the same tokens
+# ---------------------------------------------------------------------------
+def silu(z: np.ndarray) -> np.ndarray:
+    """z * sigmoid(z) = z / (1 + exp(-z)), float64, written so that neither branch overflows."""
+    z = np.asarray(z, dtype=np.float64)
+    out = np.empty_like(z)
+    pos = z >= 0
+    out[pos] = z[pos] / (1.0 + np.exp(-z[pos]))
+    ez = np.exp(z[~pos])
+    out[~pos] = z[~pos] * ez / (1.0 + ez)
+    return out
+
+
+def gated(x, W_gate, W_up, ids, adapters_gate, adapters_up) -> np.ndarray:
+    """h[t, n] = silu(gate[t, n]) * up[t, n] with gate and up the two LoRA projections of the same x (the input
+    of the `down` projection in the gated MLP of the Llama and Qwen2.5 model families the paper evaluates on,
+    Sec. 8.1): each projection by the definition above, unrounded, then the activation and the product in float64."""
+    g = project(x, W_gate, ids, adapters_gate)
+    u = project(x, W_up, ids, adapters_up)
+    return silu(g) * u

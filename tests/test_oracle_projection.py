@@ -201,3 +201,48 @@ def test_bf16_rounding_of_inputs_is_nearest_even():
     vals = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.0, 3.0], dtype=np.float32)
     back = wl.bf16_bits_to_f32(wl.to_bf16_bits(vals))
     assert back.tolist() == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -0.0, 3.0]
+
+
+# ---- silu(gate) * up ----
+def test_silu_against_the_library_routine_and_its_limits():
+    import torch
+    z = np.concatenate([np.linspace(-60, 60, 2001), [-745.0, -40.0, 0.0, 1e-300, 40.0, 800.0]])
+    want = torch.nn.functional.silu(torch.from_numpy(z)).numpy()
+    got = oracle.silu(z)
+    assert np.allclose(got, want, rtol=1e-14, atol=1e-300)
+    assert oracle.silu(np.array([0.0]))[0] == 0.0
+    assert oracle.silu(np.array([800.0]))[0] == 800.0                  # sigmoid saturates, no overflow
+    assert abs(oracle.silu(np.array([-800.0]))[0]) < 1e-300 and np.isfinite(oracle.silu(np.array([-800.0]))[0])
+    # z * sigmoid(z) - (-z) * sigmoid(-z) = z  (sigmoid(z) + sigmoid(-z) = 1)
+    zz = np.linspace(-30, 30, 601)
+    assert np.allclose(oracle.silu(zz) - oracle.silu(-zz), zz, rtol=0, atol=1e-13)
+    # minimum of z * sigmoid(z): about -0.27846 at z = -1.27846
+    assert abs(oracle.silu(zz).min() + 0.2784645) < 1e-4
+
+
+def test_gated_hand_case_and_reductions():
+    bits = lambda a: wl.to_bf16_bits(np.asarray(a, dtype=np.float32))
+    # one token, x = [1, 2]; gate row [1, -1] -> -1 + adapter 2 * (x . [1, 0]) * 0.5 = 0; up row [0.5, 0.25] -> 1
+    x = bits([[1.0, 2.0]])
+    Wg, Wu = bits([[1.0, -1.0], [0.0, 1.0]]), bits([[0.5, 0.25], [2.0, 0.0]])
+    ids = np.array([0], dtype=np.int32)
+    Ag, Bg = bits([[1.0, 0.0]]), bits([[0.5], [0.0]])
+    ad_g = {0: (1, 2.0, Ag, Bg)}
+    ad_u = {0: (0, 0.0, None, None)}
+    h = oracle.gated(x, Wg, Wu, ids, ad_g, ad_u)
+    # column 0: gate = -1 + 2 * 1 * 0.5 = 0 -> silu 0 -> h = 0;  column 1: gate = 2, up = 2 -> 2 / (1 + e^-2) * 2
+    assert h[0, 0] == 0.0
+    assert h[0, 1] == pytest.approx(4.0 / (1.0 + np.exp(-2.0)), rel=1e-15)
+    # without adapters and with a huge gate the activation is the identity: h = gate * up
+    rng = np.random.default_rng(3)
+    x = bits(rng.standard_normal((5, 8)))
+    Wg = bits(np.full((4, 8), 0.0))
+    Wg_big = bits(np.tile(np.sign(wl.bf16_bits_to_f32(x))[0] * 64.0, (4, 1)))      # gate of token 0 is large and positive
+    Wu = bits(rng.standard_normal((4, 8)))
+    none = np.full(5, -1, dtype=np.int32)
+    h0 = oracle.gated(x, Wg, Wu, none, {}, {})
+    assert np.all(h0 == 0.0)                                                       # silu(0) = 0 whatever `up` is
+    hb = oracle.gated(x, Wg_big, Wu, none, {}, {})
+    g = oracle.project(x, Wg_big, none, {})
+    u = oracle.project(x, Wu, none, {})
+    assert g[0].min() > 50 and np.allclose(hb[0], g[0] * u[0], rtol=1e-15)
