@@ -251,6 +251,18 @@ lora_status lora_model_forward_group(lora_ctx *ctx, int32_t layer, int32_t n, co
                                      const void *const *d_x, const void *const *d_W, const lora_segments *seg,
                                      void *const *d_out, void *stream);
 
+/* Gate and up of a gated MLP in one call, with their product: d_out[t, n] = silu(gate[t, n]) * up[t, n], where gate
+ * and up are the projections proj_gate and proj_up of the same input d_x, each with its adapter term as in
+ * lora_layer_forward (paper Sec. 2.2), and silu(z) = z / (1 + exp(-z)).  This is what the `down` projection of the
+ * Llama and Qwen2.5 model families reads (the paper's evaluation, Sec. 8.1); formed in the GEMM's epilogue from the
+ * fp32 accumulators and rounded to bf16 once, the two projections never travel to memory.  Both projections must
+ * have the same d_in and d_out and no bias (lora_set_bias): SHAPE / INVALID_ARG otherwise.  d_out: device bf16
+ * [T, d_out].  Always one GEMM launch over full K (plus the shrink launch where it does not ride inside); everything
+ * else as lora_layer_forward_group.  Errors: as lora_layer_forward_group. */
+lora_status lora_layer_forward_glu(lora_ctx *ctx, int32_t proj_gate, int32_t proj_up, const void *d_x,
+                                   const void *d_W_gate, const void *d_W_up, const lora_segments *seg, void *d_out,
+                                   void *stream);
+
 /* Bias of a backbone projection (paper Sec. 2.2: the adapter's activations are added to the backbone layer's
  * output, which for a layer with a bias is x W^T + b; Sec. 8.1 evaluates on the Qwen2.5 family, whose q, k, v
  * projections have one).  d_bias: device bf16 [d_out_proj], 16-byte aligned, owned by the caller, read by every

@@ -347,10 +347,15 @@ __device__ inline void park_v_share(uint16_t* sV, int q, u32x4 packed)
 // (DeviceView::row_loc: one value per resident adapter, so it also tells adapters apart; -1 or rank 0: backbone only).  sV: the windows' scaled
 // shrink results in LDS, window mb at sV + mb * kPieceRows * kVStageStride.
 // ---------------------------------------------------------------------------------------------------
-template <int MB, int NB, int D>
+// GLU: the column blocks alternate between two projections of the same tokens (block 2 j: columns n_first + 32 j ..
+// of the first, block 2 j + 1: the same columns of the second), each with its own B (b_unit / b_unit2) and its own
+// shrink results (sV / sV2).
+template <int MB, int NB, int D, bool GLU = false>
 __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[MB], const int (&rank)[MB], int n_first,
-                                      int N, const DeviceView& dv, size_t b_unit, const uint16_t* sV)
+                                      int N, const DeviceView& dv, size_t b_unit, const uint16_t* sV, size_t b_unit2 = 0,
+                                      const uint16_t* sV2 = nullptr)
 {
+    static_assert(!GLU || NB % 2 == 0, "pairs of column blocks");
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 31, h = lane >> 5;
     unsigned long long todo[MB];
@@ -390,9 +395,10 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
         const int kc = k < q.r ? k : 0;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            int n = n_first + nb * 32 + i;
+            int n = n_first + (GLU ? (nb >> 1) : nb) * 32 + i;
             if (n > N - 1) n = N - 1;
-            const uint16_t* Bs = dv.slots + (size_t)q.s * kLocUnit + ((size_t)q.r * b_unit + (size_t)n * q.r);
+            const size_t bu = (GLU && (nb & 1)) ? b_unit2 : b_unit;
+            const uint16_t* Bs = dv.slots + (size_t)q.s * kLocUnit + ((size_t)q.r * bu + (size_t)n * q.r);
             fb.f[nb] = load16(Bs + kc);
         }
     };
@@ -404,16 +410,19 @@ __device__ inline void expand_windows(f32x16 (&acc)[MB][NB], const int (&slot)[M
         const int k = q.ks * 16 + h * 8;
         const bool k_on = k < q.r;                            // beyond the rank the lane loaded a stand-in
         const uint16_t* vrow = sV + (q.mb * kPieceRows + i) * kVStageStride;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (my == q.s && k_on) v = *reinterpret_cast<const u32x4*>(vrow + k);
-        const bf16x8 vf = as_bf16x8(v);
+        u32x4 v = {0u, 0u, 0u, 0u}, v2 = {0u, 0u, 0u, 0u};
+        if (my == q.s && k_on) {
+            v = *reinterpret_cast<const u32x4*>(vrow + k);
+            if (GLU) v2 = *reinterpret_cast<const u32x4*>(sV2 + (q.mb * kPieceRows + i) * kVStageStride + k);
+        }
+        const bf16x8 vf = as_bf16x8(v), vf2 = as_bf16x8(v2);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if (q.mb == mb) {                                 // uniform over the wave
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const u32x4 bf = k_on ? fb.f[nb] : u32x4{0u, 0u, 0u, 0u};
-                    acc[mb][nb] = mfma32(as_bf16x8(bf), vf, acc[mb][nb]);
+                    acc[mb][nb] = mfma32(as_bf16x8(bf), (GLU && (nb & 1)) ? vf2 : vf, acc[mb][nb]);
                 }
             }
         }

@@ -241,6 +241,56 @@ __device__ __forceinline__ void finish_tile_prefetched(f32x16 (&acc)[MB][NB], co
     store_windows<MB, NB>(acc, a, sl, m_first, n_first, mine);
 }
 
+// Fused path over a pair of projections of the same tokens whose product leaves the kernel (the gated MLP of the
+// Llama and Qwen2.5 families, paper Sec. 8.1: h = silu(gate) * up is what `down` reads): acc[mb][2 j] holds columns
+// n_first + 32 j .. of gate, acc[mb][2 j + 1] the same columns of up.  One window per pass: shrink results of both
+// projections parked side by side, one expand pass over the window's slots with each block's own B and shrink
+// results, then the activation and the product in fp32, one bf16 rounding, rows out through LDS.
+constexpr int glu_epilogue_bytes_per_wave() { return 2 * kPieceRows * kVStageStride * 2; }
+
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
+
+template <int MB, int NB>
+__device__ __forceinline__ void finish_tile_glu(f32x16 (&acc)[MB][NB], const GemmArgs& a, const Slice& gate, const Slice& up,
+                                                int m_first, int n_first, int wave, uint16_t* ring)
+{
+    static_assert(NB % 2 == 0, "pairs of column blocks");
+    static_assert(glu_epilogue_bytes_per_wave() >= kPieceRows * (NB / 2) * 64, "output rows fit the wave's piece");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 31;
+    const int T = a.m_end, N = gate.N;
+    uint8_t* mine = reinterpret_cast<uint8_t*>(ring) + wave * glu_epilogue_bytes_per_wave();
+    uint16_t* sV = reinterpret_cast<uint16_t*>(mine);
+    uint16_t* sV2 = sV + kPieceRows * kVStageStride;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = m_first + mb * 32 + i;
+        const bool ok = m < T;
+        const int ps[1] = {ok ? a.dv.row_loc[m] : -1};
+        const int pr[1] = {ok ? a.dv.row_rank[m] : 0};
+        f32x16(&win)[1][NB] = *reinterpret_cast<f32x16(*)[1][NB]>(&acc[mb]);
+        if (__ballot(ps[0] >= 0 && pr[0] > 0) != 0) {             // uniform over the wave
+            u32x4 share[1][4], share2[1][4];
+            window_v_shares<1>(share, gate.vpart, a.n_kc, m_first + mb * 32, a.dv);
+            window_v_shares<1>(share2, up.vpart, a.n_kc, m_first + mb * 32, a.dv);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                park_v_share(sV, q, share[0][q]);
+                park_v_share(sV2, q, share2[0][q]);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            expand_windows<1, NB, kExpandDepth<NB>, true>(win, ps, pr, n_first, N, a.dv, gate.b_unit, sV, up.b_unit, sV2);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the piece is reused
+        }
+        f32x16 prod[1][NB / 2];
+#pragma unroll
+        for (int j = 0; j < NB / 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) prod[0][j][v] = silu_f32(win[0][2 * j][v]) * win[0][2 * j + 1][v];
+        store_windows<1, NB / 2>(prod, a, gate, m_first + mb * 32, n_first, mine);
+    }
+}
+
 // ring: LDS no longer used by the main loop (the caller has synchronised).
 template <int MB, int NB, bool FUSED>
 __device__ __forceinline__ void finish_tile(f32x16 (&acc)[MB][NB], const GemmArgs& a, const Slice& sl, int m_first,

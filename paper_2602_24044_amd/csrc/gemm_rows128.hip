@@ -51,9 +51,14 @@ __device__ inline void wait_copies_then_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
+// GLU (fused path only): the launch serves two projections of the same tokens, gate = slice 0 and up = slice 1, and
+// stores silu(gate) * up.  A workgroup then owns BN / 2 output columns; the W part of a stage alternates between
+// the two matrices in blocks of 32 rows (block 2 j: rows of gate, block 2 j + 1: the same rows of up), so that a
+// wave holds both factors of every output element it owns in the same lane.
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, bool GLU = false>
 __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs a, ShrinkArgs sa)
 {
+    static_assert(!GLU || FUSED, "the product is formed in the fused epilogue");
     constexpr int NWV = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;           // wave tile
     constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 accumulator blocks per wave
@@ -122,13 +127,16 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         tile_n = b / a.tiles_m;
     }
     int si = 0;
-    for (int k = 1; k < a.g.n; ++k)
-        if (tile_n >= a.g.s[k].tile0) si = k;
+    if (!GLU)
+        for (int k = 1; k < a.g.n; ++k)
+            if (tile_n >= a.g.s[k].tile0) si = k;
     const Slice sl = pick_slice(a.g, si);
     const uint16_t* const xg = sl.x;
     const uint16_t* const Wg = sl.W;
+    const uint16_t* const Wup = GLU ? a.g.s[1].W : sl.W;
     const int N = sl.N;
-    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
+    // n0: first column inside the slice (GLU: first output column; the tile is BN / 2 of them wide)
+    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * (GLU ? BN / 2 : BN);
 
     ShrinkPrefetch spf{};
     const int rest_first = extra * a.shrink_q + (int)blockIdx.x;     // this workgroup's first item after its tile
@@ -154,13 +162,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         if (m > T - 1) m = T - 1;
         xoff[q] = (uint32_t)a.dv.perm[m] * (uint32_t)K + (uint32_t)(c * 8 + kt_begin * kTK64);
     }
+    bool w_up[WQ];                                           // GLU: this copy instruction's rows come from `up` (uniform over the wave)
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         const int r = (wave * WQ + q) * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ((r >> 1) & 7);
-        int n = n0 + r;
+        int n = GLU ? n0 + (r >> 6) * 32 + (r & 31) : n0 + r;
         if (n > N - 1) n = N - 1;
         woff[q] = (uint32_t)n * (uint32_t)K + (uint32_t)(c * 8 + kt_begin * kTK64);
+        w_up[q] = GLU && ((((wave * WQ + q) * 8) >> 5) & 1);
     }
     const uint32_t cp_x = ring_addr + wave * XQ * 1024;
     const uint32_t cp_w = ring_addr + BM * kRowB + wave * WQ * 1024;
@@ -171,7 +181,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         for (int q = 0; q < QPT; ++q) {
             if (q < q_begin || q >= q_end) continue;
             if (q < WQ)
-                copy16_to_lds(Wg + (woff[q] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + q * 1024));
+                copy16_to_lds((w_up[q] ? Wup : Wg) + (woff[q] + k0), __builtin_amdgcn_readfirstlane(cp_w + so + q * 1024));
             else
                 copy16_to_lds(xg + (xoff[q - WQ] + k0), __builtin_amdgcn_readfirstlane(cp_x + so + (q - WQ) * 1024));
         }
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     auto copy_tile = [&](int t, int stage) { copy_part(t, stage, 0, QPT); };
 
     f32x16 acc[MB][NB];
-    init_accumulators<MB, NB, FUSED>(acc, sl, n0 + wn * WTN);
+    init_accumulators<MB, NB, FUSED && !GLU>(acc, sl, n0 + wn * WTN);       // GLU: no bias (refused by the host)
 
     // byte offset of this lane's fragment of K step kk inside a 32-row block: row i, chunk 2 kk + h
     const int sw = (i >> 1) & 7;
@@ -194,7 +204,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         if (d < nk) copy_tile(d, d);
 
     // fused path: the epilogue's per-row data travels while the first tiles do
-    constexpr bool PRE = FUSED && MB <= 2;
+    constexpr bool PRE = FUSED && MB <= 2 && !GLU;
     TilePrefetch<PRE ? MB : 1> pre;
     if constexpr (PRE) {
         prefetch_rows(pre, a, m0 + wm * WTM);
@@ -297,6 +307,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
 
     // ---------------- epilogue ----------------
     static_assert(!FUSED || NS * STAGE_B >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
+    static_assert(!GLU || NS * STAGE_B >= NWV * glu_epilogue_bytes_per_wave(), "ring too small for the gated epilogue");
     static_assert(FUSED || NS * STAGE_B >= NWV * kRedFloatsPerWave * 4, "ring too small for the reduction");
     if (FUSED) __syncthreads();
     if (FUSED && front > 0 && !early) {                           // uniform over the workgroup
@@ -318,7 +329,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
         if constexpr (PRE) prefetch_v_issue(pre, a, sl, m0 + wm * WTM);
     }
     if constexpr (PRE) prefetch_v_finish(pre, a, sl, m0 + wm * WTM);
-    if constexpr (PRE)
+    if constexpr (GLU)
+        finish_tile_glu<MB, NB>(acc, a, sl, a.g.s[1], m0 + wm * WTM, n0 + wn * (WTN / 2), wave, reinterpret_cast<uint16_t*>(ring));
+    else if constexpr (PRE)
         finish_tile_prefetched<MB, NB>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, wave, reinterpret_cast<uint16_t*>(ring), pre);
     else
         finish_tile<MB, NB, FUSED>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, split, wave, reinterpret_cast<uint16_t*>(ring));
@@ -333,22 +346,27 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_rows128_kernel(GemmArgs 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS>
+template <int BM, int BN, int WGM, int WGN, bool FUSED, int NS, bool GLU = false>
 hipError_t launch_rows128(GemmArgs a, const ShrinkArgs& sa, hipStream_t stream)
 {
     a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
     a.tiles_n = 0;
-    for (int k = 0; k < a.g.n; ++k) {
-        a.g.s[k].tile0 = a.tiles_n;
-        a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+    if (GLU) {                                            // gate and up together: BN / 2 output columns per tile
+        a.g.s[0].tile0 = a.g.s[1].tile0 = 0;
+        a.tiles_n = (a.g.s[0].N + BN / 2 - 1) / (BN / 2);
+    } else {
+        for (int k = 0; k < a.g.n; ++k) {
+            a.g.s[k].tile0 = a.tiles_n;
+            a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+        }
     }
     int grid = a.tiles_m * a.tiles_n * (FUSED ? 1 : a.split_k);
     const int extra = FUSED ? 0 : a.main_grid;            // on entry: workgroups that only do shrink items
     a.main_grid = grid;
     grid += extra;
     if (FUSED) grid += a.shrink_front;                    // those come first
-    hipLaunchKernelGGL((gemm_rows128_kernel<BM, BN, WGM, WGN, FUSED, NS>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream,
-                       a, sa);
+    hipLaunchKernelGGL((gemm_rows128_kernel<BM, BN, WGM, WGN, FUSED, NS, GLU>), dim3(grid), dim3(WGM * WGN * kWave), 0,
+                       stream, a, sa);
     return hipGetLastError();
 }
 
@@ -378,6 +396,17 @@ hipError_t launch_gemm_rows128_fused(const GemmArgs& a, const ShrinkArgs& none, 
             *name = "gemm_fused_256x128x64_w8";
             return launch_rows128<256, 128, 4, 2, true, 3>(a, none, stream);
     }
+}
+
+hipError_t launch_gemm_rows128_glu(const GemmArgs& a, const ShrinkArgs& none, int variant, hipStream_t stream,
+                                   const char** name)
+{
+    if (variant == 1) {
+        *name = "gemm_glu_128x128x64_w4";
+        return launch_rows128<128, 128, 2, 2, true, 4, true>(a, none, stream);
+    }
+    *name = "gemm_glu_256x128x64_w8";
+    return launch_rows128<256, 128, 4, 2, true, 3, true>(a, none, stream);
 }
 
 hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream,

@@ -47,7 +47,10 @@ __device__ inline void lds_done_then_barrier()
 
 // PG: tiles in flight in registers (1: compute-bound shapes, the tile's data comes from L2 within one tile time;
 // 2: small batches, where the weight stream comes from HBM and bytes in flight set the rate).
-template <int BM, int BN, int WGM, int WGN, int PG>
+// GLU: gate = slice 0 and up = slice 1 of the same tokens, silu(gate) * up stored; the W part of a stage alternates
+// between the two matrices in blocks of 32 rows and a workgroup owns BN / 2 output columns (as in the 64-wide-K
+// kernel for small batches).
+template <int BM, int BN, int WGM, int WGN, int PG, bool GLU = false>
 __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a)
 {
     constexpr int NWV = WGM * WGN;
@@ -59,6 +62,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
     static_assert(2 * STAGE_B <= 160 * 1024, "LDS");
     static_assert(2 * STAGE_B >= NWV * epilogue_bytes_per_wave<NB>(), "ring too small for the fused epilogue");
+    static_assert(!GLU || 2 * STAGE_B >= NWV * glu_epilogue_bytes_per_wave(), "ring too small for the gated epilogue");
 
     __shared__ __attribute__((aligned(1024))) uint8_t ring[2 * STAGE_B];
 
@@ -71,11 +75,13 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     // blockIdx -> (tile_m, tile_n): the M tile is the fastest index (neighbouring workgroups share the W tile)
     const int tile_m = (int)blockIdx.x % a.tiles_m, tile_n = (int)blockIdx.x / a.tiles_m;
     int si = 0;
-    for (int k = 1; k < a.g.n; ++k)
-        if (tile_n >= a.g.s[k].tile0) si = k;
+    if (!GLU)
+        for (int k = 1; k < a.g.n; ++k)
+            if (tile_n >= a.g.s[k].tile0) si = k;
     const Slice sl = pick_slice(a.g, si);
     const int N = sl.N;
-    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * BN;      // n0: column inside the slice
+    // n0: first column inside the slice (GLU: first output column; the tile is BN / 2 of them wide)
+    const int m0 = a.m_begin + tile_m * BM, n0 = (tile_n - sl.tile0) * (GLU ? BN / 2 : BN);
     const int nk = K / kSK;
 
     // Staging assignment: load q of wave w covers stage rows 8 (w XQ + q) .. + 7 of the x part (same for the W
@@ -83,6 +89,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     // line.  Rows past T or N are clamped to the last valid row: they are computed, never stored.
     uint32_t xoff[XQ], woff[WQ];                            // byte offset of this lane's 16 bytes in tile 0
     uint32_t xst[XQ], wst[WQ];                              // byte offset of their place in a stage
+    bool w_up[WQ];                                          // GLU: the rows of this load come from `up` (uniform over the wave)
 #pragma unroll
     for (int q = 0; q < XQ; ++q) {
         const int r = (wave * XQ + q) * 8 + (lane >> 3), c = lane & 7;
@@ -94,19 +101,21 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
 #pragma unroll
     for (int q = 0; q < WQ; ++q) {
         const int r = (wave * WQ + q) * 8 + (lane >> 3), c = lane & 7;
-        int n = n0 + r;
+        int n = GLU ? n0 + (r >> 6) * 32 + (r & 31) : n0 + r;
         if (n > N - 1) n = N - 1;
         woff[q] = ((uint32_t)n * (uint32_t)K + (uint32_t)(c * 8)) * 2u;
+        w_up[q] = GLU && ((((wave * WQ + q) * 8) >> 5) & 1);
         wst[q] = (uint32_t)((BM + r) * kSRow + ((c ^ ((r >> 1) & 7)) << 4));
     }
     const uint8_t* const xb = reinterpret_cast<const uint8_t*>(sl.x);
     const uint8_t* const wb = reinterpret_cast<const uint8_t*>(sl.W);
+    const uint8_t* const wb_up = reinterpret_cast<const uint8_t*>(GLU ? a.g.s[1].W : sl.W);
     static_assert(PG == 1 || PG == 2, "register sets");
     u32x4 stg[PG][XQ + WQ];                                 // the tiles in flight: W parts first, then x parts
     constexpr int NST = XQ + WQ;
     auto load_one = [&](int set, int t, int q) {             // set, q: compile-time constants at every call site
         const size_t k0 = (size_t)t * (kSK * 2);
-        stg[set][q] = q < WQ ? *reinterpret_cast<const u32x4*>(wb + k0 + woff[q])
+        stg[set][q] = q < WQ ? *reinterpret_cast<const u32x4*>((w_up[q] ? wb_up : wb) + k0 + woff[q])
                              : *reinterpret_cast<const u32x4*>(xb + k0 + xoff[q - WQ]);
     };
     auto store_one = [&](int set, int stage, int q) {
@@ -115,7 +124,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     };
 
     f32x16 acc[MB][NB];
-    init_accumulators<MB, NB, true>(acc, sl, n0 + wn * WTN);
+    init_accumulators<MB, NB, !GLU>(acc, sl, n0 + wn * WTN);        // GLU: no bias (refused by the host)
 
     // byte offset of this lane's fragment of K step kk inside a 32-row block: row i, chunk 2 kk + h
     const int sw_i = (i >> 1) & 7;
@@ -227,24 +236,38 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
 
     // ---------------- epilogue ----------------
     __syncthreads();          // every wave has left the main loop: the ring is free
-    finish_tile<MB, NB, true>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, 0, wave, reinterpret_cast<uint16_t*>(ring));
+    if constexpr (GLU)
+        finish_tile_glu<MB, NB>(acc, a, sl, a.g.s[1], m0 + wm * WTM, n0 + wn * (WTN / 2), wave, reinterpret_cast<uint16_t*>(ring));
+    else
+        finish_tile<MB, NB, true>(acc, a, sl, m0 + wm * WTM, n0 + wn * WTN, 0, wave, reinterpret_cast<uint16_t*>(ring));
 }
 
-template <int BM, int BN, int WGM, int WGN, int PG>
+template <int BM, int BN, int WGM, int WGN, int PG, bool GLU = false>
 hipError_t launch_staged(GemmArgs a, hipStream_t stream)
 {
     a.tiles_m = (a.m_end - a.m_begin + BM - 1) / BM;
     a.tiles_n = 0;
-    for (int k = 0; k < a.g.n; ++k) {
-        a.g.s[k].tile0 = a.tiles_n;
-        a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+    if (GLU) {                                            // gate and up together: BN / 2 output columns per tile
+        a.g.s[0].tile0 = a.g.s[1].tile0 = 0;
+        a.tiles_n = (a.g.s[0].N + BN / 2 - 1) / (BN / 2);
+    } else {
+        for (int k = 0; k < a.g.n; ++k) {
+            a.g.s[k].tile0 = a.tiles_n;
+            a.tiles_n += (a.g.s[k].N + BN - 1) / BN;
+        }
     }
     const int grid = a.tiles_m * a.tiles_n;
-    hipLaunchKernelGGL((gemm_staged_kernel<BM, BN, WGM, WGN, PG>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream, a);
+    hipLaunchKernelGGL((gemm_staged_kernel<BM, BN, WGM, WGN, PG, GLU>), dim3(grid), dim3(WGM * WGN * kWave), 0, stream, a);
     return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_gemm_staged_glu(const GemmArgs& a, hipStream_t stream, const char** name)
+{
+    *name = "gemm_glu_staged_256x256x64_w8";
+    return launch_staged<256, 256, 2, 4, 1, true>(a, stream);
+}
 
 hipError_t launch_gemm_staged_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name)
 {

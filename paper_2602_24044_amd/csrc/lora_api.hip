@@ -360,7 +360,7 @@ struct ForwardPlan {
 };
 
 lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t* projs, size_t part_elems,
-                         size_t vpart_elems, ForwardPlan& out)
+                         size_t vpart_elems, ForwardPlan& out, bool fused_only = false)
 {
     const int K = c->proj[projs[0]].d_in;
     // the slices sit side by side along N, each padded to a multiple of 128 columns
@@ -385,6 +385,7 @@ lora_status plan_forward(const lora_ctx* c, int32_t T, int32_t n, const int32_t*
         if (c->cfg.path == LORA_PATH_SPLITK) split = true;
         else if (c->cfg.path == LORA_PATH_AUTO) split = tiles_of(256, 256) < c->n_cus / 2;
     }
+    if (fused_only) split = false;
     if (split) {
         // narrow launches (k, v alone) fill the chip better with square 128 x 128 tiles
         // small batches walk K in 64-wide tiles (whole cache lines per row segment).  Narrow launches (k, v
@@ -962,9 +963,10 @@ struct ScratchRef {
     bool is_static;
 };
 
+// glu: the two projections are gate and up of the same tokens and silu(gate) * up is stored to d_out[0]
 lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* projs, const void* const* d_x,
                          const void* const* d_W, const lora_segments* seg, void* const* d_out, void* stream_v,
-                         const ScratchRef& scr)
+                         const ScratchRef& scr, bool glu = false)
 {
     if (!c || !seg || !projs || n < 1 || n > kMaxGroup) return LORA_ERR_INVALID_ARG;
     if (layer < 0 || layer >= c->n_layers) return LORA_ERR_INVALID_ARG;
@@ -1001,7 +1003,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
         }
     }
     ForwardPlan plan;
-    if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, scr.vpart_elems, plan); st != LORA_OK)
+    if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, scr.vpart_elems, plan, glu); st != LORA_OK)
         return (st == LORA_ERR_OOM && scr.is_static) ? LORA_ERR_SCRATCH_LIMIT : st;
     const int K = plan.K, Mpad = plan.Mpad, n_max = plan.n_max, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
     const long n_pad_total = plan.n_pad_total;
@@ -1104,7 +1106,10 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
     if (!split) {
         // ---- shrink, then base GEMM with the expand in its epilogue ----
         int fv = c->tune[LORA_TUNE_FUSED_VARIANT];
-        const bool auto_variant = fv == 0;
+        const bool auto_variant = fv == 0 && !glu;
+        // gate and up with their product: the 64-wide-K kernel up to 1024 tokens (128-row tiles up to 128), the
+        // register-staged 256 x 256 tile above
+        if (glu) fv = T <= 128 ? 9 : (T <= kSplitMaxTokens ? 8 : 0);
         if (auto_variant) {
             fv = pick_fused_variant(c->n_cus, tiles_of);
             // small batch: bound by the copies, not by the MFMA issue: whole-line tiles, every wave copies
@@ -1195,7 +1200,8 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
             a.sync = c->dev<uint32_t>(c->L.off_header) + 8;
             a.flags = c->d_flags();
             // 8 .. 11, 13, 14: 64-wide K tiles through the copy instruction; 12: the 32-wide 256 x 256 eight-wave kernel
-            const hipError_t le = ((fv >= 8 && fv <= 11) || fv == 13 || fv == 14)
+            const hipError_t le = glu ? (fv == 0 ? launch_gemm_staged_glu(a, s, &name) : launch_gemm_rows128_glu(a, sa, fv - 8, s, &name))
+                                  : ((fv >= 8 && fv <= 11) || fv == 13 || fv == 14)
                                       ? launch_gemm_rows128_fused(a, sa, fv >= 13 ? fv - 9 : fv - 8, s, &name)
                                       // 0 (the big tile of the automatic choice), 15, 16: tiles staged through registers
                                       : (fv == 0 || (fv >= 15 && fv <= 18)) ? launch_gemm_staged_fused(a, fv == 0 ? 0 : fv - 15, s, &name)
@@ -1254,6 +1260,22 @@ lora_status lora_layer_forward_static(lora_ctx* c, int32_t p, const void* d_x, c
 }
 
 size_t lora_static_scratch_bytes(void) { return kStaticPartBytes + kStaticVpartBytes; }
+
+lora_status lora_layer_forward_glu(lora_ctx* c, int32_t proj_gate, int32_t proj_up, const void* d_x, const void* d_W_gate,
+                                   const void* d_W_up, const lora_segments* seg, void* d_out, void* stream_v)
+{
+    if (!c) return LORA_ERR_INVALID_ARG;
+    if (proj_gate < 0 || proj_gate >= c->cfg.n_proj || proj_up < 0 || proj_up >= c->cfg.n_proj || proj_gate == proj_up)
+        return LORA_ERR_INVALID_ARG;
+    if (c->proj[proj_gate].d_out != c->proj[proj_up].d_out || c->proj[proj_gate].d_in != c->proj[proj_up].d_in)
+        return LORA_ERR_SHAPE;
+    if (c->bias[proj_gate] || c->bias[proj_up]) return LORA_ERR_INVALID_ARG;      // the gated MLPs served here have none
+    const int32_t projs[2] = {proj_gate, proj_up};
+    const void* xs[2] = {d_x, d_x};
+    const void* Ws[2] = {d_W_gate, d_W_up};
+    void* outs[2] = {d_out, d_out};
+    return forward_impl(c, 0, 2, projs, xs, Ws, seg, outs, stream_v, slab_scratch(c), true);
+}
 
 lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,
                                      const void* const* d_W, const lora_segments* seg, void* const* d_out,

@@ -174,6 +174,9 @@ hipError_t launch_gemm_splitk(const GemmArgs& a, const ShrinkArgs& sa, int varia
 hipError_t launch_gemm_rows128_fused(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 hipError_t launch_gemm_rows128_splitk(const GemmArgs& a, const ShrinkArgs& sa, int variant, hipStream_t stream, const char** name);
 // large batches: tiles staged through registers (ordinary loads + LDS writes)
+hipError_t launch_gemm_rows128_glu(const GemmArgs& a, const ShrinkArgs& none, int variant, hipStream_t stream,
+                                   const char** name);
+hipError_t launch_gemm_staged_glu(const GemmArgs& a, hipStream_t stream, const char** name);
 hipError_t launch_gemm_staged_fused(const GemmArgs& a, int variant, hipStream_t stream, const char** name);
 hipError_t launch_reduce_expand(const ReduceArgs& a, int grid, hipStream_t stream);
 

@@ -157,6 +157,16 @@ class Session:
                                    [self.out[p].data_ptr() for p in ps], s)
         return [self.out[p] for p in ps]
 
+    def forward_glu(self, p_gate: int, p_up: int, out: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """silu(gate) * up of the two projections on the input of p_gate (lora_layer_forward_glu)."""
+        if out is None:
+            out = torch.empty((self.w.T, self.w.proj[p_gate][1]), dtype=torch.bfloat16, device=self.device)
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        B.lora_layer_forward_glu(self.ctx, p_gate, p_up, self.x[p_gate].data_ptr(), self.W[p_gate].data_ptr(),
+                                 self.W[p_up].data_ptr(), self.seg, out.data_ptr(), s)
+        return out
+
     def packed_groups(self) -> List[List[int]]:
         return packed_groups(self.w)
 

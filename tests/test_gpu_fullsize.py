@@ -128,3 +128,35 @@ def test_whole_model_two_layers_full_size():
         assert st == B.LORA_OK and word == 0
     finally:
         ms.close()
+
+
+@pytest.mark.parametrize("make", [wl.config2, wl.config3, wl.config5])
+def test_gated_gate_up_full(make):
+    # silu(gate) * up in one call at full size: stratified samples, each factor evaluated by the oracle on its own
+    w = make()
+    g, u = w.proj_names.index("gate"), w.proj_names.index("up")
+    announce(f"full-size glu {w.name} T={w.T} proj={w.proj[g]}")
+    sess = Session(w)
+    try:
+        sess.load(w.resident)
+        if w.missing:
+            sess.load(w.missing, in_use=w.distinct_adapters())
+        sess.bucket()
+        assert check_segments(sess, w) == 0
+        perm, seg_start, _, n_seg, _ = oracle.bucket(w.token_ids, sess.id2slot(), w.mode)
+        out = sess.forward_glu(g, u)
+        torch.cuda.synchronize()
+        launches = B.lora_last_launches(sess.ctx)
+        got_all = bf16_tensor_to_bits(out)
+        ts, ns = stratified_samples(np.random.default_rng(99), perm, seg_start, n_seg, w.T, w.proj[g][1])
+        gate = oracle.project_at(w.x[g], w.W[g], w.token_ids, oracle.adapters_of(w, g), ts, ns)
+        up = oracle.project_at(w.x[g], w.W[u], w.token_ids, oracle.adapters_of(w, u), ts, ns)
+        h_ref = oracle.silu(gate) * up
+        got = wl.bf16_bits_to_f64(got_all[ts, ns])
+        err = float(np.max(np.abs(got - h_ref)) / np.max(np.abs(h_ref)))
+        announce(f"  launches={launches} samples={ts.shape[0]} rel_err={err:.3e}")
+        assert err <= TOL
+        assert np.isfinite(wl.bf16_bits_to_f32(got_all)).all()
+        assert B.lora_poll_device_flags(sess.ctx) == (B.LORA_OK, 0)
+    finally:
+        sess.close()
