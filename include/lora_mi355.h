@@ -24,7 +24,8 @@
  *   - argument errors are detected on the host and reported before anything is enqueued;
  *   - GPU work is enqueued on the stream handed in (a hipStream_t passed as void*; NULL = the
  *     default stream); no hot call (lora_slots_load, lora_bucket, lora_layer_forward)
- *     synchronises with the device or allocates memory;
+ *     synchronises with the device or allocates device memory (lora_slots_load plans on small
+ *     host-side copies of the slot table and asks the runtime about each pinned source buffer);
  *   - there is no CPU fallback: without a usable GPU the calls that enqueue work fail with
  *     LORA_ERR_HIP.
  */
