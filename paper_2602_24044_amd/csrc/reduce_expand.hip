@@ -89,11 +89,11 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
         }
     }
 
-    // the window's shrink results, thread -> (row, 8 ranks): requested behind the first partial tiles (their
-    // address needs only the row's rank, which was requested before those)
+    // the window's shrink results, thread -> (row, 8 ranks): requested behind the first partial tiles, for every
+    // existing row whatever its rank (what lies beyond a row's rank was never written and is dropped below): the
+    // loads then do not wait for the row's rank to arrive, one memory round trip less on the kernel's chain
     f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-    const bool st_live = st_on && st_seg * 8 < st_rank;
-    if (st_live) {
+    if (st_on) {
 #pragma unroll 4
         for (int c = 0; c < a.n_kc; ++c) {
             const float* vp = sl.vpart + ((size_t)c * T + st_m) * a.dv.max_rank + st_seg * 8;
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kRT) void reduce_expand_kernel(ReduceArgs a)
     // stage the scaled shrink results as bf16
     {
         u32x4 packed = {0u, 0u, 0u, 0u};
-        if (st_live) {
+        if (st_on && st_seg * 8 < st_rank) {
             bf16x8 vb;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
