@@ -9,8 +9,9 @@
 // 43 (eight) bytes per clock from L2-resident data, and ordinary loads reach 56 - 60; a 256 x 256 tile at the full
 // MFMA rate needs 64 KB per 2048 clocks = 32 bytes per clock, so the copy instruction, not the matrix cores, set
 // the pace of the kernel that used it.  Registers also hold the tile in flight, so two LDS stages are enough:
-// tile j is multiplied out of one stage while tile j + 1 (loaded during tile j - 1 and the first K step of tile j)
-// is written into the other and tile j + 2 is on its way into the registers that have just been emptied.
+// tile j is multiplied out of one stage while tile j + 1 (on its way since the first K step of tile j - 1) is written
+// into the other during the first K step, and every register that write empties is refilled at once with its part of
+// tile j + 2, which so has a whole tile time to arrive (refilling in the second K step left three quarters of one).
 //
 // One barrier per tile, in front of the MFMAs of the tile's last K step: every wave has its last fragments of
 // tile j in registers by then (the stage may be overwritten) and has written its share of tile j + 1 (the
@@ -37,6 +38,7 @@ __device__ __forceinline__ void staged_for(F&& f)
 
 constexpr int kSK = 64;        // K extent of one LDS tile (bf16 elements)
 constexpr int kSRow = 128;     // bytes per LDS row
+constexpr bool kLoadBehindStore = true;   // a staging register is refilled right behind the LDS write that empties it
 
 // LDS writes of this wave have landed, then meet the other waves.  No wait for global loads: the tile on its way
 // into registers stays in flight across the barrier.
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     staged_for<NR>([&](auto r) { read_one(0, ring, 0, r.value); });
 
     // One tile.  STORE: tile j + 1 waits in its registers and goes into the other stage during K step 0; LOAD:
-    // tile j + 1 + PG is requested into the same registers during K step 1; NEXT: there is a tile j + 1 to hand
+    // tile j + 1 + PG is requested into the same registers, each right behind the write that empties it; NEXT: there is a tile j + 1 to hand
     // over to.  SET: the register set of tile j + 1.  The instruction order is written out and pinned: behind
     // every MFMA one LDS read of the next K step's fragments and its share of the K step's LDS writes (step 0) or
     // global loads (step 1), so that neither a row of writes that wait for their loads nor a row of reads stands
@@ -174,7 +176,10 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (t < NR) read_one(1, st, 1, t);
             if constexpr (STORE)
-                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { store_one(SET, other, t * NST / NM + q.value); });
+                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) {
+                    store_one(SET, other, t * NST / NM + q.value);
+                    if constexpr (LOAD && kLoadBehindStore) load_one(SET, j + 1 + PG, t * NST / NM + q.value);
+                });
             __builtin_amdgcn_sched_barrier(0);
         });
         staged_for<NM>([&](auto tc) {                           // K step 1
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             mma_one(1, t);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (t < NR) read_one(0, st, 2, t);
-            if constexpr (LOAD)
+            if constexpr (LOAD && !kLoadBehindStore)
                 staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { load_one(SET, j + 1 + PG, t * NST / NM + q.value); });
             __builtin_amdgcn_sched_barrier(0);
         });
