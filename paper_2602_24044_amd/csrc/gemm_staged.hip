@@ -38,7 +38,6 @@ __device__ __forceinline__ void staged_for(F&& f)
 
 constexpr int kSK = 64;        // K extent of one LDS tile (bf16 elements)
 constexpr int kSRow = 128;     // bytes per LDS row
-constexpr bool kLoadBehindStore = true;   // a staging register is refilled right behind the LDS write that empties it
 
 // LDS writes of this wave have landed, then meet the other waves.  No wait for global loads: the tile on its way
 // into registers stays in flight across the barrier.
@@ -161,8 +160,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
     // One tile.  STORE: tile j + 1 waits in its registers and goes into the other stage during K step 0; LOAD:
     // tile j + 1 + PG is requested into the same registers, each right behind the write that empties it; NEXT: there is a tile j + 1 to hand
     // over to.  SET: the register set of tile j + 1.  The instruction order is written out and pinned: behind
-    // every MFMA one LDS read of the next K step's fragments and its share of the K step's LDS writes (step 0) or
-    // global loads (step 1), so that neither a row of writes that wait for their loads nor a row of reads stands
+    // every MFMA one LDS read of the next K step's fragments and, in step 0, its share of the tile's LDS writes and
+    // global loads, so that neither a row of writes that wait for their loads nor a row of reads stands
     // in front of the MFMAs (scheduling barriers: plain compiler fences do not hold MFMAs in place, they are not
     // memory operations).
     auto tile = [&](auto set_c, auto store_c, auto load_c, auto next_c, int j) {
@@ -178,7 +177,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             if constexpr (STORE)
                 staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) {
                     store_one(SET, other, t * NST / NM + q.value);
-                    if constexpr (LOAD && kLoadBehindStore) load_one(SET, j + 1 + PG, t * NST / NM + q.value);
+                    if constexpr (LOAD) load_one(SET, j + 1 + PG, t * NST / NM + q.value);
                 });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -187,8 +186,6 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_staged_kernel(GemmArgs a
             mma_one(1, t);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (t < NR) read_one(0, st, 2, t);
-            if constexpr (LOAD && !kLoadBehindStore)
-                staged_for<(t + 1) * NST / NM - t * NST / NM>([&](auto q) { load_one(SET, j + 1 + PG, t * NST / NM + q.value); });
             __builtin_amdgcn_sched_barrier(0);
         });
         staged_for<NM>([&](auto tc) {                           // K step 2
