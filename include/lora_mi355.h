@@ -170,15 +170,17 @@ lora_status lora_destroy(lora_ctx *ctx);
  * nothing is enqueued and the table is unchanged.  On success the slot metadata update, the
  * id->slot map update and the copies are enqueued on copy_stream, the copies projection after
  * projection (layer after layer when n_layers > 1) with one event each.  Runs travel in launches
- * of a kernel that reads the page-locked host buffers directly, or, when n_layers > 1 and every
- * run of the call is at least 1 MiB, through the copy engine, which keeps its rate while forward
+ * of a kernel that reads the page-locked host buffers directly, or, when every run of the call
+ * is at least 128 KiB, through the copy engine, which keeps its rate while forward
  * kernels occupy the compute units (LORA_TUNE_COPY_ENGINE overrides the choice; a source that is not
  * page-locked, device-visible host memory is always copied with hipMemcpyAsync).  Later
  * lora_bucket / lora_layer_forward calls on other streams wait through those events, each
  * forward only for the copies of its own projection (layer), and the copies themselves wait
- * for forward work already enqueued (a slot is never overwritten while an earlier step may
+ * for forward work of this context already enqueued (a slot is never overwritten while an earlier step may
  * still read it: forward calls of a context are chained across streams, see lora_layer_forward, so the wait for
- * the latest one covers all of them).
+ * the latest one covers all of them; work that other contexts have enqueued on the same stream since is not
+ * waited for once the context has loaded before).  With n_pages > 0 a load may also send away adapters that the
+ * call does not name, to free a run of pages (see lora_config.n_pages).
  * Errors: INVALID_ARG, ID_RANGE, SLOT_RANGE, RANK_EXCEEDS_SMAX, SHAPE (rank not a multiple of
  * 8), SLOTS_EXHAUSTED, HIP. */
 lora_status lora_slots_load(lora_ctx *ctx, int32_t n, lora_adapter_desc *descs,
