@@ -266,6 +266,15 @@ lora_status lora_layer_forward_glu(lora_ctx *ctx, int32_t proj_gate, int32_t pro
                                    const void *d_W_gate, const void *d_W_up, const lora_segments *seg, void *d_out,
                                    void *stream);
 
+/* Whole-model form of lora_layer_forward_glu, as lora_model_forward_group is of lora_layer_forward_group (paper
+ * Sec. 2.2: an adapter targets the same projections in every decoder layer): `layer` (0 .. n_layers - 1) selects
+ * which layer's part of every slot the call reads; lora_layer_forward_glu is this call with layer 0.  Errors: as
+ * lora_layer_forward_glu (the bias rule applies to the projections of that layer), INVALID_ARG also for a layer
+ * out of range. */
+lora_status lora_model_forward_glu(lora_ctx *ctx, int32_t layer, int32_t proj_gate, int32_t proj_up, const void *d_x,
+                                   const void *d_W_gate, const void *d_W_up, const lora_segments *seg, void *d_out,
+                                   void *stream);
+
 /* Bias of a backbone projection (paper Sec. 2.2: the adapter's activations are added to the backbone layer's
  * output, which for a layer with a bias is x W^T + b; Sec. 8.1 evaluates on the Qwen2.5 family, whose q, k, v
  * projections have one).  d_bias: device bf16 [d_out_proj], 16-byte aligned, owned by the caller, read by every

@@ -65,7 +65,7 @@ LORA_CREATE_HOST_ONLY = 1
 EXPORTS = [
     "lora_slab_bytes", "lora_create", "lora_destroy", "lora_slots_load", "lora_bucket", "lora_layer_forward",
     "lora_layer_forward_group",
-    "lora_layer_forward_glu", "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_slot_first_page", "lora_last_launches",
+    "lora_layer_forward_glu", "lora_model_forward_glu", "lora_poll_device_flags", "lora_slot_of", "lora_slot_adapter", "lora_slot_first_page", "lora_last_launches",
     "lora_profile_enable", "lora_profile_collect", "lora_profile_reset", "lora_status_string",
     "lora_last_hip_error", "lora_calibrate_stream", "lora_calibrate_mfma", "lora_layer_forward_static", "lora_static_scratch_bytes", "lora_set_tuning", "lora_set_bias", "lora_model_forward_group", "lora_place_adapters", "lora_priority_sorting",
 ]
@@ -336,6 +336,9 @@ def lora_place_adapters(size: Sequence[int], rate: Sequence[float], n_gpus: int,
 
 _lib.lora_layer_forward_glu.restype = ctypes.c_int
 _lib.lora_layer_forward_glu.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, ctypes.POINTER(lora_segments), _P, _P]
+_lib.lora_model_forward_glu.restype = ctypes.c_int
+_lib.lora_model_forward_glu.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P,
+                                        ctypes.POINTER(lora_segments), _P, _P]
 
 
 def lora_layer_forward_glu(ctx: int, proj_gate: int, proj_up: int, d_x: int, d_W_gate: int, d_W_up: int,
@@ -344,6 +347,14 @@ def lora_layer_forward_glu(ctx: int, proj_gate: int, proj_up: int, d_x: int, d_W
                                      ctypes.byref(seg), _P(d_out), _P(stream or None))
     if st != LORA_OK:
         raise LoraError(st, "lora_layer_forward_glu")
+
+
+def lora_model_forward_glu(ctx: int, layer: int, proj_gate: int, proj_up: int, d_x: int, d_W_gate: int, d_W_up: int,
+                           seg: lora_segments, d_out: int, stream: int = 0) -> None:
+    st = _lib.lora_model_forward_glu(_P(ctx), int(layer), int(proj_gate), int(proj_up), _P(d_x), _P(d_W_gate),
+                                     _P(d_W_up), ctypes.byref(seg), _P(d_out), _P(stream or None))
+    if st != LORA_OK:
+        raise LoraError(st, "lora_model_forward_glu")
 
 
 def lora_poll_device_flags(ctx: int, stream: int = 0) -> Tuple[int, int]:

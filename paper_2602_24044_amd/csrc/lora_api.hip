@@ -1005,7 +1005,7 @@ lora_status forward_impl(lora_ctx* c, int32_t layer, int32_t n, const int32_t* p
     ForwardPlan plan;
     if (const lora_status st = plan_forward(c, T, n, projs, scr.part_elems, scr.vpart_elems, plan, glu); st != LORA_OK)
         return (st == LORA_ERR_OOM && scr.is_static) ? LORA_ERR_SCRATCH_LIMIT : st;
-    const int K = plan.K, Mpad = plan.Mpad, n_max = plan.n_max, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
+    const int K = plan.K, Mpad = plan.Mpad, S = plan.S, n_kc = plan.n_kc, kc_len = plan.kc_len;
     const long n_pad_total = plan.n_pad_total;
     const bool split = plan.split, dyn_shrink = plan.dyn_shrink;
     const int split_variant = plan.split_variant;
@@ -1261,20 +1261,29 @@ lora_status lora_layer_forward_static(lora_ctx* c, int32_t p, const void* d_x, c
 
 size_t lora_static_scratch_bytes(void) { return kStaticPartBytes + kStaticVpartBytes; }
 
-lora_status lora_layer_forward_glu(lora_ctx* c, int32_t proj_gate, int32_t proj_up, const void* d_x, const void* d_W_gate,
-                                   const void* d_W_up, const lora_segments* seg, void* d_out, void* stream_v)
+lora_status lora_model_forward_glu(lora_ctx* c, int32_t layer, int32_t proj_gate, int32_t proj_up, const void* d_x,
+                                   const void* d_W_gate, const void* d_W_up, const lora_segments* seg, void* d_out,
+                                   void* stream_v)
 {
     if (!c) return LORA_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= c->n_layers) return LORA_ERR_INVALID_ARG;
     if (proj_gate < 0 || proj_gate >= c->cfg.n_proj || proj_up < 0 || proj_up >= c->cfg.n_proj || proj_gate == proj_up)
         return LORA_ERR_INVALID_ARG;
     if (c->proj[proj_gate].d_out != c->proj[proj_up].d_out || c->proj[proj_gate].d_in != c->proj[proj_up].d_in)
         return LORA_ERR_SHAPE;
-    if (c->bias[proj_gate] || c->bias[proj_up]) return LORA_ERR_INVALID_ARG;      // the gated MLPs served here have none
+    const size_t flat0 = (size_t)layer * c->cfg.n_proj;
+    if (c->bias[flat0 + proj_gate] || c->bias[flat0 + proj_up]) return LORA_ERR_INVALID_ARG;      // the gated MLPs served here have none
     const int32_t projs[2] = {proj_gate, proj_up};
     const void* xs[2] = {d_x, d_x};
     const void* Ws[2] = {d_W_gate, d_W_up};
     void* outs[2] = {d_out, d_out};
-    return forward_impl(c, 0, 2, projs, xs, Ws, seg, outs, stream_v, slab_scratch(c), true);
+    return forward_impl(c, layer, 2, projs, xs, Ws, seg, outs, stream_v, slab_scratch(c), true);
+}
+
+lora_status lora_layer_forward_glu(lora_ctx* c, int32_t proj_gate, int32_t proj_up, const void* d_x, const void* d_W_gate,
+                                   const void* d_W_up, const lora_segments* seg, void* d_out, void* stream_v)
+{
+    return lora_model_forward_glu(c, 0, proj_gate, proj_up, d_x, d_W_gate, d_W_up, seg, d_out, stream_v);
 }
 
 lora_status lora_layer_forward_group(lora_ctx* c, int32_t n, const int32_t* projs, const void* const* d_x,

@@ -290,6 +290,17 @@ class ModelSession:
                                        [self.W[l][p].data_ptr() for p in g], self.seg,
                                        [self.out[l][p].data_ptr() for p in g], s)
 
+    def forward_glu(self, l: int, p_gate: int, p_up: int, out: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        """silu(gate) * up of layer l's two projections on the input of p_gate (lora_model_forward_glu)."""
+        w = self.layers[l]
+        if out is None:
+            out = torch.empty((w.T, w.proj[p_gate][1]), dtype=torch.bfloat16, device=self.device)
+        s = (stream or torch.cuda.current_stream()).cuda_stream
+        B.lora_model_forward_glu(self.ctx, l, p_gate, p_up, self.x[l][p_gate].data_ptr(), self.W[l][p_gate].data_ptr(),
+                                 self.W[l][p_up].data_ptr(), self.seg, out.data_ptr(), s)
+        return out
+
     def step(self, stream: Optional[torch.cuda.Stream] = None) -> None:
         """One step of the whole model: one segment map, then every layer's projections."""
         self.bucket(stream)

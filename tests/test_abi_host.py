@@ -165,6 +165,31 @@ def test_group_argument_errors():
         B.lora_destroy(ctx)
 
 
+def test_gated_pair_argument_errors():
+    cfg = B.make_config(((64, 128), (64, 128), (64, 96), (128, 64)), 3, 32, 16, 63, flags=B.LORA_CREATE_HOST_ONLY, n_layers=2)
+    ctx = B.lora_create(cfg)
+    seg = B.lora_segments()
+    try:
+        def status(layer, pg, pu):
+            with pytest.raises(B.LoraError) as e:
+                B.lora_model_forward_glu(ctx, layer, pg, pu, 16, 16, 16, seg, 16)
+            return e.value.status
+        assert status(2, 0, 1) == B.LORA_ERR_INVALID_ARG              # layers 0 and 1 only
+        assert status(-1, 0, 1) == B.LORA_ERR_INVALID_ARG
+        assert status(0, 0, 0) == B.LORA_ERR_INVALID_ARG              # two different projections
+        assert status(0, 0, 4) == B.LORA_ERR_INVALID_ARG              # in range
+        assert status(1, 0, 2) == B.LORA_ERR_SHAPE                    # d_out 128 vs 96
+        assert status(1, 0, 3) == B.LORA_ERR_SHAPE                    # d_in 64 vs 128
+        assert status(1, 0, 1) == B.LORA_ERR_INVALID_ARG              # no segment map yet
+        B.lora_set_bias(ctx, 1, 256, layer=1)                         # a bias on the second projection of layer 1 only
+        with pytest.raises(B.LoraError) as e:
+            B.lora_layer_forward_glu(ctx, 0, 1, 16, 16, 16, seg, 16)  # layer 0: past the bias rule, stopped by the missing map
+        assert e.value.status == B.LORA_ERR_INVALID_ARG
+        assert status(1, 0, 1) == B.LORA_ERR_INVALID_ARG
+    finally:
+        B.lora_destroy(ctx)
+
+
 def test_bias_argument_errors():
     ctx = _host_ctx(proj=((64, 64), (64, 128)))
     try:

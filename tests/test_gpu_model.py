@@ -105,3 +105,28 @@ def test_many_layers():
         assert st == B.LORA_OK and word == 0
     finally:
         ms.close()
+
+
+def test_gated_mlp_of_every_layer_reads_that_layers_part_of_the_slots():
+    # silu(gate) * up of each layer in one call per layer (lora_model_forward_glu): layer l's W, x and the layer-l
+    # matrices of the adapters; a wrong layer offset would pick another layer's A and B
+    layers = wl.model_layers(wl.config2(shrink=8, n_tokens=300), 3)
+    g, u = layers[0].proj_names.index("gate"), layers[0].proj_names.index("up")
+    announce(f"model glu {layers[0].name} layers={len(layers)} T={layers[0].T}")
+    ms = ModelSession(layers)
+    try:
+        ms.load(layers[0].resident)
+        ms.bucket()
+        for l, lw in enumerate(layers):
+            out = ms.forward_glu(l, g, u)
+            torch.cuda.synchronize()
+            h_ref = oracle.gated(lw.x[g], lw.W[g], lw.W[u], lw.token_ids, oracle.adapters_of(lw, g), oracle.adapters_of(lw, u))
+            e = rel_err(bf16_tensor_to_bits(out), h_ref)
+            announce(f"  layer {l} launches={B.lora_last_launches(ms.ctx)} rel_err={e:.3e}")
+            assert e <= TOL, (l, e)
+        with pytest.raises(B.LoraError) as err:
+            ms.forward_glu(len(layers), g, u)
+        assert err.value.status == B.LORA_ERR_INVALID_ARG
+        assert B.lora_poll_device_flags(ms.ctx) == (B.LORA_OK, 0)
+    finally:
+        ms.close()
