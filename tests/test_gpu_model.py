@@ -125,7 +125,8 @@ def test_gated_mlp_of_every_layer_reads_that_layers_part_of_the_slots():
             announce(f"  layer {l} launches={B.lora_last_launches(ms.ctx)} rel_err={e:.3e}")
             assert e <= TOL, (l, e)
         with pytest.raises(B.LoraError) as err:
-            ms.forward_glu(len(layers), g, u)
+            B.lora_model_forward_glu(ms.ctx, len(layers), g, u, ms.x[0][g].data_ptr(), ms.W[0][g].data_ptr(),
+                                     ms.W[0][u].data_ptr(), ms.seg, out.data_ptr())
         assert err.value.status == B.LORA_ERR_INVALID_ARG
         assert B.lora_poll_device_flags(ms.ctx) == (B.LORA_OK, 0)
     finally:
