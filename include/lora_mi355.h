@@ -310,7 +310,8 @@ enum {
     LORA_TUNE_SHRINK_WAIT_TEST = 4 /* test aid, value n > 0: in such a launch the tile workgroups expect one report more
                                       than will come and give up after n polls, so that the expired-wait handling
                                       (LORA_FLAG_INTERNAL, counter reset, fallback) can be exercised from the host
-                                      with every kernel ending normally; the outputs of that launch are still right */
+                                      with every kernel ending normally; the outputs of that launch are undefined, as after any
+                                      expired wait (the tile workgroups may have read shrink results that were not there yet) */
 };
 /* Values of LORA_TUNE_INLINE_SHRINK. */
 enum {
